@@ -1,0 +1,52 @@
+"""Error measures the parity tests gate on -- TEST INFRASTRUCTURE ONLY.
+
+The accuracy targets are "max relative error 1e-5 (fp32) / 2e-2 (bf16, fp16)
+against the fp64 result".  A strictly element-wise relative error is not a
+usable gate: an output that is small only because large terms cancelled has an
+absolute error set by the size of the terms, not of the result.  The gate used
+here divides by max(|ref_ij|, rms(ref)) per operator; the strict element-wise,
+norm-wise and backward (relative to sum_k |a||b|) figures are returned beside
+it.  `order_free_bound` is the rigorous ceiling any fp32-accumulate summation
+order must sit under.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+TOL = {"f32": 1e-5, "bf16": 2e-2, "f16": 2e-2}
+
+# unit roundoff of the output format (round to nearest)
+_U_OUT = {"f32": 2.0 ** -24, "bf16": 2.0 ** -9, "f16": 2.0 ** -11}
+
+
+def errors(c, ref, mag=None):
+    c = np.asarray(c, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    diff = np.abs(c - ref)
+    rms = float(np.sqrt(np.mean(ref * ref))) if ref.size else 0.0
+    floor = np.maximum(np.abs(ref), rms)
+    out = {
+        "gate": float(np.max(diff / np.where(floor > 0, floor, 1.0))) if ref.size else 0.0,
+        "normwise": float(np.max(diff) / max(float(np.max(np.abs(ref))), 1e-300)) if ref.size else 0.0,
+        "max_abs": float(np.max(diff)) if ref.size else 0.0,
+    }
+    with np.errstate(divide="ignore", invalid="ignore"):
+        strict = np.where(np.abs(ref) > 0, diff / np.abs(ref), 0.0)
+    out["strict"] = float(np.max(strict)) if ref.size else 0.0
+    if mag is not None:
+        mag = np.asarray(mag, dtype=np.float64)
+        with np.errstate(divide="ignore", invalid="ignore"):
+            bw = np.where(mag > 0, diff / mag, 0.0)
+        out["backward"] = float(np.max(bw)) if ref.size else 0.0
+    return out
+
+
+def order_free_bound(ref, mag, K: int, dtype: str):
+    """|c - ref| <= gamma*mag + u_out*(|ref| + gamma*mag) for fp32 accumulation of K
+    exactly representable products in any order, followed by one rounding to the
+    output format.  gamma = (K+2)*2^-24 (first-order, slightly inflated)."""
+    gamma = (K + 2) * 2.0 ** -24
+    ref = np.abs(np.asarray(ref, dtype=np.float64))
+    mag = np.asarray(mag, dtype=np.float64)
+    acc = gamma * mag
+    return acc + _U_OUT[dtype] * (ref + acc) * 1.0000001 + 1e-300

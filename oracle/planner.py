@@ -1,0 +1,176 @@
+"""Reference tile planner and coverage checker -- TEST INFRASTRUCTURE ONLY.
+
+The paper's runtime "repacks multiple small kernels into a large execution
+block" (Section 5.3) and "prioritizes streams with tighter latency budgets"
+(Section 5, item (a)); it gives no packing algorithm, table layout or policy.
+This module fixes this build's reading as a pure integer function of the
+operator list and a few parameters, in plain Python, so that the C++ planner
+behind the C ABI can be compared with it byte for byte:
+
+  1. canonical GEMM view of every operator (a convolution is the GEMM that
+     backs it: rows = output pixels, columns = output channels, reduction =
+     filter taps x input channels);
+  2. tile class and tile extents per operator;
+  3. operator order: earliest deadline first, ties (and "no deadline") by
+     submission index;
+  4. the flat table: operators in that order, row blocks outer, column blocks
+     inner, reduction slices innermost; one fixed-size record per tile.
+
+It shares no code with the product's planner.
+
+Pins (tests/test_oracle_planner.py): tiny cases enumerated by hand, brute-force
+coverage (every output element owned by exactly one rectangle, reduction slices
+partition [0,Kg)), table length == sum of tile counts, order == Python's sorted.
+"""
+from __future__ import annotations
+
+import math
+import struct
+from dataclasses import dataclass
+from typing import List, Sequence
+
+import numpy as np
+
+ELEM_SIZE = {"f32": 4, "bf16": 2, "f16": 2}
+
+RECORD = struct.Struct("<IHBBIIHHIII")  # 32 bytes
+assert RECORD.size == 32
+
+# tile classes
+#   0..5  "skinny": all rows of a small-M operator against a block of 32*G weight
+#         rows; the four waves of a workgroup split the reduction wk ways.
+#         id = 3*(rm-1) + {1:0, 2:1, 4:2}[wk],  rm = 1 (Mg<=16) or 2 (Mg<=32)
+#   6     64 x 128 output tile staged through LDS
+#   7     128 x 128 output tile staged through LDS
+CLS_TILE_64x128 = 6
+CLS_TILE_128x128 = 7
+_WK_CODE = {1: 0, 2: 1, 4: 2}
+
+
+@dataclass
+class Params:
+    edf: int = 1
+    skinny_max_m: int = 32          # <= 32
+    tile_bytes_max: int = 256 * 1024
+    tile_bytes_min: int = 32 * 1024
+    balance_div: int = 2048
+    max_groups: int = 256
+
+
+def canonical(p):
+    """(Mg, Ng, Kg) of an operator description with .op/.M/.N/.K or conv fields."""
+    if p.op == "gemm":
+        return p.M, p.N, p.K
+    ho = p.H + 2 * p.pad_h - p.R + 1
+    wo = p.W + 2 * p.pad_w - p.S + 1
+    return p.Nb * ho * wo, p.Cout, p.R * p.S * p.Cin
+
+
+def _deadline_key(d):
+    if d is None or not (d > 0.0) or math.isinf(d):   # <=0, NaN, inf: no deadline
+        return math.inf
+    return float(d)
+
+
+def order(problems: Sequence, edf: int = 1) -> List[int]:
+    n = len(problems)
+    if not edf:
+        return list(range(n))
+    return sorted(range(n), key=lambda i: (_deadline_key(problems[i].deadline_ms), i))
+
+
+def target_tile_bytes(problems: Sequence, prm: Params) -> int:
+    total = 0
+    for p in problems:
+        _, ng, kg = canonical(p)
+        total += ng * kg * ELEM_SIZE[p.dtype]
+    return max(prm.tile_bytes_min, min(prm.tile_bytes_max, total // prm.balance_div))
+
+
+def tiling(p, T: int, prm: Params):
+    """(cls, BM, BN) for one operator given the target bytes per skinny tile."""
+    mg, ng, kg = canonical(p)
+    es = ELEM_SIZE[p.dtype]
+    if mg <= prm.skinny_max_m:
+        rm = 1 if mg <= 16 else 2
+        gb = 32 * kg * es
+        if gb >= T:
+            wk, G = 4, 1
+        elif 2 * gb >= T:
+            wk, G = 2, 2
+        else:
+            wk, G = 1, min(prm.max_groups, 4 * max(1, T // (4 * gb)))
+        return 3 * (rm - 1) + _WK_CODE[wk], mg, 32 * G
+    if mg <= 64:
+        return CLS_TILE_64x128, 64, 128
+    return CLS_TILE_128x128, 128, 128
+
+
+def plan(problems: Sequence, prm: Params | None = None):
+    """Returns (table_bytes, order, first_tile[n], tile_count[n]) -- first/count by submission index."""
+    prm = prm or Params()
+    n = len(problems)
+    T = target_tile_bytes(problems, prm) if n else prm.tile_bytes_min
+    ordr = order(problems, prm.edf)
+    first = [0] * n
+    count = [0] * n
+    recs = []
+    out_id = 0
+    for i in ordr:
+        p = problems[i]
+        mg, ng, kg = canonical(p)
+        cls, BM, BN = tiling(p, T, prm)
+        first[i] = len(recs)
+        for m0 in range(0, mg, BM):
+            for n0 in range(0, ng, BN):
+                S = 1
+                for ks in range(S):
+                    recs.append(RECORD.pack(i, cls, ks, S, m0, n0, min(BM, mg - m0), min(BN, ng - n0),
+                                            0, kg, out_id))
+                out_id += 1
+        count[i] = len(recs) - first[i]
+    return b"".join(recs), ordr, first, count
+
+
+def decode(table: bytes):
+    names = ("problem", "cls", "ks_idx", "S", "m0", "n0", "m_len", "n_len", "k0", "k_len", "out_tile_id")
+    return [dict(zip(names, RECORD.unpack_from(table, off))) for off in range(0, len(table), RECORD.size)]
+
+
+def check_coverage(problems: Sequence, table: bytes) -> None:
+    """Brute force: every output element of every operator is owned by exactly one
+    output rectangle, and the reduction slices of a rectangle partition [0, Kg).
+    Raises AssertionError with the first violation."""
+    tiles = decode(table)
+    dims = [canonical(p) for p in problems]
+    own = [np.zeros((mg, ng), dtype=np.int32) for (mg, ng, _) in dims]
+    slices = {}
+    for t in tiles:
+        i = t["problem"]
+        assert 0 <= i < len(problems), f"tile names operator {i}"
+        mg, ng, kg = dims[i]
+        assert t["m_len"] >= 1 and t["n_len"] >= 1 and t["k_len"] >= 1
+        assert t["m0"] + t["m_len"] <= mg and t["n0"] + t["n_len"] <= ng, f"tile leaves operator {i}"
+        assert t["k0"] + t["k_len"] <= kg
+        key = (i, t["m0"], t["n0"], t["m_len"], t["n_len"], t["out_tile_id"])
+        if key not in slices:
+            own[i][t["m0"]:t["m0"] + t["m_len"], t["n0"]:t["n0"] + t["n_len"]] += 1
+            slices[key] = []
+        slices[key].append((t["ks_idx"], t["S"], t["k0"], t["k_len"]))
+    for i, o in enumerate(own):
+        assert o.size == 0 or (o.min() == 1 and o.max() == 1), \
+            f"operator {i}: some output element is owned {o.min()}..{o.max()} times"
+    ids = set()
+    for key, sl in slices.items():
+        assert key[5] not in ids, "two output rectangles share an out_tile_id"
+        ids.add(key[5])
+        kg = dims[key[0]][2]
+        sl.sort()
+        S = sl[0][1]
+        assert len(sl) == S and [s[0] for s in sl] == list(range(S)), f"slice indices of {key}"
+        pos = 0
+        for (_, s, k0, kl) in sl:
+            assert s == S and k0 == pos, f"reduction slices of {key} do not tile [0,{kg})"
+            pos += kl
+        assert pos == kg, f"reduction slices of {key} stop at {pos} of {kg}"
+    assert ids == set(range(len(ids))), "out_tile_id is not a running index"

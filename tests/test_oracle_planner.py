@@ -1,0 +1,143 @@
+"""Pins for the reference tile planner and its coverage checker (CPU only)."""
+import math
+import struct
+from types import SimpleNamespace as NS
+
+import pytest
+
+import workloads
+from oracle import planner as P
+
+
+def gemm(m, n, k, dtype="bf16", deadline=math.inf):
+    return NS(op="gemm", dtype=dtype, M=m, N=n, K=k, deadline_ms=deadline)
+
+
+def conv(hw, cin, cout, r, dtype="bf16", deadline=math.inf):
+    return NS(op="conv", dtype=dtype, Nb=1, H=hw, W=hw, Cin=cin, Cout=cout, R=r, S=r,
+              pad_h=(r - 1) // 2, pad_w=(r - 1) // 2, deadline_ms=deadline)
+
+
+def test_canonical_view_of_conv_and_gemm():
+    assert P.canonical(gemm(3, 5, 7)) == (3, 5, 7)
+    assert P.canonical(conv(56, 64, 256, 1)) == (3136, 256, 64)
+    assert P.canonical(conv(7, 512, 512, 3)) == (49, 512, 4608)
+    c = NS(op="conv", dtype="bf16", Nb=2, H=8, W=6, Cin=4, Cout=3, R=3, S=3, pad_h=0, pad_w=1, deadline_ms=0)
+    assert P.canonical(c) == (2 * 6 * 6, 3, 36)
+
+
+def test_hand_enumerated_skinny_plan():
+    # M=1, N=70, K=3, fp32: one 32-row weight group is 32*3*4 = 384 B, far below the 32 KiB
+    # floor => wk=1, G = 4*(32768 // (4*384)) = 84 groups, capped by nothing: BN = 2688 >= N.
+    # One tile covering all 70 columns.
+    table, order, first, count = P.plan([gemm(1, 70, 3, "f32")])
+    t = P.decode(table)
+    assert len(t) == 1 and order == [0] and first == [0] and count == [1]
+    assert t[0] == dict(problem=0, cls=0, ks_idx=0, S=1, m0=0, n0=0, m_len=1, n_len=70, k0=0, k_len=3,
+                        out_tile_id=0)
+    # bytes, field by field, little endian
+    assert table == struct.pack("<IHBBIIHHIII", 0, 0, 0, 1, 0, 0, 1, 70, 0, 3, 0)
+
+
+def test_hand_enumerated_split_modes():
+    prm = P.Params(tile_bytes_min=32768, tile_bytes_max=32768)   # T fixed at 32 KiB
+    # K=1024 bf16: group = 32*1024*2 = 64 KiB >= T  => wk=4, one group (32 rows) per tile
+    t = P.decode(P.plan([gemm(4, 100, 1024)], prm)[0])
+    assert [x["cls"] for x in t] == [2, 2, 2, 2]
+    assert [(x["n0"], x["n_len"]) for x in t] == [(0, 32), (32, 32), (64, 32), (96, 4)]
+    # K=256 bf16: group = 16 KiB, 2*16 >= 32 => wk=2, two groups per tile; Mg=20 => rm=2 => cls 3+1
+    t = P.decode(P.plan([gemm(20, 100, 256)], prm)[0])
+    assert [x["cls"] for x in t] == [4, 4]
+    assert [(x["n0"], x["n_len"], x["m_len"]) for x in t] == [(0, 64, 20), (64, 36, 20)]
+    # K=64 bf16: group = 4 KiB => wk=1, G = 4*(32768//(16384)) = 8 groups = 256 rows
+    t = P.decode(P.plan([gemm(16, 600, 64)], prm)[0])
+    assert [x["cls"] for x in t] == [0, 0, 0]
+    assert [(x["n0"], x["n_len"]) for x in t] == [(0, 256), (256, 256), (512, 88)]
+
+
+def test_hand_enumerated_lds_tiles():
+    # Mg = 49 (7x7 conv) -> 64x128 tiles; Mg = 196 -> 128x128 tiles, rows outer, columns inner
+    t = P.decode(P.plan([conv(7, 64, 256, 1)])[0])
+    assert [(x["cls"], x["m0"], x["n0"], x["m_len"], x["n_len"]) for x in t] == \
+        [(6, 0, 0, 49, 128), (6, 0, 128, 49, 128)]
+    t = P.decode(P.plan([conv(14, 64, 192 + 8, 3)])[0])
+    assert [(x["cls"], x["m0"], x["n0"], x["m_len"], x["n_len"], x["k_len"]) for x in t] == \
+        [(7, 0, 0, 128, 128, 576), (7, 0, 128, 128, 72, 576),
+         (7, 128, 0, 68, 128, 576), (7, 128, 128, 68, 72, 576)]
+    assert [x["out_tile_id"] for x in t] == [0, 1, 2, 3]
+
+
+def test_edf_order_is_stable_sort_by_deadline_then_index():
+    ds = [3.0, math.inf, 1.0, 3.0, 0.0, -2.0, 1.0, float("nan"), 0.75]
+    probs = [gemm(1, 32, 64, deadline=d) for d in ds]
+    want = [8, 2, 6, 0, 3, 1, 4, 5, 7]      # by hand: 0.75, 1.0(2), 1.0(6), 3.0(0), 3.0(3), then no-deadline by index
+    assert P.order(probs, 1) == want
+    assert P.order(probs, 0) == list(range(len(ds)))
+    table, order, first, count = P.plan(probs)
+    assert order == want
+    assert [x["problem"] for x in P.decode(table)] == want
+    assert [first[i] for i in want] == list(range(len(ds)))
+    # no deadlines at all => submission order
+    probs = [gemm(1, 32, 64) for _ in range(5)]
+    assert P.order(probs, 1) == [0, 1, 2, 3, 4]
+
+
+def test_target_bytes_rule():
+    prm = P.Params()
+    small = [gemm(1, 256, 256, "f32")]
+    assert P.target_tile_bytes(small, prm) == prm.tile_bytes_min
+    big = [gemm(1, 8192, 8192)] * 8      # 8 x 128 MiB of weights / 2048 = 512 KiB -> clamped
+    assert P.target_tile_bytes(big, prm) == prm.tile_bytes_max
+    mid = [gemm(1, 4096, 4096)] * 4      # 128 MiB / 2048 = 64 KiB
+    assert P.target_tile_bytes(mid, prm) == 65536
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
+def test_coverage_on_every_config(idx):
+    probs = workloads.config(idx, seed=0)
+    table, order, first, count = P.plan(probs)
+    assert len(table) == 32 * sum(count)
+    P.check_coverage(probs, table)
+    tiles = P.decode(table)
+    # tiles of one operator are contiguous and in EDF order
+    seen = []
+    for t in tiles:
+        if not seen or seen[-1] != t["problem"]:
+            seen.append(t["problem"])
+    assert seen == order == sorted(range(len(probs)), key=lambda i: (probs[i].deadline_ms, i))
+    for i in range(len(probs)):
+        assert all(t["problem"] == i for t in tiles[first[i]:first[i] + count[i]])
+
+
+def test_coverage_on_ragged_shapes():
+    probs = [gemm(1, 5, 3, "f32"), gemm(17, 33, 129), gemm(33, 130, 70, "f16"), gemm(65, 129, 8),
+             gemm(200, 300, 100, "f32"), conv(5, 3, 7, 3), conv(9, 8, 130, 1), conv(13, 16, 40, 3)]
+    table = P.plan(probs)[0]
+    P.check_coverage(probs, table)
+
+
+def _mutate(table, idx, **kw):
+    tiles = P.decode(table)
+    tiles[idx].update(kw)
+    names = ("problem", "cls", "ks_idx", "S", "m0", "n0", "m_len", "n_len", "k0", "k_len", "out_tile_id")
+    return b"".join(P.RECORD.pack(*[t[n] for n in names]) for t in tiles)
+
+
+def test_coverage_checker_catches_planted_mistakes():
+    probs = [gemm(100, 300, 128), gemm(4, 256, 4096)]
+    table = P.plan(probs)[0]
+    P.check_coverage(probs, table)
+    n = len(table) // 32
+    assert n >= 4
+    with pytest.raises(AssertionError):
+        P.check_coverage(probs, table[:-32])                       # a tile dropped
+    with pytest.raises(AssertionError):
+        P.check_coverage(probs, table + table[-32:])               # a tile doubled (same id)
+    with pytest.raises(AssertionError):
+        P.check_coverage(probs, _mutate(table, 1, n0=64))          # overlapping rectangle
+    with pytest.raises(AssertionError):
+        P.check_coverage(probs, _mutate(table, 0, k_len=64))       # reduction cut short
+    with pytest.raises(AssertionError):
+        P.check_coverage(probs, _mutate(table, 0, n_len=129))      # rectangle too wide
+    with pytest.raises(AssertionError):
+        P.check_coverage(probs, _mutate(table, 2, out_tile_id=0))  # id collision

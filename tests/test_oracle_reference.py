@@ -1,0 +1,167 @@
+"""Pins for the fp64 GEMM / convolution oracle (CPU only).
+
+Each pin is something other than the oracle's own formula: hand-worked values
+(tests/golden/hand_examples.json), closed forms, numpy's fp64 matmul, and
+identities between the two operators.  A dropped term, a flipped filter, a
+transposed operand, a wrong padding offset or a wrong k ordering fails at
+least one of them.
+"""
+import json
+import os
+
+import numpy as np
+import pytest
+
+from oracle import reference as R
+
+
+@pytest.fixture(scope="module")
+def hand(golden_dir):
+    with open(os.path.join(golden_dir, "hand_examples.json")) as f:
+        return json.load(f)
+
+
+def _bnk(b_kn):
+    return np.ascontiguousarray(np.array(b_kn, dtype=np.float32).T)
+
+
+def test_gemm_hand_examples(hand):
+    for case in hand["gemm"]:
+        A = np.array(case["A"], dtype=np.float32)
+        C = R.gemm(A, _bnk(case["B_kn"]))
+        assert np.array_equal(C, np.array(case["C"], dtype=np.float64)), case["name"]
+        assert np.array_equal(R.gemm_py(A.tolist(), _bnk(case["B_kn"]).tolist()), C)
+
+
+def test_conv_hand_examples(hand):
+    for case in hand["conv"]:
+        X = np.array(case["X_hw"], dtype=np.float32)[None, :, :, None]
+        W = np.array(case["W_rs"], dtype=np.float32)[None, :, :, None]
+        Y = R.conv2d_nhwc(X, W, case["pad"], case["pad"])
+        want = np.array(case["Y_hw"], dtype=np.float64)[None, :, :, None]
+        assert np.array_equal(Y, want), case["name"]
+        assert np.array_equal(R.conv2d_nhwc_py(X, W, case["pad"], case["pad"]), want)
+
+
+def test_conv1x1_hand_example(hand):
+    c = hand["conv1x1"]
+    X = np.array(c["X_nhwc"], dtype=np.float32)
+    W = np.array(c["W_oc_ic"], dtype=np.float32)[:, None, None, :]
+    Y = R.conv2d_nhwc(X, W, 0, 0)
+    assert np.array_equal(Y.reshape(4, 2), np.array(c["Y_rows"], dtype=np.float64))
+
+
+def test_gemm_closed_forms():
+    M, N, K = 7, 9, 33
+    # rank one: A[m,k] = m+1, B[k,n] = n+1  =>  C = K (m+1)(n+1)
+    A = np.repeat(np.arange(1, M + 1, dtype=np.float32)[:, None], K, axis=1)
+    B = np.repeat(np.arange(1, N + 1, dtype=np.float32)[:, None], K, axis=1)   # [N,K]
+    C = R.gemm(A, B)
+    want = K * np.outer(np.arange(1, M + 1), np.arange(1, N + 1)).astype(np.float64)
+    assert np.array_equal(C, want)
+    # identity weight => C = A ; unit-vector activation => C = a row of the K x N operand
+    g = np.random.default_rng(1)
+    A = g.standard_normal((5, 16)).astype(np.float32)
+    assert np.array_equal(R.gemm(A, np.eye(16, dtype=np.float32)), A.astype(np.float64))
+    Bkn = g.standard_normal((16, 11)).astype(np.float32)
+    e = np.zeros((1, 16), dtype=np.float32)
+    e[0, 3] = 1
+    assert np.array_equal(R.gemm(e, np.ascontiguousarray(Bkn.T))[0], Bkn[3].astype(np.float64))
+
+
+def test_gemm_k_weighted_sum_distinguishes_k_alignment():
+    # A[m,k] = 10^k digits, B[n,k] = k+1: a shifted or reversed k pairing changes the value
+    A = np.array([[1.0, 10.0, 100.0, 1000.0]], dtype=np.float32)
+    B = np.array([[1.0, 2.0, 3.0, 4.0], [4.0, 3.0, 2.0, 1.0]], dtype=np.float32)
+    assert R.gemm(A, B).tolist() == [[4321.0, 1234.0]]
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 1), (3, 5, 7), (17, 33, 129), (64, 48, 300)])
+def test_gemm_against_numpy_matmul(shape):
+    M, N, K = shape
+    g = np.random.default_rng(sum(shape))
+    A = g.standard_normal((M, K)).astype(np.float32)
+    B = g.standard_normal((N, K)).astype(np.float32)
+    C, S = R.gemm(A, B, want_mag=True)
+    want = A.astype(np.float64) @ B.astype(np.float64).T
+    wmag = np.abs(A.astype(np.float64)) @ np.abs(B.astype(np.float64)).T
+    assert np.max(np.abs(C - want)) <= 1e-12 * np.max(wmag)
+    assert np.max(np.abs(S - wmag)) <= 1e-12 * np.max(wmag)
+    # the single-element evaluator agrees with the full loop
+    s, mag = R.gemm_at(A[M - 1], B[N // 2])
+    assert abs(s - C[M - 1, N // 2]) <= 1e-12 * mag and abs(mag - S[M - 1, N // 2]) <= 1e-12 * mag
+
+
+def test_gemm_accumulates_in_fp64_not_fp32():
+    # 2^24 + 1 is not an fp32 number; an fp32 accumulator would lose the final +1
+    K = 3
+    A = np.array([[4096.0, 1.0, -4096.0]], dtype=np.float32)
+    B = np.array([[4096.0, 1.0, 4096.0]], dtype=np.float32)
+    assert R.gemm(A, B)[0, 0] == 1.0
+    A = np.array([[4096.0, 1.0]], dtype=np.float32)
+    B = np.array([[4096.0, 1.0]], dtype=np.float32)
+    assert R.gemm(A, B)[0, 0] == 16777217.0
+
+
+def test_conv1x1_is_gemm():
+    g = np.random.default_rng(2)
+    X = g.standard_normal((2, 5, 4, 6)).astype(np.float32)
+    W = g.standard_normal((7, 1, 1, 6)).astype(np.float32)
+    Y = R.conv2d_nhwc(X, W, 0, 0)
+    C = R.gemm(X.reshape(-1, 6), W.reshape(7, 6))
+    assert np.array_equal(Y.reshape(-1, 7), C)
+
+
+@pytest.mark.parametrize("cfg", [
+    dict(Nb=1, H=5, W=5, Cin=3, Cout=4, R=3, S=3, ph=1, pw=1),
+    dict(Nb=2, H=4, W=6, Cin=2, Cout=3, R=3, S=3, ph=0, pw=0),
+    dict(Nb=1, H=6, W=3, Cin=5, Cout=2, R=3, S=1, ph=1, pw=0),
+    dict(Nb=1, H=4, W=4, Cin=1, Cout=1, R=1, S=3, ph=0, pw=2),
+])
+def test_direct_conv_equals_patch_matrix_gemm(cfg):
+    g = np.random.default_rng(3)
+    X = g.standard_normal((cfg["Nb"], cfg["H"], cfg["W"], cfg["Cin"])).astype(np.float32)
+    W = g.standard_normal((cfg["Cout"], cfg["R"], cfg["S"], cfg["Cin"])).astype(np.float32)
+    Y, Sm = R.conv2d_nhwc(X, W, cfg["ph"], cfg["pw"], want_mag=True)
+    P = R.patch_matrix(X, cfg["R"], cfg["S"], cfg["ph"], cfg["pw"])
+    want = P.astype(np.float64) @ W.reshape(cfg["Cout"], -1).astype(np.float64).T
+    assert Y.reshape(-1, cfg["Cout"]).shape == want.shape
+    assert np.max(np.abs(Y.reshape(-1, cfg["Cout"]) - want)) <= 1e-12 * max(1.0, np.max(np.abs(want)))
+    assert np.allclose(Y, R.conv2d_nhwc_py(X, W, cfg["ph"], cfg["pw"]), rtol=0, atol=1e-12)
+    # single-element evaluator
+    b, ho, wo, co = cfg["Nb"] - 1, Y.shape[1] - 1, 0, cfg["Cout"] - 1
+    s, mag = R.conv2d_at(X, W[co], b, ho, wo, cfg["ph"], cfg["pw"])
+    assert abs(s - Y[b, ho, wo, co]) <= 1e-12 * max(mag, 1e-30)
+    assert abs(mag - Sm[b, ho, wo, co]) <= 1e-12 * max(mag, 1e-30)
+
+
+def test_conv_delta_filter_is_identity_and_shift():
+    g = np.random.default_rng(4)
+    X = g.standard_normal((1, 6, 5, 3)).astype(np.float32)
+    # centre tap: Y = X (per channel)
+    W = np.zeros((3, 3, 3, 3), dtype=np.float32)
+    for c in range(3):
+        W[c, 1, 1, c] = 1
+    assert np.array_equal(R.conv2d_nhwc(X, W, 1, 1), X.astype(np.float64))
+    # tap (r=0,s=1) with pad 1 reads the pixel one row above: Y[h] = X[h-1], first row zero
+    W = np.zeros((3, 3, 3, 3), dtype=np.float32)
+    for c in range(3):
+        W[c, 0, 1, c] = 1
+    Y = R.conv2d_nhwc(X, W, 1, 1)
+    assert np.array_equal(Y[:, 1:], X[:, :-1].astype(np.float64)) and not Y[:, 0].any()
+    # tap (r=1,s=2) reads the pixel to the right: Y[w] = X[w+1], last column zero
+    W = np.zeros((3, 3, 3, 3), dtype=np.float32)
+    for c in range(3):
+        W[c, 1, 2, c] = 1
+    Y = R.conv2d_nhwc(X, W, 1, 1)
+    assert np.array_equal(Y[:, :, :-1], X[:, :, 1:].astype(np.float64)) and not Y[:, :, -1].any()
+
+
+def test_conv_output_shape_rule():
+    X = np.ones((1, 7, 9, 2), dtype=np.float32)
+    W = np.ones((1, 3, 3, 2), dtype=np.float32)
+    assert R.conv2d_nhwc(X, W, 1, 1).shape == (1, 7, 9, 1)
+    assert R.conv2d_nhwc(X, W, 0, 0).shape == (1, 5, 7, 1)
+    Y = R.conv2d_nhwc(X, W, 1, 1)
+    # all-ones: each output counts the taps inside the image times Cin
+    assert Y[0, 0, 0, 0] == 8 and Y[0, 0, 4, 0] == 12 and Y[0, 3, 4, 0] == 18

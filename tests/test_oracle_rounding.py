@@ -1,0 +1,66 @@
+"""Pins for the storage-type rounding helpers (CPU only)."""
+import numpy as np
+
+from oracle import rounding as Q
+
+
+def test_bf16_all_patterns_round_trip():
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    vals = Q.bf16_bits_to_f32(bits)
+    back = Q.f32_to_bf16_bits(vals)
+    nan = np.isnan(vals)
+    assert np.array_equal(back[~nan], bits[~nan])
+    assert np.all(np.isnan(Q.bf16_bits_to_f32(back[nan])))
+
+
+def test_bf16_ties_to_even_and_neighbours():
+    # 1.0 = 0x3F80; bf16 spacing at 1.0 is 2^-7
+    def f(u):
+        return np.array([u], dtype=np.uint32).view(np.float32)
+    # exact midpoint between 0x3F80 (even) and 0x3F81 -> 0x3F80
+    assert Q.f32_to_bf16_bits(f(0x3F808000))[0] == 0x3F80
+    # exact midpoint between 0x3F81 (odd) and 0x3F82 -> 0x3F82
+    assert Q.f32_to_bf16_bits(f(0x3F818000))[0] == 0x3F82
+    # just above / below a midpoint
+    assert Q.f32_to_bf16_bits(f(0x3F808001))[0] == 0x3F81
+    assert Q.f32_to_bf16_bits(f(0x3F807FFF))[0] == 0x3F80
+    # carry into the exponent: 1.9999999 -> 2.0
+    assert Q.f32_to_bf16_bits(f(0x3FFFFFFF))[0] == 0x4000
+    # largest finite fp32 rounds to +inf in bf16
+    assert Q.f32_to_bf16_bits(f(0x7F7FFFFF))[0] == 0x7F80
+    # sign is kept, zero stays zero
+    assert Q.f32_to_bf16_bits(np.array([-1.0, 0.0, -0.0], dtype=np.float32)).tolist() == [0xBF80, 0x0000, 0x8000]
+    # known values: 1+2^-8 (midpoint, even below) -> 1 ; 3.140625 is exact in bf16
+    assert Q.round_to("bf16", np.array([1.00390625], dtype=np.float32))[1][0] == 1.0
+    assert Q.round_to("bf16", np.array([3.140625], dtype=np.float32))[1][0] == 3.140625
+
+
+def test_bf16_rounding_is_nearest():
+    g = np.random.default_rng(0)
+    x = g.standard_normal(20000).astype(np.float32) * np.float32(37.0)
+    bits, v = Q.round_to("bf16", x)
+    up = Q.bf16_bits_to_f32((bits.astype(np.int32) + 1).astype(np.uint16))
+    dn = Q.bf16_bits_to_f32((bits.astype(np.int32) - 1).astype(np.uint16))
+    d = np.abs(v.astype(np.float64) - x)
+    assert np.all(d <= np.abs(up.astype(np.float64) - x))
+    assert np.all(d <= np.abs(dn.astype(np.float64) - x))
+    assert np.all(d <= np.abs(x) * 2.0 ** -8)
+
+
+def test_f16_midpoints_and_round_trip():
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    vals = Q.f16_bits_to_f32(bits)
+    back = Q.f32_to_f16_bits(vals)
+    nan = np.isnan(vals)
+    assert np.array_equal(back[~nan], bits[~nan])
+    # fp16 spacing at 1.0 is 2^-10: midpoints go to even
+    one = np.float32(1.0)
+    assert Q.f32_to_f16_bits(np.array([one + np.float32(2.0 ** -11)]))[0] == 0x3C00
+    assert Q.f32_to_f16_bits(np.array([one + np.float32(3 * 2.0 ** -11)]))[0] == 0x3C02
+    assert Q.f32_to_f16_bits(np.array([65520.0], dtype=np.float32))[0] == 0x7C00  # overflow to inf
+
+
+def test_f32_passthrough():
+    x = np.array([1.5, -2.25, 3e-39], dtype=np.float32)
+    bits, v = Q.round_to("f32", x)
+    assert np.array_equal(v, x) and np.array_equal(Q.bits_to_f32("f32", bits), x)
