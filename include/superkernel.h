@@ -1,0 +1,190 @@
+/*
+ * superkernel.h -- C ABI of the coalesced "superkernel" library for MI355X (gfx950).
+ *
+ * The paper (arXiv 1901.10008, "The OoO VLIW JIT Compiler for GPU Inference")
+ * proposes that callers hand the GPU runtime *operators, their inputs and a
+ * latency constraint* instead of grids and blocks (Section 5.1, declarative
+ * kernel dispatch), and that the runtime then (a) coalesces the mutually
+ * independent operators of several inference streams into one large launch,
+ * the superkernel (Sections 1 and 5.3), and (b) puts operators with tighter
+ * latency budgets first (Section 5, item (a)).  This header is that interface
+ * for one batch of operators: describe them (sk_problem), plan them
+ * (sk_plan_create), run them as one launch (sk_launch) or, as the paper's
+ * time-multiplexing baseline of Section 4.1, one launch per operator
+ * (sk_launch_sequential).
+ *
+ * Operators are GEMMs and NHWC convolutions executed as the GEMM that backs
+ * them (Section 5.3, Figure 6 caption).  Every operator has its own operands;
+ * alpha = 1, beta = 0: C is overwritten and never read.
+ *
+ * General rules
+ *   - Every function returns sk_status (0 = success, negative = error) unless
+ *     stated otherwise.  No C++ exception crosses this boundary.  On error the
+ *     output arguments are left untouched; sk_last_error() gives a thread-local
+ *     detail string.
+ *   - A, B and C pointers are DEVICE pointers borrowed from the caller, who
+ *     keeps them alive and unmodified until the launches that use them have
+ *     completed.  The sk_problem array itself is copied by sk_plan_create.
+ *   - The plan owns its device-side tile table, operator descriptors and
+ *     counters.  `hip_stream` arguments are hipStream_t handles owned by the
+ *     caller (NULL = the default stream).  Launches are asynchronous.
+ *   - A plan has one work counter: two launches of the SAME plan must not be in
+ *     flight at the same time (launching it again on the same stream is fine).
+ */
+#ifndef SUPERKERNEL_H
+#define SUPERKERNEL_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SK_OK = 0,
+  SK_ERR_INVALID_ARG = -1, /* null pointer, dimension < 1, bad struct field          */
+  SK_ERR_UNSUPPORTED = -2, /* dtype / operator / dimension outside what is built      */
+  SK_ERR_OVERLAP = -3,     /* two operators' C ranges overlap                        */
+  SK_ERR_ALLOC = -4,       /* host or device allocation failed                       */
+  SK_ERR_HIP = -5,         /* a HIP runtime call failed (no device, launch error...) */
+  SK_ERR_STATE = -6        /* plan is host-only / stamps not enabled / ...           */
+} sk_status;
+
+/* A, B and C of one operator share the element type; accumulation is always fp32. */
+typedef enum { SK_F32 = 0, SK_BF16 = 1, SK_F16 = 2 } sk_dtype;
+typedef enum { SK_GEMM = 0, SK_CONV2D_NHWC = 1 } sk_op;
+
+/*
+ * One operator (Section 5.1: "the operators, the inputs, and latency constraints").
+ *
+ * SK_GEMM:  C[M,N] = A[M,K] . B, with the K x N weight operand stored
+ *   K-contiguous as Bs[N,K] (the layout of a linear layer's weight), i.e.
+ *   C[m,n] = sum_k A[m*lda + k] * Bs[n*ldb + k].  A and C are row-major.
+ *   lda, ldb, ldc are row strides in ELEMENTS; 0 means packed (K, K, N).
+ *   The conv fields are ignored.
+ *
+ * SK_CONV2D_NHWC:  Y = conv(X, W), cross-correlation, stride 1, dilation 1, one
+ *   group, zero padding, no bias:  A = X[Nb,H,Wd,Cin],  B = W[Cout,R,S,Cin],
+ *   C = Y[Nb,Ho,Wo,Cout] with Ho = H + 2*pad_h - R + 1, Wo = Wd + 2*pad_w - S + 1,
+ *   all dense.  M, N, K and the strides are ignored.  It is executed as the
+ *   GEMM with rows (b*Ho+ho)*Wo+wo, columns co and reduction index
+ *   (r*S+s)*Cin+c, without materialising the patch matrix.
+ *
+ * deadline_ms: latency budget measured from the start of the launch.  <= 0, NaN
+ *   or +inf mean "none".  It only orders the operators (earliest first, ties by
+ *   index); nothing is dropped or aborted when a deadline is missed.
+ */
+typedef struct {
+  int32_t op;    /* sk_op    */
+  int32_t dtype; /* sk_dtype */
+  int32_t M, N, K;
+  int64_t lda, ldb, ldc;
+  int32_t Nb, H, Wd, Cin, Cout, R, S, pad_h, pad_w;
+  int32_t reserved;
+  const void *A; /* device, read only */
+  const void *B; /* device, read only */
+  void *C;       /* device, written   */
+  double deadline_ms;
+} sk_problem;
+
+/*
+ * Planning parameters.  sk_plan_params_default() fills the defaults; a NULL
+ * params pointer means the defaults.  The tile table is a pure integer
+ * function of (problems, these fields); no device property enters it.
+ */
+typedef struct {
+  int32_t edf;            /* 1: order operators by (deadline, index); 0: by index            */
+  int32_t stamps;         /* 1: record a completion timestamp per operator (small cost)      */
+  int32_t host_only;      /* 1: plan on the host only, touch no device (launches then fail)  */
+  int32_t skinny_max_m;   /* operators with at most this many rows stream their weights      */
+                          /* straight to registers ("skinny" classes); 1..32, default 32     */
+  int64_t tile_bytes_max; /* skinny tiles: upper/lower clamp of the target weight bytes per  */
+  int64_t tile_bytes_min; /* tile; the target is sum(weight bytes) / balance_div             */
+  int32_t balance_div;    /* default 2048                                                    */
+  int32_t max_groups;     /* cap on 32-row weight groups per skinny tile, default 256        */
+  int32_t grid_limit;     /* upper bound on persistent workgroups per launch;                */
+                          /* 0 = 2 per compute unit of the current device                    */
+  int32_t reserved;
+} sk_plan_params;
+
+/*
+ * One record of the flat tile table (32 bytes, little endian).  The table
+ * lists, operator after operator in execution order, row blocks outer, column
+ * blocks inner, reduction slices innermost.
+ */
+typedef struct {
+  uint32_t problem;     /* index of the operator in the sk_problem array                    */
+  uint16_t cls;         /* tile class: 0..5 skinny (3*(rm-1) + log2(wk)), 6: 64x128, 7: 128x128 */
+  uint8_t ks_idx;       /* which reduction slice of the output rectangle this record is     */
+  uint8_t S;            /* number of reduction slices of the rectangle (1 = not split)      */
+  uint32_t m0, n0;      /* origin of the output rectangle in the operator's [Mg,Ng] GEMM view */
+  uint16_t m_len, n_len;/* its extent, already clipped to the operator                      */
+  uint32_t k0, k_len;   /* reduction range of this record                                   */
+  uint32_t out_tile_id; /* running index of the output rectangle over the whole plan        */
+} sk_tile;
+
+typedef struct sk_plan sk_plan; /* opaque, owned by the library */
+
+void sk_plan_params_default(sk_plan_params *params);
+
+/*
+ * Build the plan for n operators (the paper's runtime packing step, Section
+ * 5.3): canonical GEMM view, tile class per operator, earliest-deadline-first
+ * operator order, flat tile table; then upload table and descriptors to the
+ * current HIP device (unless params->host_only).
+ * n = 0 is a valid empty plan whose launches do nothing.
+ * Errors: SK_ERR_INVALID_ARG (null pointers, dims < 1, negative strides,
+ * strides smaller than a row), SK_ERR_UNSUPPORTED (unknown op/dtype, a
+ * dimension that does not fit the table's fields), SK_ERR_OVERLAP (the C
+ * ranges of two operators intersect; A and B may be shared freely),
+ * SK_ERR_ALLOC, SK_ERR_HIP.
+ */
+sk_status sk_plan_create(const sk_problem *problems, int32_t n, const sk_plan_params *params,
+                         sk_plan **out);
+sk_status sk_plan_destroy(sk_plan *plan); /* NULL is accepted */
+
+/*
+ * Run every operator of the plan in ONE kernel launch on `hip_stream`
+ * (Sections 1 and 5.3: the superkernel).  Persistent workgroups take tiles
+ * from the table in order through a single atomic counter, so operators with
+ * earlier deadlines start first.  Asynchronous.  Needs a device-resident plan
+ * (SK_ERR_STATE otherwise).
+ */
+sk_status sk_launch(sk_plan *plan, void *hip_stream);
+
+/*
+ * The time-multiplexing baseline (Section 4.1): the same device code, one
+ * launch per operator, in submission (index) order, all on `hip_stream`.
+ * Produces bit-identical outputs to sk_launch.
+ */
+sk_status sk_launch_sequential(sk_plan *plan, void *hip_stream);
+
+/* Introspection (used to compare the plan with a reference planner). */
+int64_t sk_plan_num_tiles(const sk_plan *plan);    /* < 0 on error */
+int32_t sk_plan_num_problems(const sk_plan *plan); /* < 0 on error */
+/* Copies the flat table (num_tiles * 32 bytes) to host memory `dst`. */
+sk_status sk_plan_get_tiles(const sk_plan *plan, void *dst, int64_t dst_bytes);
+/* Execution order: order[i] = index of the i-th operator to start (n entries). */
+sk_status sk_plan_get_order(const sk_plan *plan, int32_t *order);
+/* Per operator (by index): first record and number of records in the table. */
+sk_status sk_plan_get_ranges(const sk_plan *plan, int64_t *first_tile, int64_t *tile_count);
+/* Persistent workgroups sk_launch uses for this plan (0 for an empty or host-only plan). */
+int32_t sk_plan_grid(const sk_plan *plan);
+
+/*
+ * Completion stamps of the LAST completed launch of this plan (the caller must
+ * have synchronised the stream).  done_ticks[i] is the device wall clock when
+ * operator i's last tile retired, *start_tick the clock when the first
+ * workgroup of the launch started; *ticks_per_ms converts.  Any pointer may be
+ * NULL.  SK_ERR_STATE unless the plan was created with params->stamps = 1.
+ */
+sk_status sk_plan_get_stamps(sk_plan *plan, uint64_t *done_ticks, uint64_t *start_tick,
+                             double *ticks_per_ms);
+
+const char *sk_strerror(sk_status status);
+const char *sk_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SUPERKERNEL_H */

@@ -1,0 +1,32 @@
+"""MI355X-native coalesced "superkernel" for multi-tenant low-batch inference.
+
+Thin Python binding over the C ABI in include/superkernel.h.  All planning and
+all arithmetic run in libsuperkernel.so (C++ planner + hand-written HIP kernels
+for gfx950); this package only marshals arguments.  There is no CPU fallback:
+if the library has not been built, importing the binding raises.
+"""
+from .binding import (  # noqa: F401
+    SkError,
+    Plan,
+    PlanParams,
+    lib,
+    lib_path,
+    make_problem,
+    sk_plan_create,
+    sk_plan_destroy,
+    sk_launch,
+    sk_launch_sequential,
+    sk_plan_num_tiles,
+    sk_plan_num_problems,
+    sk_plan_get_tiles,
+    sk_plan_get_order,
+    sk_plan_get_ranges,
+    sk_plan_get_stamps,
+    sk_plan_grid,
+    sk_plan_params_default,
+    sk_strerror,
+    sk_last_error,
+    SK_F32, SK_BF16, SK_F16, SK_GEMM, SK_CONV2D_NHWC,
+    DTYPE_CODE,
+    EXPORTED_SYMBOLS,
+)

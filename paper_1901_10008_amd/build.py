@@ -1,0 +1,53 @@
+"""Build libsuperkernel.so (HIP, gfx950 only) in-tree next to this file."""
+from __future__ import annotations
+
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+CSRC = os.path.join(HERE, "csrc")
+LIB = os.path.join(HERE, "libsuperkernel.so")
+SOURCES = ["superkernel.hip", "planner.cpp"]
+HEADERS = ["kernels.hip.h", "sk_internal.h", os.path.join(ROOT, "include", "superkernel.h")]
+
+HIPCC_FLAGS = [
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-fno-gpu-rdc", "-Wall", "-Wno-unused-function",
+]
+
+
+def build(force: bool = True, verbose: bool = False, extra=()) -> str:
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    srcs = [os.path.join(CSRC, s) for s in SOURCES]
+    if not force and os.path.exists(LIB):
+        newest = max(os.path.getmtime(p) for p in srcs + [os.path.join(CSRC, h) if not os.path.isabs(h) else h
+                                                          for h in HEADERS])
+        if os.path.getmtime(LIB) >= newest:
+            return LIB
+    inc = ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    obj_dir = os.path.join(HERE, "_build")
+    os.makedirs(obj_dir, exist_ok=True)
+    o_hip = os.path.join(obj_dir, "superkernel.o")
+    o_cpp = os.path.join(obj_dir, "planner.o")
+    steps = [
+        [hipcc, *HIPCC_FLAGS, *extra, *inc, "-c", srcs[0], "-o", o_hip],
+        ["g++", "-O2", "-std=c++17", "-fPIC", "-Wall", *inc, "-c", srcs[1], "-o", o_cpp],
+        [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", o_hip, o_cpp, "-o", LIB],
+    ]
+    for cmd in steps:
+        if verbose:
+            print(" ".join(cmd))
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        # the host pass warns that it does not know the packed-fp32 feature: harmless noise
+        err = "\n".join(l for l in res.stderr.splitlines() if "packed-fp32-ops" not in l)
+        if res.returncode != 0:
+            raise RuntimeError("build step failed: " + " ".join(cmd) + "\n" + err)
+        if verbose and err.strip():
+            print(err)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(force=True, verbose=True))

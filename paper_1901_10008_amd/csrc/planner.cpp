@@ -1,0 +1,284 @@
+// Host planner: operators -> canonical GEMM view -> tile classes -> earliest-
+// deadline-first operator order -> flat tile table.
+//
+// This is the paper's runtime packing step (Section 5.3: many small kernels are
+// repacked into one large execution block) together with its latency-aware
+// reordering (Section 5, item (a): tighter latency budgets first).  The paper
+// gives no algorithm for either; the rule implemented here is a pure integer
+// function of the operator list and sk_plan_params, so that it can be checked
+// byte for byte against an independent reference planner.
+//
+// No HIP call is made in this file.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <limits>
+#include <numeric>
+
+#include "sk_internal.h"
+
+namespace sk {
+
+namespace {
+
+struct Canon {
+  int64_t Mg, Ng, Kg;
+  int32_t Ho, Wo;
+};
+
+std::string at(int32_t i) { return "problem " + std::to_string(i) + ": "; }
+
+// Canonical GEMM view (rows = output pixels, columns = output channels,
+// reduction = filter taps x input channels for a convolution).
+sk_status canonicalise(const sk_problem &p, int32_t i, Canon &c, std::string &err) {
+  if (p.dtype != SK_F32 && p.dtype != SK_BF16 && p.dtype != SK_F16) {
+    err = at(i) + "unknown dtype " + std::to_string(p.dtype);
+    return SK_ERR_UNSUPPORTED;
+  }
+  if (!p.A || !p.B || !p.C) {
+    err = at(i) + "null operand pointer";
+    return SK_ERR_INVALID_ARG;
+  }
+  if (p.op == SK_GEMM) {
+    if (p.M < 1 || p.N < 1 || p.K < 1) {
+      err = at(i) + "GEMM dimensions must be >= 1";
+      return SK_ERR_INVALID_ARG;
+    }
+    if (p.lda < 0 || p.ldb < 0 || p.ldc < 0 || (p.lda && p.lda < p.K) || (p.ldb && p.ldb < p.K) ||
+        (p.ldc && p.ldc < p.N)) {
+      err = at(i) + "row stride smaller than a row";
+      return SK_ERR_INVALID_ARG;
+    }
+    c = Canon{p.M, p.N, p.K, 0, 0};
+  } else if (p.op == SK_CONV2D_NHWC) {
+    if (p.Nb < 1 || p.H < 1 || p.Wd < 1 || p.Cin < 1 || p.Cout < 1 || p.R < 1 || p.S < 1 || p.pad_h < 0 ||
+        p.pad_w < 0) {
+      err = at(i) + "convolution dimensions must be >= 1 and padding >= 0";
+      return SK_ERR_INVALID_ARG;
+    }
+    const int64_t Ho = (int64_t)p.H + 2 * (int64_t)p.pad_h - p.R + 1;
+    const int64_t Wo = (int64_t)p.Wd + 2 * (int64_t)p.pad_w - p.S + 1;
+    if (Ho < 1 || Wo < 1) {
+      err = at(i) + "filter larger than the padded image";
+      return SK_ERR_INVALID_ARG;
+    }
+    if (Ho > 1 << 20 || Wo > 1 << 20) {
+      err = at(i) + "image too large";
+      return SK_ERR_UNSUPPORTED;
+    }
+    c = Canon{(int64_t)p.Nb * Ho * Wo, p.Cout, (int64_t)p.R * p.S * p.Cin, (int32_t)Ho, (int32_t)Wo};
+  } else {
+    err = at(i) + "unknown operator " + std::to_string(p.op);
+    return SK_ERR_UNSUPPORTED;
+  }
+  const int64_t lim = std::numeric_limits<int32_t>::max() / 2;
+  if (c.Mg > lim || c.Ng > lim || c.Kg > lim) {
+    err = at(i) + "canonical dimension does not fit 31 bits";
+    return SK_ERR_UNSUPPORTED;
+  }
+  return SK_OK;
+}
+
+double deadline_key(double d) {
+  if (!(d > 0.0) || std::isinf(d)) return std::numeric_limits<double>::infinity();
+  return d;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+}  // namespace
+
+sk_status plan_host(const sk_problem *problems, int32_t n, const sk_plan_params *params, HostPlan &out,
+                    std::string &err) {
+  if (n < 0 || (n > 0 && !problems)) {
+    err = "problems is null or n < 0";
+    return SK_ERR_INVALID_ARG;
+  }
+  sk_plan_params prm;
+  if (params)
+    prm = *params;
+  else
+    sk_plan_params_default(&prm);
+  if (prm.skinny_max_m < 0 || prm.skinny_max_m > 32 || prm.tile_bytes_min < 1 ||
+      prm.tile_bytes_max < prm.tile_bytes_min || prm.balance_div < 1 || prm.max_groups < 1 ||
+      prm.max_groups > 256 || prm.grid_limit < 0) {
+    err = "sk_plan_params field out of range";
+    return SK_ERR_INVALID_ARG;
+  }
+  out = HostPlan{};
+  out.params = prm;
+  out.problems.assign(problems, problems + n);
+  out.dev.resize(n);
+  out.first.assign(n, 0);
+  out.count.assign(n, 0);
+
+  // ---- canonical view, operand strides, vector-access flags ----
+  std::vector<Canon> canon(n);
+  int64_t total_w = 0;
+  for (int32_t i = 0; i < n; ++i) {
+    const sk_problem &p = out.problems[i];
+    sk_status st = canonicalise(p, i, canon[i], err);
+    if (st != SK_OK) return st;
+    const Canon &c = canon[i];
+    const int es = elem_size(p.dtype);
+    const int ce = 16 / es;  // elements per 16-byte piece
+    DevProblem d;
+    std::memset(&d, 0, sizeof(d));
+    d.A = p.A;
+    d.B = p.B;
+    d.C = p.C;
+    d.Mg = (int32_t)c.Mg;
+    d.Ng = (int32_t)c.Ng;
+    d.Kg = (int32_t)c.Kg;
+    d.dtype = p.dtype;
+    if (p.op == SK_GEMM) {
+      d.lda = p.lda ? p.lda : p.K;
+      d.ldb = p.ldb ? p.ldb : p.K;
+      d.ldc = p.ldc ? p.ldc : p.N;
+      d.gather = 0;
+    } else {
+      d.ldb = c.Kg;
+      d.ldc = p.Cout;
+      d.H = p.H;
+      d.W = p.Wd;
+      d.Cin = p.Cin;
+      d.Ho = c.Ho;
+      d.Wo = c.Wo;
+      d.R = p.R;
+      d.S = p.S;
+      d.pad_h = p.pad_h;
+      d.pad_w = p.pad_w;
+      // a 1x1 filter without padding reads the image as a plain [pixels, Cin] matrix
+      d.gather = !(p.R == 1 && p.S == 1 && p.pad_h == 0 && p.pad_w == 0);
+      d.lda = p.Cin;
+    }
+    int32_t flags = 0;
+    if (d.gather) {
+      if (aligned16(p.A) && p.Cin % ce == 0) flags |= FLAG_VEC_A;
+    } else {
+      if (aligned16(p.A) && d.lda % ce == 0 && c.Kg % ce == 0) flags |= FLAG_VEC_A;
+    }
+    if (aligned16(p.B) && d.ldb % ce == 0 && c.Kg % ce == 0) flags |= FLAG_VEC_B;
+    if ((reinterpret_cast<uintptr_t>(p.C) % (4 * es)) == 0 && d.ldc % 4 == 0) flags |= FLAG_VEC_C;
+    d.flags = flags;
+    out.dev[i] = d;
+    total_w += c.Ng * c.Kg * es;
+  }
+
+  // ---- output ranges must be pairwise disjoint ----
+  {
+    struct Range {
+      uintptr_t lo, hi;
+      int32_t idx;
+    };
+    std::vector<Range> r(n);
+    for (int32_t i = 0; i < n; ++i) {
+      const DevProblem &d = out.dev[i];
+      const uintptr_t lo = reinterpret_cast<uintptr_t>(d.C);
+      const uint64_t elems = (uint64_t)(d.Mg - 1) * (uint64_t)d.ldc + (uint64_t)d.Ng;
+      r[i] = Range{lo, lo + elems * (uint64_t)elem_size(d.dtype), i};
+    }
+    std::sort(r.begin(), r.end(), [](const Range &a, const Range &b) { return a.lo < b.lo; });
+    for (int32_t i = 1; i < n; ++i) {
+      if (r[i].lo < r[i - 1].hi) {
+        err = "output ranges of problems " + std::to_string(r[i - 1].idx) + " and " + std::to_string(r[i].idx) +
+              " overlap";
+        return SK_ERR_OVERLAP;
+      }
+    }
+  }
+
+  // ---- target weight bytes per skinny tile ----
+  int64_t T = total_w / prm.balance_div;
+  T = std::max<int64_t>(prm.tile_bytes_min, std::min<int64_t>(prm.tile_bytes_max, T));
+  if (n == 0) T = prm.tile_bytes_min;
+  out.target_tile_bytes = T;
+
+  // ---- operator order: earliest deadline first, ties by index ----
+  out.order.resize(n);
+  std::iota(out.order.begin(), out.order.end(), 0);
+  if (prm.edf) {
+    std::stable_sort(out.order.begin(), out.order.end(), [&](int32_t a, int32_t b) {
+      return deadline_key(out.problems[a].deadline_ms) < deadline_key(out.problems[b].deadline_ms);
+    });
+  }
+
+  // ---- flat table ----
+  uint32_t out_id = 0;
+  for (int32_t pos = 0; pos < n; ++pos) {
+    const int32_t i = out.order[pos];
+    const Canon &c = canon[i];
+    const int es = elem_size(out.problems[i].dtype);
+    uint16_t cls;
+    int64_t BM, BN;
+    if (c.Mg <= prm.skinny_max_m) {
+      const int rm = c.Mg <= 16 ? 1 : 2;
+      const int64_t gb = 32 * c.Kg * es;  // bytes of one 32-row weight group
+      int wk_code;
+      int64_t G;
+      if (gb >= T) {
+        wk_code = 2;  // four-way reduction split, one group
+        G = 1;
+      } else if (2 * gb >= T) {
+        wk_code = 1;  // two-way split, two groups
+        G = 2;
+      } else {
+        wk_code = 0;
+        G = std::min<int64_t>(prm.max_groups, 4 * std::max<int64_t>(1, T / (4 * gb)));
+      }
+      cls = (uint16_t)(3 * (rm - 1) + wk_code);
+      BM = c.Mg;
+      BN = 32 * G;
+    } else if (c.Mg <= 64) {
+      cls = CLS_TILE_64x128;
+      BM = 64;
+      BN = 128;
+    } else {
+      cls = CLS_TILE_128x128;
+      BM = 128;
+      BN = 128;
+    }
+    out.first[i] = (int64_t)out.tiles.size();
+    for (int64_t m0 = 0; m0 < c.Mg; m0 += BM) {
+      for (int64_t n0 = 0; n0 < c.Ng; n0 += BN) {
+        sk_tile t;
+        t.problem = (uint32_t)i;
+        t.cls = cls;
+        t.ks_idx = 0;
+        t.S = 1;
+        t.m0 = (uint32_t)m0;
+        t.n0 = (uint32_t)n0;
+        t.m_len = (uint16_t)std::min<int64_t>(BM, c.Mg - m0);
+        t.n_len = (uint16_t)std::min<int64_t>(BN, c.Ng - n0);
+        t.k0 = 0;
+        t.k_len = (uint32_t)c.Kg;
+        t.out_tile_id = out_id++;
+        out.tiles.push_back(t);
+        if (out.tiles.size() > (size_t)1 << 30) {
+          err = "tile table too large";
+          return SK_ERR_UNSUPPORTED;
+        }
+      }
+    }
+    out.count[i] = (int64_t)out.tiles.size() - out.first[i];
+    out.dev[i].tile_first = (int32_t)out.first[i];
+    out.dev[i].tile_count = (int32_t)out.count[i];
+  }
+  return SK_OK;
+}
+
+}  // namespace sk
+
+extern "C" void sk_plan_params_default(sk_plan_params *p) {
+  if (!p) return;
+  std::memset(p, 0, sizeof(*p));
+  p->edf = 1;
+  p->stamps = 0;
+  p->host_only = 0;
+  p->skinny_max_m = 32;
+  p->tile_bytes_max = 256 * 1024;
+  p->tile_bytes_min = 32 * 1024;
+  p->balance_div = 2048;
+  p->max_groups = 256;
+  p->grid_limit = 0;
+}

@@ -1,0 +1,61 @@
+// Internal declarations shared by the host planner and the HIP launch code.
+// Not part of the public ABI (include/superkernel.h is).
+#pragma once
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "superkernel.h"
+
+namespace sk {
+
+enum : int32_t {
+  FLAG_VEC_A = 1,  // activation rows can be read in aligned 16-byte pieces
+  FLAG_VEC_B = 2,  // weight rows can be read in aligned 16-byte pieces
+  FLAG_VEC_C = 4,  // four consecutive outputs of a row can be stored as one vector
+};
+
+enum : uint16_t {
+  CLS_SKINNY_FIRST = 0,  // 0..5: 3*(rm-1) + log2(wk)
+  CLS_TILE_64x128 = 6,
+  CLS_TILE_128x128 = 7,
+};
+
+// Device-side description of one operator in its canonical GEMM view
+//   C[Mg,Ng] = A'[Mg,Kg] . Bs[Ng,Kg]^T
+// where A' is either a plain row-major matrix (gather == 0) or the implicit
+// patch matrix of an NHWC image (gather == 1; Section 5.3: a convolution is
+// executed through the GEMM that backs it).
+struct DevProblem {
+  const void *A;
+  const void *B;
+  void *C;
+  int64_t lda, ldb, ldc;  // row strides in elements (lda unused when gather)
+  int32_t Mg, Ng, Kg;
+  int32_t dtype;
+  int32_t gather;
+  int32_t H, W, Cin, Ho, Wo, R, S, pad_h, pad_w;
+  int32_t flags;
+  int32_t tile_first, tile_count;
+  int32_t pad0;
+};
+static_assert(sizeof(DevProblem) % 8 == 0, "DevProblem must stay 8-byte sized");
+
+struct HostPlan {
+  std::vector<sk_problem> problems;
+  std::vector<DevProblem> dev;
+  std::vector<sk_tile> tiles;
+  std::vector<int32_t> order;
+  std::vector<int64_t> first, count;
+  sk_plan_params params;
+  int64_t target_tile_bytes = 0;
+};
+
+// Pure host planning (no HIP call).  Returns SK_OK or an error with `err` set.
+sk_status plan_host(const sk_problem *problems, int32_t n, const sk_plan_params *params,
+                    HostPlan &out, std::string &err);
+
+inline int elem_size(int32_t dtype) { return dtype == SK_F32 ? 4 : 2; }
+
+}  // namespace sk

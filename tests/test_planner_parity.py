@@ -1,0 +1,182 @@
+"""Host logic behind the C ABI, checked without a GPU: the C++ planner's tile
+table, operator order and ranges equal the reference planner's byte for byte;
+argument validation returns error codes; the library exports every declared
+symbol."""
+import math
+import os
+import re
+from types import SimpleNamespace as NS
+
+import pytest
+
+import paper_1901_10008_amd as sk
+import workloads
+from oracle import planner as P
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+ES = {"f32": 4, "bf16": 2, "f16": 2}
+
+
+def fake_problems(specs, misalign=None):
+    """sk_problem list with made-up, disjoint, 256-byte aligned device addresses (never dereferenced)."""
+    out = []
+    addr = 0x10000000
+    for i, s in enumerate(specs):
+        es = ES[s.dtype]
+        if s.op == "gemm":
+            na, nb, nc = s.M * s.K, s.N * s.K, s.M * s.N
+        else:
+            ho = s.H + 2 * s.pad_h - s.R + 1
+            wo = s.W + 2 * s.pad_w - s.S + 1
+            na, nb, nc = s.Nb * s.H * s.W * s.Cin, s.Cout * s.R * s.S * s.Cin, s.Nb * ho * wo * s.Cout
+        ptrs = []
+        for cnt in (na, nb, nc):
+            ptrs.append(addr)
+            addr += (cnt * es + 255) // 256 * 256 + 256
+        out.append(sk.make_problem(s, *ptrs))
+    return out
+
+
+def host_plan(specs, **prm):
+    params = sk.sk_plan_params_default(host_only=1, **prm)
+    return sk.sk_plan_create(fake_problems(specs), params)
+
+
+def ref_params(**kw):
+    return P.Params(**kw)
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("seed", [0, 1])
+def test_plan_bytes_match_reference_on_configs(idx, seed):
+    specs = workloads.config(idx, seed=seed)
+    with host_plan(specs) as plan:
+        table, order, first, count = P.plan(specs)
+        assert sk.sk_plan_num_problems(plan) == len(specs)
+        assert sk.sk_plan_num_tiles(plan) == len(table) // 32
+        assert sk.sk_plan_get_tiles(plan) == table
+        assert sk.sk_plan_get_order(plan) == order
+        assert sk.sk_plan_get_ranges(plan) == (first, count)
+        P.check_coverage(specs, sk.sk_plan_get_tiles(plan))
+
+
+def _g(m, n, k, dtype="bf16", d=math.inf):
+    return NS(op="gemm", dtype=dtype, M=m, N=n, K=k, deadline_ms=d)
+
+
+def _c(h, w, cin, cout, r, s, ph, pw, dtype="bf16", nb=1, d=math.inf):
+    return NS(op="conv", dtype=dtype, Nb=nb, H=h, W=w, Cin=cin, Cout=cout, R=r, S=s, pad_h=ph, pad_w=pw,
+              deadline_ms=d)
+
+
+RAGGED = [_g(1, 5, 3, "f32"), _g(17, 33, 129), _g(33, 130, 70, "f16"), _g(65, 129, 8), _g(200, 300, 100, "f32"),
+          _g(16, 9000, 64), _g(32, 40, 8192), _g(2, 8192, 8192, d=1.5), _g(7, 100, 2048, "f32", d=0.25),
+          _c(5, 5, 3, 7, 3, 3, 1, 1), _c(9, 9, 8, 130, 1, 1, 0, 0, d=0.25), _c(13, 11, 16, 40, 3, 3, 1, 1, nb=2),
+          _c(6, 6, 4, 4, 3, 1, 0, 0, "f32"), _c(4, 4, 8, 8, 1, 1, 1, 1)]
+
+
+@pytest.mark.parametrize("prm", [
+    {},
+    {"edf": 0},
+    {"skinny_max_m": 16},
+    {"skinny_max_m": 0},
+    {"tile_bytes_min": 4096, "tile_bytes_max": 8192, "balance_div": 7},
+    {"tile_bytes_min": 1 << 20, "tile_bytes_max": 1 << 22, "max_groups": 3},
+])
+def test_plan_bytes_match_reference_ragged_and_params(prm):
+    with host_plan(RAGGED, **prm) as plan:
+        table, order, first, count = P.plan(RAGGED, ref_params(**prm))
+        assert sk.sk_plan_get_tiles(plan) == table
+        assert sk.sk_plan_get_order(plan) == order
+        assert sk.sk_plan_get_ranges(plan) == (first, count)
+        P.check_coverage(RAGGED, table)
+
+
+def test_permuting_operators_permutes_the_plan_consistently():
+    specs = workloads.config(4, seed=3)
+    perm = list(range(len(specs)))[::-1]
+    with host_plan(specs) as a, host_plan([specs[i] for i in perm]) as b:
+        ta, tb = P.decode(sk.sk_plan_get_tiles(a)), P.decode(sk.sk_plan_get_tiles(b))
+        strip = lambda t, idx: sorted((idx(x["problem"]), x["cls"], x["m0"], x["n0"], x["m_len"], x["n_len"],
+                                       x["k0"], x["k_len"]) for x in t)
+        assert strip(ta, lambda i: i) == strip(tb, lambda i: perm[i])
+
+
+def test_empty_plan():
+    with sk.sk_plan_create([], sk.sk_plan_params_default(host_only=1)) as plan:
+        assert sk.sk_plan_num_tiles(plan) == 0 and sk.sk_plan_num_problems(plan) == 0
+        assert sk.sk_plan_get_tiles(plan) == b"" and sk.sk_plan_get_order(plan) == []
+        assert sk.sk_plan_grid(plan) == 0
+
+
+def _expect(status, problems, **prm):
+    with pytest.raises(sk.SkError) as e:
+        sk.sk_plan_create(problems, sk.sk_plan_params_default(host_only=1, **prm))
+    assert e.value.status == status, e.value
+    assert e.value.detail
+
+
+def test_validation_errors():
+    ok = fake_problems([_g(4, 64, 64), _g(4, 64, 64)])
+    # dimension < 1
+    bad = fake_problems([_g(4, 64, 64)])
+    bad[0].M = 0
+    _expect(-1, bad)
+    # null pointer
+    bad = fake_problems([_g(4, 64, 64)])
+    bad[0].B = None
+    _expect(-1, bad)
+    # stride shorter than a row
+    bad = fake_problems([_g(4, 64, 64)])
+    bad[0].lda = 32
+    _expect(-1, bad)
+    # unknown dtype / op
+    bad = fake_problems([_g(4, 64, 64)])
+    bad[0].dtype = 9
+    _expect(-2, bad)
+    bad = fake_problems([_g(4, 64, 64)])
+    bad[0].op = 5
+    _expect(-2, bad)
+    # filter larger than the image
+    _expect(-1, fake_problems([_c(2, 2, 4, 4, 3, 3, 0, 0)]))
+    # overlapping outputs (same C) -> overlap; sharing A and B is fine
+    bad = fake_problems([_g(4, 64, 64), _g(4, 64, 64)])
+    bad[1].C = bad[0].C + 64
+    _expect(-3, bad)
+    shared = fake_problems([_g(4, 64, 64), _g(4, 64, 64)])
+    shared[1].A, shared[1].B = shared[0].A, shared[0].B
+    sk.sk_plan_create(shared, sk.sk_plan_params_default(host_only=1)).close()
+    # adjacent but disjoint outputs are fine; strided outputs interleaving in address but overlapping in range are not
+    adj = fake_problems([_g(4, 64, 64), _g(4, 64, 64)])
+    adj[1].C = adj[0].C + 4 * 64 * 2
+    sk.sk_plan_create(adj, sk.sk_plan_params_default(host_only=1)).close()
+    # parameter out of range
+    _expect(-1, ok, skinny_max_m=33)
+    _expect(-1, ok, balance_div=0)
+    # launching a host-only plan is a state error
+    with sk.sk_plan_create(ok, sk.sk_plan_params_default(host_only=1)) as plan:
+        with pytest.raises(sk.SkError) as e:
+            sk.sk_launch(plan)
+        assert e.value.status == -6
+        with pytest.raises(sk.SkError) as e:
+            sk.sk_plan_get_stamps(plan)
+        assert e.value.status == -6
+
+
+def test_library_exports_every_declared_symbol():
+    with open(os.path.join(ROOT, "include", "superkernel.h")) as f:
+        text = f.read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(sk_[a-z_]+)\s*\(", text))
+    assert declared == set(sk.EXPORTED_SYMBOLS)
+    L = sk.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+    assert sk.sk_strerror(0) == "success" and "overlap" in sk.sk_strerror(-3)
+
+
+def test_struct_layout_matches_header():
+    import ctypes
+    from paper_1901_10008_amd import binding
+    assert ctypes.sizeof(binding.sk_problem) == 120
+    assert ctypes.sizeof(binding.PlanParams) == 48
