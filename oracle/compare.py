@@ -15,8 +15,9 @@ import numpy as np
 
 TOL = {"f32": 1e-5, "bf16": 2e-2, "f16": 2e-2}
 
-# unit roundoff of the output format (round to nearest)
-_U_OUT = {"f32": 2.0 ** -24, "bf16": 2.0 ** -9, "f16": 2.0 ** -11}
+# unit roundoff of the output format (round to nearest): 2^-p for p significand bits
+# (fp32: 24, fp16: 11, bf16: 8 = 7 stored + 1 implicit)
+_U_OUT = {"f32": 2.0 ** -24, "bf16": 2.0 ** -8, "f16": 2.0 ** -11}
 
 
 def errors(c, ref, mag=None):

@@ -32,6 +32,18 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
+// Operand pointers reach the kernel through descriptors in memory, so the compiler cannot
+// see that they are global addresses; say so explicitly (global_load instead of flat_load).
+#define SK_GLOBAL __attribute__((address_space(1)))
+template <class T>
+__device__ __forceinline__ const T SK_GLOBAL *as_global(const void *p) {
+  return (const T SK_GLOBAL *)(uintptr_t)p;
+}
+template <class T>
+__device__ __forceinline__ T SK_GLOBAL *as_global_mut(void *p) {
+  return (T SK_GLOBAL *)(uintptr_t)p;
+}
+
 constexpr int WG_THREADS = 256;
 constexpr int LDS_ROW = 144;                  // 128 bytes of K + 16 bytes of padding (bank spread)
 constexpr int LDS_TILE_BYTES = 256 * LDS_ROW;  // 128 activation rows + 128 weight rows
@@ -85,24 +97,24 @@ __device__ __forceinline__ uint32_t cvt_bits(float f) {
 template <int DT>
 __device__ __forceinline__ void store4(void *C, int64_t row_off, int n, int n_end, f32x4 v, bool vec_ok) {
   constexpr int ES = Elem<DT>::ES;
-  char *p = (char *)C + (row_off + n) * ES;
+  char SK_GLOBAL *p = as_global_mut<char>(C) + (row_off + n) * ES;
   if (vec_ok && n + 3 < n_end) {
     if constexpr (ES == 4) {
-      *(f32x4 *)p = v;
+      *(f32x4 SK_GLOBAL *)p = v;
     } else {
       u32x2 o;
       o.x = cvt_bits<DT>(v.x) | (cvt_bits<DT>(v.y) << 16);
       o.y = cvt_bits<DT>(v.z) | (cvt_bits<DT>(v.w) << 16);
-      *(u32x2 *)p = o;
+      *(u32x2 SK_GLOBAL *)p = o;
     }
   } else {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       if (n + i < n_end) {
         if constexpr (ES == 4)
-          ((float *)p)[i] = v[i];
+          ((float SK_GLOBAL *)p)[i] = v[i];
         else
-          ((uint16_t *)p)[i] = (uint16_t)cvt_bits<DT>(v[i]);
+          ((uint16_t SK_GLOBAL *)p)[i] = (uint16_t)cvt_bits<DT>(v[i]);
       }
     }
   }
@@ -114,12 +126,12 @@ template <int ES>
 __device__ __forceinline__ u32x4 load_piece_scalar(const void *base, int64_t off, int k, int Kg) {
   u32x4 v = {0u, 0u, 0u, 0u};
   if constexpr (ES == 4) {
-    const uint32_t *p = (const uint32_t *)base + off;
+    const uint32_t SK_GLOBAL *p = as_global<uint32_t>(base) + off;
 #pragma unroll
     for (int e = 0; e < 4; ++e)
       if (k + e < Kg) v[e] = p[e];
   } else {
-    const uint16_t *p = (const uint16_t *)base + off;
+    const uint16_t SK_GLOBAL *p = as_global<uint16_t>(base) + off;
 #pragma unroll
     for (int e = 0; e < 8; ++e)
       if (k + e < Kg) v[e >> 1] |= (uint32_t)p[e] << (16 * (e & 1));
@@ -129,7 +141,7 @@ __device__ __forceinline__ u32x4 load_piece_scalar(const void *base, int64_t off
 
 template <int ES, bool NT>
 __device__ __forceinline__ u32x4 load_piece_vec(const void *base, int64_t off) {
-  const u32x4 *p = (const u32x4 *)((const char *)base + off * ES);
+  const u32x4 SK_GLOBAL *p = (const u32x4 SK_GLOBAL *)(as_global<char>(base) + off * ES);
   if constexpr (NT)
     return __builtin_nontemporal_load(p);
   else
@@ -200,9 +212,9 @@ __device__ __forceinline__ u32x4 fetch_A(const DevProblem &P, const RowA &row, i
     int64_t off;
     if (k + e < P.Kg && patch_offset(P, row, k + e, off)) {
       if constexpr (ES == 4)
-        v[e] = ((const uint32_t *)P.A)[off];
+        v[e] = as_global<uint32_t>(P.A)[off];
       else
-        v[e >> 1] |= (uint32_t)((const uint16_t *)P.A)[off] << (16 * (e & 1));
+        v[e >> 1] |= (uint32_t)as_global<uint16_t>(P.A)[off] << (16 * (e & 1));
     }
   }
   return v;
@@ -222,10 +234,10 @@ __device__ __forceinline__ void mma16(const u32x4 &a, const u32x4 &b, f32x4 &c) 
   } else if constexpr (DT == SK_F16) {
     c = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
   } else {
+    // (whole-vector casts: a bit cast applied to a single vector element reads element 0)
+    const f32x4 af = __builtin_bit_cast(f32x4, a), bf = __builtin_bit_cast(f32x4, b);
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-      c = __builtin_amdgcn_mfma_f32_16x16x4f32(__builtin_bit_cast(float, a[j]), __builtin_bit_cast(float, b[j]), c, 0,
-                                               0, 0);
+    for (int j = 0; j < 4; ++j) c = __builtin_amdgcn_mfma_f32_16x16x4f32(af[j], bf[j], c, 0, 0, 0);
   }
 }
 
@@ -237,10 +249,9 @@ __device__ __forceinline__ void mma32(const u32x4 &a, const u32x4 &b, f32x16 &c)
   } else if constexpr (DT == SK_F16) {
     c = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
   } else {
+    const f32x4 af = __builtin_bit_cast(f32x4, a), bf = __builtin_bit_cast(f32x4, b);
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-      c = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(float, a[j]), __builtin_bit_cast(float, b[j]), c, 0,
-                                               0, 0);
+    for (int j = 0; j < 4; ++j) c = __builtin_amdgcn_mfma_f32_32x32x2f32(af[j], bf[j], c, 0, 0, 0);
   }
 }
 
@@ -309,32 +320,39 @@ __device__ __forceinline__ void run_skinny(const DevProblem &P, const sk_tile &T
       }
       int k = k_lo;
       if (fast) {
-        // whole blocks, aligned operands, plain row-major activations: no predicates on k
-        const char *wp0 = (const char *)P.B + (wrow[0] + q * 2 * CE) * ES;
-        const char *wp1 = (const char *)P.B + (wrow[1] + q * 2 * CE) * ES;
-        const char *ap[RM];
+        // whole blocks, aligned operands, plain row-major activations: no predicates at all.
+        // Activation rows past Mg repeat row 0; their output columns are never stored.
+        const char SK_GLOBAL *wp0 = as_global<char>(P.B) + (wrow[0] + q * 2 * CE) * ES;
+        const char SK_GLOBAL *wp1 = as_global<char>(P.B) + (wrow[1] + q * 2 * CE) * ES;
+        const char SK_GLOBAL *ap[RM];
 #pragma unroll
-        for (int mb = 0; mb < RM; ++mb) ap[mb] = (const char *)P.A + (rowa[mb].base + q * 2 * CE) * ES;
-        const int k_full = k_lo + ((k_hi - k_lo) / KB) * KB;
-#pragma unroll 2
-        for (; k < k_full; k += KB) {
-          const int64_t ko = (int64_t)k * ES;
-          u32x4 w00 = __builtin_nontemporal_load((const u32x4 *)(wp0 + ko));
-          u32x4 w01 = __builtin_nontemporal_load((const u32x4 *)(wp0 + ko + 16));
-          u32x4 w10 = __builtin_nontemporal_load((const u32x4 *)(wp1 + ko));
-          u32x4 w11 = __builtin_nontemporal_load((const u32x4 *)(wp1 + ko + 16));
+        for (int mb = 0; mb < RM; ++mb) ap[mb] = as_global<char>(P.A) + (rowa[mb].base + q * 2 * CE) * ES;
+        constexpr int U = 2;  // blocks per trip: all loads of a trip are issued before its first MFMA
+        const int k_full = k_lo + ((k_hi - k_lo) / (U * KB)) * (U * KB);
+        for (; k < k_full; k += U * KB) {
+          u32x4 w[U][4], av[U][RM][2];
 #pragma unroll
-          for (int mb = 0; mb < RM; ++mb) {
-            u32x4 a0 = {0u, 0u, 0u, 0u}, a1 = {0u, 0u, 0u, 0u};
-            if (m_ok[mb]) {
-              a0 = *(const u32x4 *)(ap[mb] + ko);
-              a1 = *(const u32x4 *)(ap[mb] + ko + 16);
+          for (int u = 0; u < U; ++u) {
+            const int64_t ko = (int64_t)(k + u * KB) * ES;
+            w[u][0] = __builtin_nontemporal_load((const u32x4 SK_GLOBAL *)(wp0 + ko));
+            w[u][1] = __builtin_nontemporal_load((const u32x4 SK_GLOBAL *)(wp0 + ko + 16));
+            w[u][2] = __builtin_nontemporal_load((const u32x4 SK_GLOBAL *)(wp1 + ko));
+            w[u][3] = __builtin_nontemporal_load((const u32x4 SK_GLOBAL *)(wp1 + ko + 16));
+#pragma unroll
+            for (int mb = 0; mb < RM; ++mb) {
+              av[u][mb][0] = *(const u32x4 SK_GLOBAL *)(ap[mb] + ko);
+              av[u][mb][1] = *(const u32x4 SK_GLOBAL *)(ap[mb] + ko + 16);
             }
-            mma16<DT>(w00, a0, acc[0][mb]);
-            mma16<DT>(w01, a1, acc[0][mb]);
-            mma16<DT>(w10, a0, acc[1][mb]);
-            mma16<DT>(w11, a1, acc[1][mb]);
           }
+#pragma unroll
+          for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int mb = 0; mb < RM; ++mb) {
+              mma16<DT>(w[u][0], av[u][mb][0], acc[0][mb]);
+              mma16<DT>(w[u][1], av[u][mb][1], acc[0][mb]);
+              mma16<DT>(w[u][2], av[u][mb][0], acc[1][mb]);
+              mma16<DT>(w[u][3], av[u][mb][1], acc[1][mb]);
+            }
         }
       }
       // general blocks: ragged K, unaligned operands, gathered activations

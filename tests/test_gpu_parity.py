@@ -1,0 +1,175 @@
+"""GPU parity: the HIP superkernel, called through the C ABI, against the fp64
+CPU oracle on the same seeded inputs.  Tolerances: max |c-ref| / max(|ref|,
+rms(ref)) <= 1e-5 (fp32), 2e-2 (bf16, fp16), plus the summation-order-free
+rounding bound; plans, ordering and launch-mode equivalence are bit-exact."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import paper_1901_10008_amd as sk
+import workloads
+from workloads import Problem
+from oracle import compare, planner as P, reference as R, rounding as Q
+
+import sk_harness as H
+
+pytestmark = pytest.mark.gpu
+
+
+def _sync():
+    torch.cuda.synchronize()
+
+
+def run_all_modes(specs, seed=0, label="", **batch_kw):
+    """Superkernel vs oracle; sequential and index-order plans bit-identical to it."""
+    b = H.Batch(specs, seed=seed, **batch_kw)
+    with b.plan() as plan:
+        # plan parity with the reference planner on the real addresses
+        table, order, first, count = P.plan(specs)
+        assert sk.sk_plan_get_tiles(plan) == table
+        assert sk.sk_plan_get_order(plan) == order
+        sk.sk_launch(plan, H.stream_handle())
+        _sync()
+        worst = H.check_against_oracle(b, label + " superkernel")
+        coalesced = b.all_output_bits()
+        # second launch of the same plan (the queue re-arms itself)
+        b.reset_outputs()
+        sk.sk_launch(plan, H.stream_handle())
+        _sync()
+        for x, y in zip(coalesced, b.all_output_bits()):
+            assert np.array_equal(x, y), label + ": relaunch differs"
+        b.reset_outputs()
+        sk.sk_launch_sequential(plan, H.stream_handle())
+        _sync()
+        for i, (x, y) in enumerate(zip(coalesced, b.all_output_bits())):
+            assert np.array_equal(x, y), f"{label}: sequential differs from coalesced on operator {i}"
+    with b.plan(edf=0) as plan:
+        b.reset_outputs()
+        sk.sk_launch(plan, H.stream_handle())
+        _sync()
+        for i, (x, y) in enumerate(zip(coalesced, b.all_output_bits())):
+            assert np.array_equal(x, y), f"{label}: index-order plan differs on operator {i}"
+    return worst
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3, 4])
+def test_config_matches_oracle(idx):
+    specs = workloads.config(idx, seed=0)
+    worst = run_all_modes(specs, seed=0, label=f"config {idx}")
+    print(f"config {idx}: worst gate error {worst}")
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+def test_configs_in_every_dtype(dtype):
+    # the conv mix and a slice of the low-batch GEMM mix, in each operand type
+    specs = workloads.config(3, seed=1, dtype=dtype)[4:] + workloads.config(2, seed=1, dtype=dtype)[:4]
+    run_all_modes(specs, seed=1, label=f"{dtype}")
+
+
+def g(m, n, k, dtype="bf16", d=math.inf, a=("normal", 1.0), b=("normal", 0.05)):
+    return Problem(op="gemm", dtype=dtype, M=m, N=n, K=k, deadline_ms=d, a_dist=a, b_dist=b)
+
+
+def c(h, w, cin, cout, r, s, ph, pw, dtype="bf16", nb=1, d=math.inf):
+    return Problem(op="conv", dtype=dtype, Nb=nb, H=h, W=w, Cin=cin, Cout=cout, R=r, S=s, pad_h=ph, pad_w=pw,
+                   deadline_ms=d, a_dist=("uniform", 0.0, 1.0), b_dist=("normal", 0.1))
+
+
+RAGGED = [
+    g(1, 5, 3, "f32"), g(1, 1, 1), g(17, 33, 129), g(33, 130, 70, "f16"), g(65, 129, 8), g(200, 300, 100, "f32"),
+    g(16, 1000, 64), g(32, 40, 4096), g(2, 96, 8192, d=1.5), g(7, 100, 2048, "f32", d=0.25), g(3, 515, 520),
+    g(31, 257, 1000, "f16"), g(64, 128, 64), g(128, 128, 128, "f32"), g(129, 130, 136),
+    c(5, 5, 3, 7, 3, 3, 1, 1), c(9, 9, 8, 130, 1, 1, 0, 0, d=0.25), c(13, 11, 16, 40, 3, 3, 1, 1, nb=2),
+    c(6, 6, 4, 4, 3, 1, 0, 0, "f32"), c(4, 4, 8, 8, 1, 1, 1, 1), c(7, 7, 24, 20, 3, 3, 1, 1, "f16"),
+    c(5, 4, 8, 16, 3, 3, 0, 0), c(3, 3, 16, 8, 3, 3, 2, 2), c(10, 10, 5, 6, 3, 3, 1, 1, "f32", nb=3),
+]
+
+
+def test_ragged_shapes_all_paths():
+    run_all_modes(RAGGED, seed=7, label="ragged")
+
+
+def test_misaligned_and_strided_operands():
+    specs = [s for s in RAGGED if s.op == "gemm"]
+    # 2/4-byte offsets break 16-byte alignment (element-wise load/store paths); padded row strides
+    run_all_modes(specs, seed=8, label="misaligned", a_off=4, b_off=4, c_off=4)
+    run_all_modes(specs, seed=9, label="strided", pad_lda=8, pad_ldb=16, pad_ldc=4)
+    run_all_modes(specs, seed=10, label="odd strides", pad_lda=3, pad_ldb=1, pad_ldc=1)
+    convs = [s for s in RAGGED if s.op == "conv"]
+    run_all_modes(convs, seed=11, label="misaligned conv", a_off=4, b_off=4, c_off=4)
+
+
+def test_single_and_empty_plans():
+    run_all_modes([g(1, 64, 64)], seed=3, label="single")
+    with sk.sk_plan_create([], None) as plan:
+        assert sk.sk_plan_grid(plan) == 0
+        sk.sk_launch(plan, H.stream_handle())
+        sk.sk_launch_sequential(plan, H.stream_handle())
+        _sync()
+
+
+def test_small_grid_and_split_modes():
+    # few persistent workgroups: every workgroup walks many tiles through the atomic queue
+    specs = workloads.config(2, seed=5)[:6] + workloads.config(3, seed=0)[2:5]
+    b = H.Batch(specs, seed=5)
+    ref_bits = None
+    for prm in ({"grid_limit": 3}, {"grid_limit": 64}, {}):
+        with b.plan(**prm) as plan:
+            b.reset_outputs()
+            sk.sk_launch(plan, H.stream_handle())
+            _sync()
+            H.check_against_oracle(b, f"grid {prm}")
+            bits = b.all_output_bits()
+            if ref_bits is not None:
+                for x, y in zip(ref_bits, bits):
+                    assert np.array_equal(x, y)
+            ref_bits = bits
+    # tile-size parameters change the reduction split (wk = 1, 2, 4): all within tolerance
+    for prm in ({"tile_bytes_min": 4096, "tile_bytes_max": 4096}, {"tile_bytes_min": 1 << 20, "tile_bytes_max": 1 << 20},
+                {"skinny_max_m": 0}, {"skinny_max_m": 16}):
+        with b.plan(**prm) as plan:
+            assert sk.sk_plan_get_tiles(plan) == P.plan(specs, P.Params(**prm))[0]
+            b.reset_outputs()
+            sk.sk_launch(plan, H.stream_handle())
+            _sync()
+            H.check_against_oracle(b, f"params {prm}")
+
+
+def test_exact_integer_products():
+    # small integers: every product and partial sum is exact in fp32 and bf16, so the result is exact
+    M, N, K = 9, 70, 96
+    A = (np.arange(M * K).reshape(M, K) % 5 - 2).astype(np.float32)
+    B = (np.arange(N * K).reshape(N, K) % 7 - 3).astype(np.float32)
+    want = R.gemm(A, B)
+    for dtype in ("bf16", "f16", "f32"):
+        spec = g(M, N, K, dtype)
+        b = H.Batch([spec], seed=0)
+        bitsA, _ = Q.round_to(dtype, A)
+        bitsB, _ = Q.round_to(dtype, B)
+        b.bufs[0].zero_()
+        b.bufs[0][:M * K] = torch.from_numpy(bitsA.view(np.int32 if dtype == "f32" else np.int16).ravel()).to("cuda")
+        b.bufs[1][:N * K] = torch.from_numpy(bitsB.view(np.int32 if dtype == "f32" else np.int16).ravel()).to("cuda")
+        with b.plan() as plan:
+            sk.sk_launch(plan, H.stream_handle())
+            _sync()
+        assert np.array_equal(b.output(0), want), dtype
+
+
+def test_completion_stamps():
+    specs = workloads.config(5, seed=0)[:24]
+    b = H.Batch(specs, seed=0)
+    with b.plan(stamps=1) as plan:
+        for launch in (sk.sk_launch, sk.sk_launch_sequential, sk.sk_launch):
+            b.reset_outputs()
+            launch(plan, H.stream_handle())
+            _sync()
+            done, start, rate = sk.sk_plan_get_stamps(plan)
+            assert rate > 0 and len(done) == len(specs)
+            lat_ms = [(d - start) / rate for d in done]
+            assert all(0 <= x < 1000 for x in lat_ms), lat_ms
+            H.check_against_oracle(b, "stamps")
+    with b.plan() as plan:
+        with pytest.raises(sk.SkError):
+            sk.sk_plan_get_stamps(plan)

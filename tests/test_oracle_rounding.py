@@ -64,3 +64,15 @@ def test_f32_passthrough():
     x = np.array([1.5, -2.25, 3e-39], dtype=np.float32)
     bits, v = Q.round_to("f32", x)
     assert np.array_equal(v, x) and np.array_equal(Q.bits_to_f32("f32", bits), x)
+
+
+def test_unit_roundoff_of_each_output_format_is_attained_and_not_exceeded():
+    # the bound used by the parity tests: |round(x) - x| <= u |x| with u = 2^-p
+    from oracle import compare
+    g = np.random.default_rng(5)
+    x = np.exp(g.uniform(-3, 3, 200000)).astype(np.float32)
+    for dtype in ("bf16", "f16"):
+        _, v = Q.round_to(dtype, x)
+        rel = np.abs(v.astype(np.float64) - x) / np.abs(x)
+        u = compare._U_OUT[dtype]
+        assert rel.max() <= u and rel.max() > 0.9 * u / (1 + u), (dtype, rel.max(), u)
