@@ -1,0 +1,249 @@
+#!/usr/bin/env python3
+"""Benchmark of the coalesced superkernel on one MI355X.
+
+One step = one sk_launch of the whole operator mix (default: the 256-operator
+mixed GEMM/conv mix with deadlines), inputs resident in HBM, the plan built
+once before the timed region (its cost is reported beside the result).
+Prints ONE JSON line: aggregate TFLOP/s, speedups over one-launch-per-operator
+and over multi-stream launches, fraction of the per-operator roofline, the
+HBM roofline of the superkernel launch, and the CPU oracle as a baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0
+PEAK_FLOPS = {"bf16": 2.5e15, "f16": 2.5e15, "f32": 157.3e12}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=5, help="1..5 (default 5: 256 mixed operators, EDF)")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-baselines", action="store_true", help="skip sequential / multi-stream legs")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--param", action="append", default=[], help="sk_plan_params override name=value")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); --gpus must be 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_1901_10008_amd as sk
+    import workloads
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    specs = workloads.config(args.config, seed=args.seed)
+    name = workloads.config_names()[args.config - 1]
+    tdt = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}
+    A, B, Cs, problems = [], [], [], []
+    for i, s in enumerate(specs):
+        a32, b32 = workloads.draw_device(s, args.seed, i, dev)
+        a = a32.to(tdt[s.dtype]).contiguous()
+        b = b32.to(tdt[s.dtype]).contiguous()
+        del a32, b32
+        c = torch.empty(s.c_shape, dtype=tdt[s.dtype], device=dev)
+        A.append(a)
+        B.append(b)
+        Cs.append(c)
+        problems.append(sk.make_problem(s, a.data_ptr(), b.data_ptr(), c.data_ptr()))
+    torch.cuda.synchronize()
+
+    overrides = {}
+    for kv in args.param:
+        k, v = kv.split("=")
+        overrides[k] = int(v)
+
+    flops = sum(workloads.flops(s) for s in specs)
+    abytes = sum(workloads.algorithmic_bytes(s) for s in specs)
+    t_roof = sum(max(workloads.flops(s) / PEAK_FLOPS[s.dtype], workloads.algorithmic_bytes(s) / (PEAK_HBM_GBS * 1e9))
+                 for s in specs)
+    t_lb = max(sum(workloads.flops(s) / PEAK_FLOPS[s.dtype] for s in specs), abytes / (PEAK_HBM_GBS * 1e9))
+
+    stream = torch.cuda.current_stream().cuda_stream
+
+    # ---- plan cost (host planning + upload), not part of the timed steps ----
+    t0 = time.perf_counter()
+    reps = 5
+    for _ in range(reps):
+        sk.sk_plan_create(problems, sk.sk_plan_params_default(**overrides)).close()
+    plan_ms = (time.perf_counter() - t0) / reps * 1e3
+
+    plan = sk.sk_plan_create(problems, sk.sk_plan_params_default(**overrides))
+    ntiles = sk.sk_plan_num_tiles(plan)
+
+    def timed(fn, steps, warmup):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        t0 = time.perf_counter()
+        for e0, e1 in evs:
+            e0.record()
+            fn()
+            e1.record()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) / steps
+        dev_ms = [e0.elapsed_time(e1) for e0, e1 in evs]
+        return wall * 1e3, dev_ms
+
+    wall_ms, dev_ms = timed(lambda: sk.sk_launch(plan, stream), args.steps, args.warmup)
+    kern_ms = sum(dev_ms) / len(dev_ms)
+    value = flops / (wall_ms * 1e-3) / 1e12
+
+    out = {
+        "metric": "aggregate TFLOP/s of the superkernel (one launch for all operators)",
+        "value": round(value, 3),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(wall_ms, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": specs[0].dtype if len({s.dtype for s in specs}) == 1 else "mixed",
+        "data": "synthetic",
+        "config": {"workload": name, "operators": len(specs), "tiles": ntiles, "grid": sk.sk_plan_grid(plan),
+                   "seed": args.seed, "gflop": round(flops / 1e9, 3), "algorithmic_MB": round(abytes / 1e6, 2),
+                   "params": overrides},
+        "kernel_ms": {"mean": round(kern_ms, 5), "min": round(min(dev_ms), 5),
+                      "median": round(sorted(dev_ms)[len(dev_ms) // 2], 5)},
+        "plan_ms": round(plan_ms, 4),
+        "value_incl_plan": round(flops / ((wall_ms + plan_ms) * 1e-3) / 1e12, 3),
+        "per_problem_roofline": {"t_roof_ms": round(t_roof * 1e3, 5), "t_overlap_bound_ms": round(t_lb * 1e3, 5),
+                                 "roofline_tflops": round(flops / t_roof / 1e12, 2),
+                                 "frac": round(t_roof / (kern_ms * 1e-3), 4)},
+        "roofline": {"bound": "hbm", "achieved": round(abytes / (kern_ms * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS,
+                     "unit": "GB/s", "frac": round(abytes / (kern_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                     "traffic": None},
+    }
+
+    if not args.no_baselines:
+        seq_steps = max(3, args.steps // 3)
+        seq_wall, seq_dev = timed(lambda: sk.sk_launch_sequential(plan, stream), seq_steps, 1)
+        out["sequential"] = {"ms": round(seq_wall, 5), "tflops": round(flops / (seq_wall * 1e-3) / 1e12, 3),
+                             "speedup": round(seq_wall / wall_ms, 3)}
+
+        # multi-stream baseline: one single-operator plan per operator, round-robin over <= 32 streams
+        nstreams = min(32, len(specs))
+        streams = [torch.cuda.Stream(device=dev) for _ in range(nstreams)]
+        singles = [sk.sk_plan_create([p], sk.sk_plan_params_default(**overrides)) for p in problems]
+        cur = torch.cuda.current_stream()
+
+        def multi():
+            fork = torch.cuda.Event()
+            fork.record(cur)
+            for st in streams:
+                st.wait_event(fork)
+            for i, sp in enumerate(singles):
+                sk.sk_launch(sp, streams[i % nstreams].cuda_stream)
+            for st in streams:
+                ev = torch.cuda.Event()
+                ev.record(st)
+                cur.wait_event(ev)
+
+        ms_wall, _ = timed(multi, seq_steps, 1)
+        out["multistream"] = {"ms": round(ms_wall, 5), "streams": nstreams,
+                              "tflops": round(flops / (ms_wall * 1e-3) / 1e12, 3),
+                              "speedup": round(ms_wall / wall_ms, 3)}
+        for sp in singles:
+            sp.close()
+
+        # deadline-met fraction (only meaningful when the mix has deadlines)
+        if any(math.isfinite(s.deadline_ms) for s in specs):
+            res = {}
+            for label, prm, launch in (("superkernel_edf", {"edf": 1}, sk.sk_launch),
+                                       ("superkernel_index_order", {"edf": 0}, sk.sk_launch),
+                                       ("sequential", {"edf": 1}, sk.sk_launch_sequential)):
+                p2 = sk.sk_plan_create(problems, sk.sk_plan_params_default(stamps=1, **{**overrides, **prm}))
+                launch(p2, stream)
+                torch.cuda.synchronize()
+                launch(p2, stream)
+                torch.cuda.synchronize()
+                done, start, rate = sk.sk_plan_get_stamps(p2)
+                lat = [(d - start) / rate for d in done]
+                met = sum(1 for l, s in zip(lat, specs) if l <= s.deadline_ms)
+                res[label] = {"met_fraction": round(met / len(specs), 4), "max_latency_ms": round(max(lat), 4)}
+                p2.close()
+            out["deadlines"] = res
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(specs, args.seed, args.cpu_seconds)
+
+    plan.close()
+    print(json.dumps(out))
+
+
+def cpu_baseline(specs, seed, target_s):
+    """The fp64 oracle, as it stands, on the host cores, over a bounded sample of the same mix."""
+    import numpy as np
+
+    import workloads
+    from oracle import reference as R, rounding as Q
+
+    cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "0") or 0) or (os.cpu_count() or 1))
+    R.set_threads(cores)
+    # calibrate on a small GEMM, then take operators in submission order until the budget is used
+    a = np.ones((8, 2048), dtype=np.float32)
+    b = np.ones((512, 2048), dtype=np.float32)
+    R.gemm(a, b)
+    t0 = time.perf_counter()
+    R.gemm(a, b)
+    rate = 2 * 8 * 512 * 2048 / max(time.perf_counter() - t0, 1e-6)
+    budget = rate * target_s
+    chosen, acc = [], 0
+    for i, s in enumerate(specs):
+        f = workloads.flops(s)
+        if acc + f > budget and chosen:
+            continue
+        if f > budget:
+            continue
+        chosen.append(i)
+        acc += f
+        if acc > 0.9 * budget:
+            break
+    if not chosen:
+        chosen = [min(range(len(specs)), key=lambda i: workloads.flops(specs[i]))]
+        acc = workloads.flops(specs[chosen[0]])
+    inputs = []
+    for i in chosen:
+        s = specs[i]
+        a32, b32 = workloads.draw_host(s, seed, i)
+        inputs.append((s, Q.round_to(s.dtype, a32)[1], Q.round_to(s.dtype, b32)[1]))
+    t0 = time.perf_counter()
+    for s, av, bv in inputs:
+        if s.op == "gemm":
+            R.gemm(av, bv)
+        else:
+            R.conv2d_nhwc(av, bv, s.pad_h, s.pad_w)
+    dt = time.perf_counter() - t0
+    return {"value": round(acc / dt / 1e12, 6), "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "sample": f"{len(chosen)} of {len(specs)} operators of the same mix in submission order "
+                      f"({acc / 1e9:.2f} GFLOP, {dt:.1f} s, fp64 naive loops, OpenMP over output rows)"}
+
+
+if __name__ == "__main__":
+    main()

@@ -97,13 +97,13 @@ typedef struct {
   int32_t stamps;         /* 1: record a completion timestamp per operator (small cost)      */
   int32_t host_only;      /* 1: plan on the host only, touch no device (launches then fail)  */
   int32_t skinny_max_m;   /* operators with at most this many rows stream their weights      */
-                          /* straight to registers ("skinny" classes); 1..32, default 32     */
+                          /* straight to registers ("skinny" classes); 0..64, default 64     */
   int64_t tile_bytes_max; /* skinny tiles: upper/lower clamp of the target weight bytes per  */
   int64_t tile_bytes_min; /* tile; the target is sum(weight bytes) / balance_div             */
   int32_t balance_div;    /* default 2048                                                    */
   int32_t max_groups;     /* cap on 32-row weight groups per skinny tile, default 256        */
   int32_t grid_limit;     /* upper bound on persistent workgroups per launch;                */
-                          /* 0 = 2 per compute unit of the current device                    */
+                          /* 0 = 4 per compute unit of the current device                    */
   int32_t reserved;
 } sk_plan_params;
 
@@ -114,7 +114,7 @@ typedef struct {
  */
 typedef struct {
   uint32_t problem;     /* index of the operator in the sk_problem array                    */
-  uint16_t cls;         /* tile class: 0..5 skinny (3*(rm-1) + log2(wk)), 6: 64x128, 7: 128x128 */
+  uint16_t cls;         /* tile class: 0, 3, 6 skinny (1, 2, 4 blocks of 16 rows), 9: 64x128 LDS tile */
   uint8_t ks_idx;       /* which reduction slice of the output rectangle this record is     */
   uint8_t S;            /* number of reduction slices of the rectangle (1 = not split)      */
   uint32_t m0, n0;      /* origin of the output rectangle in the operator's [Mg,Ng] GEMM view */

@@ -37,20 +37,17 @@ RECORD = struct.Struct("<IHBBIIHHIII")  # 32 bytes
 assert RECORD.size == 32
 
 # tile classes
-#   0..5  "skinny": all rows of a small-M operator against a block of 32*G weight
-#         rows; the four waves of a workgroup split the reduction wk ways.
-#         id = 3*(rm-1) + {1:0, 2:1, 4:2}[wk],  rm = 1 (Mg<=16) or 2 (Mg<=32)
-#   6     64 x 128 output tile staged through LDS
-#   7     128 x 128 output tile staged through LDS
-CLS_TILE_64x128 = 6
-CLS_TILE_128x128 = 7
-_WK_CODE = {1: 0, 2: 1, 4: 2}
+#   0, 3, 6  "skinny": all rows of a small-M operator (rm = 1, 2 or 4 blocks of 16 rows)
+#         against a block of 32*G weight rows; long reductions are cut into S slices
+#         that different workgroups take.   id = 3*log2(rm)
+#   9     64 x 128 output tile staged through LDS
+CLS_TILE_64x128 = 9
 
 
 @dataclass
 class Params:
     edf: int = 1
-    skinny_max_m: int = 32          # <= 32
+    skinny_max_m: int = 64          # <= 64
     tile_bytes_max: int = 256 * 1024
     tile_bytes_min: int = 32 * 1024
     balance_div: int = 2048
@@ -88,22 +85,26 @@ def target_tile_bytes(problems: Sequence, prm: Params) -> int:
 
 
 def tiling(p, T: int, prm: Params):
-    """(cls, BM, BN) for one operator given the target bytes per skinny tile."""
+    """(cls, BM, BN, S, slice_len) for one operator given the target bytes per skinny tile."""
     mg, ng, kg = canonical(p)
     es = ELEM_SIZE[p.dtype]
     if mg <= prm.skinny_max_m:
-        rm = 1 if mg <= 16 else 2
+        rm_code = 0 if mg <= 16 else (1 if mg <= 32 else 2)
         gb = 32 * kg * es
-        if gb >= T:
-            wk, G = 4, 1
-        elif 2 * gb >= T:
-            wk, G = 2, 2
+        if 4 * gb <= T:
+            G = min(prm.max_groups, 4 * max(1, T // (4 * gb)))
+            S, slice_len = 1, kg
         else:
-            wk, G = 1, min(prm.max_groups, 4 * max(1, T // (4 * gb)))
-        return 3 * (rm - 1) + _WK_CODE[wk], mg, 32 * G
-    if mg <= 64:
-        return CLS_TILE_64x128, 64, 128
-    return CLS_TILE_128x128, 128, 128
+            # four groups already exceed the target: cut the reduction into slices of whole chunks
+            G = 4
+            chunk = (16384 // (16 << rm_code)) // es
+            nchunks = -(-kg // chunk)
+            want = min(nchunks, -(-4 * gb // T), 255)
+            per = -(-nchunks // want)
+            S = -(-nchunks // per)
+            slice_len = per * chunk
+        return 3 * rm_code, mg, 32 * G, S, slice_len
+    return CLS_TILE_64x128, 64, 128, 1, kg
 
 
 def plan(problems: Sequence, prm: Params | None = None):
@@ -119,14 +120,14 @@ def plan(problems: Sequence, prm: Params | None = None):
     for i in ordr:
         p = problems[i]
         mg, ng, kg = canonical(p)
-        cls, BM, BN = tiling(p, T, prm)
+        cls, BM, BN, S, slice_len = tiling(p, T, prm)
         first[i] = len(recs)
         for m0 in range(0, mg, BM):
             for n0 in range(0, ng, BN):
-                S = 1
                 for ks in range(S):
+                    k0 = ks * slice_len
                     recs.append(RECORD.pack(i, cls, ks, S, m0, n0, min(BM, mg - m0), min(BN, ng - n0),
-                                            0, kg, out_id))
+                                            k0, min(slice_len, kg - k0), out_id))
                 out_id += 1
         count[i] = len(recs) - first[i]
     return b"".join(recs), ordr, first, count

@@ -8,14 +8,15 @@
 // time one 128-bit load and one MFMA operand (8 halves or 4 floats of K).
 //
 // Two families of tile code:
-//   * skinny (Mg <= 32): weights go HBM -> registers -> MFMA directly; the
+//   * skinny (Mg <= 64): weights go HBM -> registers -> MFMA directly; the
 //     weight rows are the MFMA's row operand and the few activation rows its
 //     column operand, so a lane ends up with four consecutive output columns.
-//     The four waves of a workgroup either take different 32-row weight groups
-//     or split the reduction (wk = 2, 4) and combine through LDS in fixed order.
-//   * LDS tiles (64x128, 128x128): classic staged GEMM, global -> registers ->
-//     LDS -> 32x32 MFMA; the activation operand may be gathered on the fly from
-//     an NHWC image (implicit GEMM for convolutions).
+//     Activations are staged through LDS.  The four waves of a workgroup take
+//     different 32-row weight groups; long reductions are split over several
+//     workgroups whose partial sums the last one to finish adds in fixed order.
+//   * LDS tiles (64x128): classic staged GEMM, global -> registers -> LDS ->
+//     32x32 MFMA; the activation operand may be gathered on the fly from an
+//     NHWC image (implicit GEMM for convolutions).
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -46,7 +47,7 @@ __device__ __forceinline__ T SK_GLOBAL *as_global_mut(void *p) {
 
 constexpr int WG_THREADS = 256;
 constexpr int LDS_ROW = 144;                  // 128 bytes of K + 16 bytes of padding (bank spread)
-constexpr int LDS_TILE_BYTES = 256 * LDS_ROW;  // 128 activation rows + 128 weight rows
+constexpr int LDS_TILE_BYTES = 256 * LDS_ROW;  // 36 KB per workgroup: four workgroups share a CU's 160 KB
 
 struct KernelArgs {
   uint32_t *counters;   // [0] tiles handed out beyond the first grid-full, [1] finished workgroups
@@ -56,6 +57,9 @@ struct KernelArgs {
   uint32_t tile_begin, tile_end;
   uint32_t dynamic;      // 1: tiles come from the atomic counter; 0: static stride over the range
   uint32_t write_start;  // 1: workgroup 0 records the start tick
+  f32x4 *ws;             // split-K partial sums
+  const uint32_t *ws_off;
+  uint32_t *arrive;
 };
 
 // ---------------------------------------------------------------------------
@@ -120,25 +124,6 @@ __device__ __forceinline__ void store4(void *C, int64_t row_off, int n, int n_en
   }
 }
 
-// One 16-byte piece (elements k .. k+CE-1 of a row) read element by element
-// with a bound on k: the path for unaligned operands and ragged K.
-template <int ES>
-__device__ __forceinline__ u32x4 load_piece_scalar(const void *base, int64_t off, int k, int Kg) {
-  u32x4 v = {0u, 0u, 0u, 0u};
-  if constexpr (ES == 4) {
-    const uint32_t SK_GLOBAL *p = as_global<uint32_t>(base) + off;
-#pragma unroll
-    for (int e = 0; e < 4; ++e)
-      if (k + e < Kg) v[e] = p[e];
-  } else {
-    const uint16_t SK_GLOBAL *p = as_global<uint16_t>(base) + off;
-#pragma unroll
-    for (int e = 0; e < 8; ++e)
-      if (k + e < Kg) v[e >> 1] |= (uint32_t)p[e] << (16 * (e & 1));
-  }
-  return v;
-}
-
 template <int ES, bool NT>
 __device__ __forceinline__ u32x4 load_piece_vec(const void *base, int64_t off) {
   const u32x4 SK_GLOBAL *p = (const u32x4 SK_GLOBAL *)(as_global<char>(base) + off * ES);
@@ -148,14 +133,30 @@ __device__ __forceinline__ u32x4 load_piece_vec(const void *base, int64_t off) {
     return *p;
 }
 
-// Weight piece: row n of Bs[Ng,Kg], elements k .. k+CE-1 (zero beyond Kg).
+// The MFMA paths below require both operands to be readable in aligned 16-byte
+// pieces (FLAG_VEC_A and FLAG_VEC_B: 16-byte aligned bases and row strides, Kg
+// and, for a convolution, Cin multiples of a piece).  Everything else goes
+// through run_generic.
+
+// Loads in the MFMA paths are never placed under a branch (a conditional load makes the
+// compiler wait for it at the end of the branch, which serialises the loads of a stage)
+// and their values are not touched before they are consumed (a select right behind a
+// load makes the wave wait for it at once).  So: addresses are clamped to a readable
+// place, activation pieces that must read as zero (beyond K, in the padding, rows past
+// Mg) are zeroed when they are written to LDS, and weight pieces are never zeroed at
+// all: a weight piece beyond K only ever meets an activation piece that is zero.
+__device__ __forceinline__ u32x4 keep_if(bool ok, const u32x4 &v) {
+  u32x4 r;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) r[i] = ok ? v[i] : 0u;
+  return r;
+}
+
+// Weight piece: row n of Bs[Ng,Kg], elements k .. k+CE-1; where !ok the start of the
+// same row is read instead (finite data that will be multiplied by zeros).
 template <int ES, bool NT>
-__device__ __forceinline__ u32x4 fetch_B(const DevProblem &P, int64_t row_off, int k) {
-  if (P.flags & FLAG_VEC_B) {
-    if (k >= P.Kg) return u32x4{0u, 0u, 0u, 0u};
-    return load_piece_vec<ES, NT>(P.B, row_off + k);
-  }
-  return load_piece_scalar<ES>(P.B, row_off + k, k, P.Kg);
+__device__ __forceinline__ u32x4 fetch_B(const DevProblem &P, int64_t row_off, int k, bool ok) {
+  return load_piece_vec<ES, NT>(P.B, row_off + (ok ? k : 0));
 }
 
 // Where row m of the activation operand starts.
@@ -194,30 +195,26 @@ __device__ __forceinline__ bool patch_offset(const DevProblem &P, const RowA &ro
   return (unsigned)h < (unsigned)P.H && (unsigned)w < (unsigned)P.W;
 }
 
-// Activation piece: elements k .. k+CE-1 of row `row` of A' (zero beyond Kg and in the padding).
+// Activation piece: elements k .. k+CE-1 of row `row` of A'.  `ok` comes back false where
+// the piece must read as zero (caller said so, or the tap falls into the padding); the
+// caller zeroes it with keep_if when it writes the piece to LDS.
 template <int ES>
-__device__ __forceinline__ u32x4 fetch_A(const DevProblem &P, const RowA &row, int k) {
-  constexpr int CE = 16 / ES;
-  if (P.flags & FLAG_VEC_A) {
-    if (k >= P.Kg) return u32x4{0u, 0u, 0u, 0u};
-    if (!P.gather) return load_piece_vec<ES, false>(P.A, row.base + k);
-    int64_t off;
-    if (!patch_offset(P, row, k, off)) return u32x4{0u, 0u, 0u, 0u};
-    return load_piece_vec<ES, false>(P.A, off);
+__device__ __forceinline__ u32x4 fetch_A(const DevProblem &P, const RowA &row, int k, bool &ok) {
+  int64_t off = row.base + k;
+  if (P.gather) ok = patch_offset(P, row, k, off) && ok;
+  return load_piece_vec<ES, false>(P.A, ok ? off : 0);
+}
+
+// Single elements as float, for run_generic.
+template <int DT>
+__device__ __forceinline__ float load_elem(const void *base, int64_t off) {
+  if constexpr (DT == SK_F32) {
+    return as_global<float>(base)[off];
+  } else if constexpr (DT == SK_BF16) {
+    return __builtin_bit_cast(float, (uint32_t)as_global<uint16_t>(base)[off] << 16);
+  } else {
+    return (float)as_global<_Float16>(base)[off];
   }
-  if (!P.gather) return load_piece_scalar<ES>(P.A, row.base + k, k, P.Kg);
-  u32x4 v = {0u, 0u, 0u, 0u};
-#pragma unroll
-  for (int e = 0; e < CE; ++e) {
-    int64_t off;
-    if (k + e < P.Kg && patch_offset(P, row, k + e, off)) {
-      if constexpr (ES == 4)
-        v[e] = as_global<uint32_t>(P.A)[off];
-      else
-        v[e >> 1] |= (uint32_t)as_global<uint16_t>(P.A)[off] << (16 * (e & 1));
-    }
-  }
-  return v;
 }
 
 // ---------------------------------------------------------------------------
@@ -258,49 +255,91 @@ __device__ __forceinline__ void mma32(const u32x4 &a, const u32x4 &b, f32x16 &c)
 // ---------------------------------------------------------------------------
 // skinny tiles
 // ---------------------------------------------------------------------------
-// A tile is all Mg (<= 16*RM) rows against n_len weight rows, processed in
-// groups of 32 weight rows.  Within a reduction block of 8 pieces (128 bytes
-// per row) lane slot q = lane/16 owns pieces 2q and 2q+1, so the four slots
-// of a row read one full 128-byte line between them.
+// A tile is all Mg (<= 16*RM) activation rows against n_len weight rows and a
+// slice [k0, k0+k_len) of the reduction.  The four waves of the workgroup take
+// different groups of 32 weight rows (two 16-row MFMA blocks per wave).
+//
+// Weights never touch LDS: each wave streams its rows HBM -> registers -> MFMA
+// through a ring of NB reduction blocks (128 bytes per row each), so NB-1
+// blocks of loads stay in flight while one is multiplied, and every wave walks
+// along its rows in consecutive 128-byte steps.  Within a block lane slot
+// q = lane/16 owns pieces 2q and 2q+1.
+//
+// The activations (tiny, and gathered from an image for a convolution) are
+// staged once per workgroup through LDS in chunks of SKINNY_CHUNK_BYTES,
+// double-buffered, one barrier per chunk.
+//
+// Long reductions are cut into S slices that different workgroups take
+// (records with S > 1).  Each slice leaves its fp32 partial sums in a
+// workspace in register layout; the workgroup that arrives last adds the S
+// partials in slice order (so the result does not depend on arrival order)
+// and writes C.
+constexpr int SKINNY_CHUNK_BYTES = 16384;
+
+struct SplitK {
+  f32x4 *ws;                // partial sums of all split output rectangles
+  const uint32_t *ws_off;   // per out_tile_id: offset of its partials in ws, in f32x4 units
+  uint32_t *arrive;         // per out_tile_id: slices that have delivered (re-armed by the last one)
+};
+
 template <int DT, int RM>
-__device__ __forceinline__ void run_skinny(const DevProblem &P, const sk_tile &T, int wk_log2, unsigned char *lds) {
+__device__ __forceinline__ void run_skinny(const DevProblem &P, const sk_tile &T, const SplitK &sp,
+                                           unsigned char *lds, uint32_t *s_flag) {
   constexpr int ES = Elem<DT>::ES;
   constexpr int CE = 16 / ES;
-  constexpr int KB = 8 * CE;  // reduction elements per block
+  constexpr int KB = 8 * CE;                        // reduction elements per block (128 bytes)
+  constexpr int ROWS = 16 * RM;                     // activation rows held in LDS
+  constexpr int ROWB = SKINNY_CHUNK_BYTES / ROWS;   // bytes of K per row and chunk
+  constexpr int LROW = ROWB + 16;                   // padded LDS row (bank spread)
+  constexpr int BPC_LOG2 = RM == 1 ? 3 : (RM == 2 ? 2 : 1);
+  constexpr int BPC = 1 << BPC_LOG2;                // blocks per chunk: 8, 4, 2
+  constexpr int PPR = ROWB / 16;                    // pieces per row and chunk
+  constexpr int BUF = ROWS * LROW;                  // bytes per LDS buffer
+  constexpr int NB = RM == 4 ? 2 : 3;               // ring slots (weight blocks per wave)
+  static_assert(ROWB == BPC * 128, "chunk geometry");
+  static_assert(2 * BUF <= LDS_TILE_BYTES, "activation chunks do not fit");
 
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps its branches scalar
+  const int lane = tid & 63;
   const int r16 = lane & 15, q = lane >> 4;
-  const int wk = 1 << wk_log2;
-  const int kpart = wave & (wk - 1);
-  const int rowlane = wave >> wk_log2;
-  const int nrowlanes = 4 >> wk_log2;
 
   const int n_end = (int)T.n0 + (int)T.n_len;
   const int ngroups = ((int)T.n_len + 31) >> 5;
-  const int iters = (ngroups + nrowlanes - 1) / nrowlanes;
+  const int iters = (ngroups + 3) >> 2;
 
-  // reduction range of this wave, in whole blocks
-  const int kblocks = ((int)T.k_len + KB - 1) / KB;
-  const int per = (kblocks + wk - 1) >> wk_log2;
-  const int k_lo = (int)T.k0 + kpart * per * KB;
-  int k_hi = k_lo + per * KB;
-  const int k_stop = (int)T.k0 + (int)T.k_len;
-  if (k_hi > k_stop) k_hi = k_stop;
+  const int k0 = (int)T.k0, k_stop = (int)T.k0 + (int)T.k_len;
+  const int nblocks = ((int)T.k_len + KB - 1) / KB;
+  const int nchunks = (nblocks + BPC - 1) >> BPC_LOG2;
+  const int nslots = nchunks << BPC_LOG2;  // block slots per wave (blocks past the end read as zero)
 
-  // activation rows of this lane
-  RowA rowa[RM];
-  bool m_ok[RM];
+  // staging map: thread -> four consecutive pieces (64 bytes) of one activation row
+  constexpr int TPR = PPR / 4;  // threads per row
+  const int s_row = tid / TPR;
+  const int s_piece = (tid % TPR) * 4;
+  const bool s_ok = s_row < P.Mg;
+  const RowA srow = row_of(P, s_ok ? s_row : 0);
+  const int s_lds = s_row * LROW + s_piece * 16;
+  u32x4 ar[4];
+  bool ar_ok[4];
+  auto stage_load = [&](int c) {
+    const int k = k0 + ((c << BPC_LOG2) * 8 + s_piece) * CE;
 #pragma unroll
-  for (int mb = 0; mb < RM; ++mb) {
-    const int m = mb * 16 + r16;
-    m_ok[mb] = m < P.Mg;
-    rowa[mb] = row_of(P, m_ok[mb] ? m : 0);
-  }
-  const bool fast = (P.flags & FLAG_VEC_A) && (P.flags & FLAG_VEC_B) && !P.gather;
+    for (int i = 0; i < 4; ++i) {
+      ar_ok[i] = s_ok && k + i * CE < k_stop;
+      ar[i] = fetch_A<ES>(P, srow, k + i * CE, ar_ok[i]);
+    }
+  };
+  auto stage_store = [&](int c) {
+    unsigned char *base = lds + (c & 1) * BUF + s_lds;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) *(u32x4 *)(base + i * 16) = keep_if(ar_ok[i], ar[i]);
+  };
+
   const bool vec_c = (P.flags & FLAG_VEC_C) != 0;
 
   for (int it = 0; it < iters; ++it) {
-    const int g = it * nrowlanes + rowlane;
+    const int g = it * 4 + wave;
     const bool active = g < ngroups;
     const int n_base = (int)T.n0 + g * 32;
 
@@ -310,99 +349,100 @@ __device__ __forceinline__ void run_skinny(const DevProblem &P, const sk_tile &T
 #pragma unroll
       for (int mb = 0; mb < RM; ++mb) acc[rb][mb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    if (active) {
-      int64_t wrow[2];
+    int64_t wrow[2];
 #pragma unroll
-      for (int rb = 0; rb < 2; ++rb) {
-        int n = n_base + rb * 16 + r16;
-        if (n >= n_end) n = n_end - 1;  // rows past the edge repeat the last row; never stored
-        wrow[rb] = (int64_t)n * P.ldb;
-      }
-      int k = k_lo;
-      if (fast) {
-        // whole blocks, aligned operands, plain row-major activations: no predicates at all.
-        // Activation rows past Mg repeat row 0; their output columns are never stored.
-        const char SK_GLOBAL *wp0 = as_global<char>(P.B) + (wrow[0] + q * 2 * CE) * ES;
-        const char SK_GLOBAL *wp1 = as_global<char>(P.B) + (wrow[1] + q * 2 * CE) * ES;
-        const char SK_GLOBAL *ap[RM];
+    for (int rb = 0; rb < 2; ++rb) {
+      int n = n_base + rb * 16 + r16;
+      if (n >= n_end) n = n_end - 1;  // rows past the edge repeat the last row; never stored
+      wrow[rb] = (int64_t)n * P.ldb;
+    }
+    // The loads are unconditional (see fetch_B): blocks past the end, and waves without a
+    // weight group, re-read the start of a row instead, so that the number of loads in
+    // flight at every point of the loop is the same on every path and the waits stay exact.
+    auto load_w = [&](int i, u32x4(&w)[4]) {
+      const int k = k0 + i * KB + q * 2 * CE;
+      const bool in0 = active && k < k_stop, in1 = active && k + CE < k_stop;
+      w[0] = fetch_B<ES, true>(P, wrow[0], k, in0);
+      w[1] = fetch_B<ES, true>(P, wrow[0], k + CE, in1);
+      w[2] = fetch_B<ES, true>(P, wrow[1], k, in0);
+      w[3] = fetch_B<ES, true>(P, wrow[1], k + CE, in1);
+    };
+
+    const bool restage = it == 0 || nchunks > 1;
+    if (restage) {
+      if (it > 0) __syncthreads();  // the previous groups' readers are done with the buffers
+      stage_load(0);
+    }
+    u32x4 w[NB][4];
 #pragma unroll
-        for (int mb = 0; mb < RM; ++mb) ap[mb] = as_global<char>(P.A) + (rowa[mb].base + q * 2 * CE) * ES;
-        constexpr int U = 2;  // blocks per trip: all loads of a trip are issued before its first MFMA
-        const int k_full = k_lo + ((k_hi - k_lo) / (U * KB)) * (U * KB);
-        for (; k < k_full; k += U * KB) {
-          u32x4 w[U][4], av[U][RM][2];
+    for (int u = 0; u < NB - 1; ++u) load_w(u, w[u]);
+
+    for (int i0 = 0; i0 < nslots; i0 += NB) {
 #pragma unroll
-          for (int u = 0; u < U; ++u) {
-            const int64_t ko = (int64_t)(k + u * KB) * ES;
-            w[u][0] = __builtin_nontemporal_load((const u32x4 SK_GLOBAL *)(wp0 + ko));
-            w[u][1] = __builtin_nontemporal_load((const u32x4 SK_GLOBAL *)(wp0 + ko + 16));
-            w[u][2] = __builtin_nontemporal_load((const u32x4 SK_GLOBAL *)(wp1 + ko));
-            w[u][3] = __builtin_nontemporal_load((const u32x4 SK_GLOBAL *)(wp1 + ko + 16));
-#pragma unroll
-            for (int mb = 0; mb < RM; ++mb) {
-              av[u][mb][0] = *(const u32x4 SK_GLOBAL *)(ap[mb] + ko);
-              av[u][mb][1] = *(const u32x4 SK_GLOBAL *)(ap[mb] + ko + 16);
-            }
-          }
-#pragma unroll
-          for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int mb = 0; mb < RM; ++mb) {
-              mma16<DT>(w[u][0], av[u][mb][0], acc[0][mb]);
-              mma16<DT>(w[u][1], av[u][mb][1], acc[0][mb]);
-              mma16<DT>(w[u][2], av[u][mb][0], acc[1][mb]);
-              mma16<DT>(w[u][3], av[u][mb][1], acc[1][mb]);
-            }
+      for (int u = 0; u < NB; ++u) {
+        const int i = i0 + u;
+        const int c = i >> BPC_LOG2;
+        if (restage && i < nslots && (i & (BPC - 1)) == 0) {
+          // first block of chunk c: publish it, then start fetching the next chunk
+          stage_store(c);
+          __syncthreads();
+          if (c + 1 < nchunks) stage_load(c + 1);
         }
-      }
-      // general blocks: ragged K, unaligned operands, gathered activations
-      for (; k < k_hi; k += KB) {
-        const int kk = k + q * 2 * CE;
-        u32x4 w[2][2];
+        load_w(i + NB - 1, w[(u + NB - 1) % NB]);
+        if (active && i < nslots) {
+          const unsigned char *abase = lds + (c & 1) * BUF + (i & (BPC - 1)) * 128 + q * 32 + r16 * LROW;
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
-          w[rb][0] = fetch_B<ES, true>(P, wrow[rb], kk);
-          w[rb][1] = fetch_B<ES, true>(P, wrow[rb], kk + CE);
-        }
-#pragma unroll
-        for (int mb = 0; mb < RM; ++mb) {
-          u32x4 a0 = {0u, 0u, 0u, 0u}, a1 = {0u, 0u, 0u, 0u};
-          if (m_ok[mb]) {
-            a0 = fetch_A<ES>(P, rowa[mb], kk);
-            a1 = fetch_A<ES>(P, rowa[mb], kk + CE);
+          for (int mb = 0; mb < RM; ++mb) {
+            const u32x4 a0 = *(const u32x4 *)(abase + mb * 16 * LROW);
+            const u32x4 a1 = *(const u32x4 *)(abase + mb * 16 * LROW + 16);
+            mma16<DT>(w[u][0], a0, acc[0][mb]);
+            mma16<DT>(w[u][1], a1, acc[0][mb]);
+            mma16<DT>(w[u][2], a0, acc[1][mb]);
+            mma16<DT>(w[u][3], a1, acc[1][mb]);
           }
-          mma16<DT>(w[0][0], a0, acc[0][mb]);
-          mma16<DT>(w[0][1], a1, acc[0][mb]);
-          mma16<DT>(w[1][0], a0, acc[1][mb]);
-          mma16<DT>(w[1][1], a1, acc[1][mb]);
         }
       }
     }
 
-    if (wk > 1) {
-      // combine the reduction parts in fixed order: ((p0 + p1) + p2) + p3
-      f32x4 *part = (f32x4 *)lds;  // [wave][2*RM][64 lanes]
-      if (kpart != 0) {
+    bool finish = true;
+    if (T.S > 1) {
+      // deliver this slice's partial sums; the last slice to arrive adds all of them in slice order
+      // (split rectangles have at most four weight groups, so this loop runs once for them)
+      f32x4 *mine = sp.ws + sp.ws_off[T.out_tile_id];
+      const int slot = (wave * 2 * RM) * 64 + lane;
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int mb = 0; mb < RM; ++mb)
+          mine[(size_t)T.ks_idx * (4 * 2 * RM * 64) + slot + (rb * RM + mb) * 64] = acc[rb][mb];
+      __syncthreads();
+      if (tid == 0) {
+        // release our partials / acquire the others' at device scope
+        const uint32_t prev =
+            __hip_atomic_fetch_add(&sp.arrive[T.out_tile_id], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        *s_flag = prev;
+      }
+      __syncthreads();
+      const uint32_t prev = *s_flag;
+      finish = prev == (uint32_t)T.S - 1;
+      if (finish) {
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-          for (int mb = 0; mb < RM; ++mb) part[(wave * 2 * RM + rb * RM + mb) * 64 + lane] = acc[rb][mb];
-      }
-      __syncthreads();
-      if (kpart == 0) {
-        for (int p = 1; p < wk; ++p) {
+          for (int mb = 0; mb < RM; ++mb) acc[rb][mb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int s2 = 0; s2 < T.S; ++s2) {
 #pragma unroll
           for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-            for (int mb = 0; mb < RM; ++mb) {
-              const f32x4 o = part[((wave + p) * 2 * RM + rb * RM + mb) * 64 + lane];
-              acc[rb][mb] += o;
-            }
+            for (int mb = 0; mb < RM; ++mb)
+              acc[rb][mb] += mine[(size_t)s2 * (4 * 2 * RM * 64) + slot + (rb * RM + mb) * 64];
         }
+        if (tid == 0) sp.arrive[T.out_tile_id] = 0u;  // re-arm for the next launch
       }
     }
 
-    if (active && kpart == 0) {
+    if (finish && active) {
       // lane holds, per (rb, mb): row m = mb*16 + lane%16, columns n_base + rb*16 + (lane/16)*4 + 0..3
 #pragma unroll
       for (int mb = 0; mb < RM; ++mb) {
@@ -417,7 +457,6 @@ __device__ __forceinline__ void run_skinny(const DevProblem &P, const sk_tile &T
         }
       }
     }
-    if (wk > 1) __syncthreads();  // partials are reused by the next group
   }
 }
 
@@ -437,7 +476,8 @@ __device__ __forceinline__ void run_tile(const DevProblem &P, const sk_tile &T, 
   static_assert((BM + BN) * LDS_ROW <= LDS_TILE_BYTES, "tile does not fit the LDS buffer");
 
   const int tid = threadIdx.x;
-  const int wave = tid >> 6, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lane = tid & 63;
   const int wm = wave % WAVES_M, wn = wave / WAVES_M;
   const int l32 = lane & 31, half = lane >> 5;
 
@@ -475,17 +515,51 @@ __device__ __forceinline__ void run_tile(const DevProblem &P, const sk_tile &T, 
 
   const int k_begin = (int)T.k0, k_stop = (int)T.k0 + (int)T.k_len;
   u32x4 ra[A_ITERS], rb[B_ITERS];
+  bool ra_ok[A_ITERS];
 
+  // Implicit GEMM: the piece column of this thread walks through the filter taps
+  // (r, s) and channels c as K advances; keep that position incrementally.
+  const bool gvec = P.gather != 0;
+  int g_r = 0, g_s = 0, g_c = 0;
+  if (gvec) {
+    const int k = k_begin + c8 * CE;
+    const int tap = k / P.Cin;
+    g_c = k - tap * P.Cin;
+    g_r = tap / P.S;
+    g_s = tap - g_r * P.S;
+  }
   auto gload = [&](int kbase) {
     const int k = kbase + c8 * CE;
+    if (gvec) {
+      const int64_t tap_off = ((int64_t)g_r * P.W + g_s) * P.Cin + g_c;
 #pragma unroll
-    for (int i = 0; i < A_ITERS; ++i) ra[i] = (k < k_stop) ? fetch_A<ES>(P, rowa[i], k) : u32x4{0u, 0u, 0u, 0u};
+      for (int i = 0; i < A_ITERS; ++i) {
+        ra_ok[i] = k < k_stop && (unsigned)(rowa[i].hb + g_r) < (unsigned)P.H &&
+                   (unsigned)(rowa[i].wb + g_s) < (unsigned)P.W;
+        ra[i] = load_piece_vec<ES, false>(P.A, ra_ok[i] ? rowa[i].base + tap_off : 0);
+      }
+      g_c += KB;
+      while (g_c >= P.Cin) {
+        g_c -= P.Cin;
+        if (++g_s == P.S) {
+          g_s = 0;
+          ++g_r;
+        }
+      }
+    } else {
 #pragma unroll
-    for (int i = 0; i < B_ITERS; ++i) rb[i] = (k < k_stop) ? fetch_B<ES, false>(P, wrow[i], k) : u32x4{0u, 0u, 0u, 0u};
+      for (int i = 0; i < A_ITERS; ++i) {
+        ra_ok[i] = k < k_stop;
+        ra[i] = fetch_A<ES>(P, rowa[i], k, ra_ok[i]);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < B_ITERS; ++i) rb[i] = fetch_B<ES, false>(P, wrow[i], k, k < k_stop);
   };
   auto lstore = [&]() {
 #pragma unroll
-    for (int i = 0; i < A_ITERS; ++i) *(u32x4 *)(ldsA + (srow + 32 * i) * LDS_ROW + c8 * 16) = ra[i];
+    for (int i = 0; i < A_ITERS; ++i)
+      *(u32x4 *)(ldsA + (srow + 32 * i) * LDS_ROW + c8 * 16) = keep_if(ra_ok[i], ra[i]);
 #pragma unroll
     for (int i = 0; i < B_ITERS; ++i) *(u32x4 *)(ldsB + (srow + 32 * i) * LDS_ROW + c8 * 16) = rb[i];
   };
@@ -538,24 +612,68 @@ __device__ __forceinline__ void run_tile(const DevProblem &P, const sk_tile &T, 
 // ---------------------------------------------------------------------------
 // dispatch and the persistent shell
 // ---------------------------------------------------------------------------
+// ---------------------------------------------------------------------------
+// generic tiles: operands that cannot be read in aligned 16-byte pieces
+// (odd K, odd Cin, unaligned pointers or strides).  One output per thread and
+// trip, plain fp32 multiply-adds in ascending k.  Correct for everything, fast
+// for nothing.
+// ---------------------------------------------------------------------------
 template <int DT>
-__device__ __forceinline__ void run_class(const DevProblem &P, const sk_tile &T, unsigned char *lds) {
-  const int cls = T.cls;
-  if (cls < 3) {
-    run_skinny<DT, 1>(P, T, cls, lds);
-  } else if (cls < 6) {
-    run_skinny<DT, 2>(P, T, cls - 3, lds);
-  } else if (cls == CLS_TILE_64x128) {
-    run_tile<DT, 64, 128, 1, 4>(P, T, lds);
-  } else {
-    run_tile<DT, 128, 128, 2, 2>(P, T, lds);
+__device__ void run_generic(const DevProblem &P, const sk_tile &T) {
+  const int m_len = T.m_len, n_len = T.n_len;
+  // a split reduction is done whole by the record of its first slice; the others have nothing to do
+  if (T.ks_idx != 0) return;
+  const int k_begin = 0, k_stop = P.Kg;
+  for (int idx = threadIdx.x; idx < m_len * n_len; idx += WG_THREADS) {
+    const int m = (int)T.m0 + idx / n_len;
+    const int n = (int)T.n0 + idx % n_len;
+    const RowA row = row_of(P, m);
+    const int64_t wrow = (int64_t)n * P.ldb;
+    float acc = 0.f;
+    for (int k = k_begin; k < k_stop; ++k) {
+      float a = 0.f;
+      if (!P.gather) {
+        a = load_elem<DT>(P.A, row.base + k);
+      } else {
+        int64_t off;
+        if (patch_offset(P, row, k, off)) a = load_elem<DT>(P.A, off);
+      }
+      acc = __builtin_fmaf(a, load_elem<DT>(P.B, wrow + k), acc);
+    }
+    char SK_GLOBAL *c = as_global_mut<char>(P.C) + ((int64_t)m * P.ldc + n) * Elem<DT>::ES;
+    if constexpr (DT == SK_F32)
+      *(float SK_GLOBAL *)c = acc;
+    else
+      *(uint16_t SK_GLOBAL *)c = (uint16_t)cvt_bits<DT>(acc);
   }
 }
 
-__global__ void __launch_bounds__(WG_THREADS)
+template <int DT>
+__device__ __forceinline__ void run_class(const DevProblem &P, const sk_tile &T, const SplitK &sp, unsigned char *lds,
+                                          uint32_t *s_flag) {
+  const int cls = T.cls;
+  if ((P.flags & (FLAG_VEC_A | FLAG_VEC_B)) != (FLAG_VEC_A | FLAG_VEC_B)) {
+    run_generic<DT>(P, T);
+  } else if (cls == 0) {
+    run_skinny<DT, 1>(P, T, sp, lds, s_flag);
+  } else if (cls == 3) {
+    run_skinny<DT, 2>(P, T, sp, lds, s_flag);
+  } else if (cls == 6) {
+    run_skinny<DT, 4>(P, T, sp, lds, s_flag);
+  } else {
+    run_tile<DT, 64, 128, 1, 4>(P, T, lds);
+  }
+}
+
+// ONLY_DT >= 0: every operator of the plan has that element type (one third of the
+// code, fewer registers); ONLY_DT < 0: operators of mixed types.
+template <int ONLY_DT>
+__global__ void __launch_bounds__(WG_THREADS, 4)
     sk_superkernel(const sk_tile *__restrict__ tiles, const DevProblem *__restrict__ probs, KernelArgs a) {
   __shared__ __attribute__((aligned(16))) unsigned char lds[LDS_TILE_BYTES];
   __shared__ uint32_t s_next[2];
+  __shared__ uint32_t s_flag;
+  const SplitK sp{a.ws, a.ws_off, a.arrive};
 
   const int tid = threadIdx.x;
   if (a.write_start && a.stamps && blockIdx.x == 0 && tid == 0) a.stamps[a.n_problems] = wall_clock64();
@@ -570,13 +688,17 @@ __global__ void __launch_bounds__(WG_THREADS)
 
     const sk_tile T = tiles[t];
     const DevProblem &P = probs[T.problem];
-    switch (P.dtype) {
-      case SK_BF16: run_class<SK_BF16>(P, T, lds); break;
-      case SK_F16: run_class<SK_F16>(P, T, lds); break;
-      default: run_class<SK_F32>(P, T, lds); break;
+    if constexpr (ONLY_DT >= 0) {
+      run_class<ONLY_DT>(P, T, sp, lds, &s_flag);
+    } else {
+      switch (P.dtype) {
+        case SK_BF16: run_class<SK_BF16>(P, T, sp, lds, &s_flag); break;
+        case SK_F16: run_class<SK_F16>(P, T, sp, lds, &s_flag); break;
+        default: run_class<SK_F32>(P, T, sp, lds, &s_flag); break;
+      }
     }
 
-    if (a.remaining) __threadfence();
+    if (a.remaining) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     if (a.dynamic && tid == 0) s_next[par] = nxt;
     __syncthreads();
     if (a.remaining && tid == 0) {

@@ -99,7 +99,7 @@ sk_status plan_host(const sk_problem *problems, int32_t n, const sk_plan_params 
     prm = *params;
   else
     sk_plan_params_default(&prm);
-  if (prm.skinny_max_m < 0 || prm.skinny_max_m > 32 || prm.tile_bytes_min < 1 ||
+  if (prm.skinny_max_m < 0 || prm.skinny_max_m > 64 || prm.tile_bytes_min < 1 ||
       prm.tile_bytes_max < prm.tile_bytes_min || prm.balance_div < 1 || prm.max_groups < 1 ||
       prm.max_groups > 256 || prm.grid_limit < 0) {
     err = "sk_plan_params field out of range";
@@ -211,51 +211,59 @@ sk_status plan_host(const sk_problem *problems, int32_t n, const sk_plan_params 
     const int es = elem_size(out.problems[i].dtype);
     uint16_t cls;
     int64_t BM, BN;
+    int64_t S = 1, slice_len = c.Kg;  // reduction slices per output rectangle and their length
     if (c.Mg <= prm.skinny_max_m) {
-      const int rm = c.Mg <= 16 ? 1 : 2;
-      const int64_t gb = 32 * c.Kg * es;  // bytes of one 32-row weight group
-      int wk_code;
+      const int rm_code = c.Mg <= 16 ? 0 : (c.Mg <= 32 ? 1 : 2);  // 1, 2 or 4 blocks of 16 activation rows
+      const int64_t gb = 32 * c.Kg * es;                          // bytes of one 32-row weight group
       int64_t G;
-      if (gb >= T) {
-        wk_code = 2;  // four-way reduction split, one group
-        G = 1;
-      } else if (2 * gb >= T) {
-        wk_code = 1;  // two-way split, two groups
-        G = 2;
-      } else {
-        wk_code = 0;
+      if (4 * gb <= T) {
         G = std::min<int64_t>(prm.max_groups, 4 * std::max<int64_t>(1, T / (4 * gb)));
+      } else {
+        // four groups already exceed the target: cut the reduction into slices of whole chunks
+        G = 4;
+        const int64_t chunk = (16384 / (16 << rm_code)) / es;  // reduction elements per activation chunk
+        const int64_t nchunks = (c.Kg + chunk - 1) / chunk;
+        int64_t want = std::min<int64_t>(std::min<int64_t>(nchunks, (4 * gb + T - 1) / T), 255);
+        const int64_t per = (nchunks + want - 1) / want;
+        S = (nchunks + per - 1) / per;
+        slice_len = per * chunk;
       }
-      cls = (uint16_t)(3 * (rm - 1) + wk_code);
+      cls = (uint16_t)(3 * rm_code);
       BM = c.Mg;
       BN = 32 * G;
-    } else if (c.Mg <= 64) {
+    } else {
       cls = CLS_TILE_64x128;
       BM = 64;
-      BN = 128;
-    } else {
-      cls = CLS_TILE_128x128;
-      BM = 128;
       BN = 128;
     }
     out.first[i] = (int64_t)out.tiles.size();
     for (int64_t m0 = 0; m0 < c.Mg; m0 += BM) {
       for (int64_t n0 = 0; n0 < c.Ng; n0 += BN) {
-        sk_tile t;
-        t.problem = (uint32_t)i;
-        t.cls = cls;
-        t.ks_idx = 0;
-        t.S = 1;
-        t.m0 = (uint32_t)m0;
-        t.n0 = (uint32_t)n0;
-        t.m_len = (uint16_t)std::min<int64_t>(BM, c.Mg - m0);
-        t.n_len = (uint16_t)std::min<int64_t>(BN, c.Ng - n0);
-        t.k0 = 0;
-        t.k_len = (uint32_t)c.Kg;
-        t.out_tile_id = out_id++;
-        out.tiles.push_back(t);
-        if (out.tiles.size() > (size_t)1 << 30) {
-          err = "tile table too large";
+        for (int64_t ks = 0; ks < S; ++ks) {
+          sk_tile t;
+          t.problem = (uint32_t)i;
+          t.cls = cls;
+          t.ks_idx = (uint8_t)ks;
+          t.S = (uint8_t)S;
+          t.m0 = (uint32_t)m0;
+          t.n0 = (uint32_t)n0;
+          t.m_len = (uint16_t)std::min<int64_t>(BM, c.Mg - m0);
+          t.n_len = (uint16_t)std::min<int64_t>(BN, c.Ng - n0);
+          t.k0 = (uint32_t)(ks * slice_len);
+          t.k_len = (uint32_t)std::min<int64_t>(slice_len, c.Kg - ks * slice_len);
+          t.out_tile_id = out_id;
+          out.tiles.push_back(t);
+        }
+        if (S > 1) {
+          // partial sums of this rectangle: S slices x 4 waves x (2 * rm) accumulators x 64 lanes, 16 bytes each
+          out.ws_off.push_back((uint32_t)out.ws_f32x4);
+          out.ws_f32x4 += S * 4 * 2 * ((int64_t)1 << (cls / 3)) * 64;
+        } else {
+          out.ws_off.push_back(0u);
+        }
+        ++out_id;
+        if (out.tiles.size() > (size_t)1 << 30 || out.ws_f32x4 > ((int64_t)1 << 31)) {
+          err = "tile table or split-K workspace too large";
           return SK_ERR_UNSUPPORTED;
         }
       }
@@ -275,7 +283,7 @@ extern "C" void sk_plan_params_default(sk_plan_params *p) {
   p->edf = 1;
   p->stamps = 0;
   p->host_only = 0;
-  p->skinny_max_m = 32;
+  p->skinny_max_m = 64;
   p->tile_bytes_max = 256 * 1024;
   p->tile_bytes_min = 32 * 1024;
   p->balance_div = 2048;

@@ -17,9 +17,8 @@ enum : int32_t {
 };
 
 enum : uint16_t {
-  CLS_SKINNY_FIRST = 0,  // 0..5: 3*(rm-1) + log2(wk)
-  CLS_TILE_64x128 = 6,
-  CLS_TILE_128x128 = 7,
+  CLS_SKINNY_FIRST = 0,  // 0..8: 3*log2(rm) + log2(wk), rm = 1, 2, 4 blocks of 16 activation rows
+  CLS_TILE_64x128 = 9,
 };
 
 // Device-side description of one operator in its canonical GEMM view
@@ -48,6 +47,8 @@ struct HostPlan {
   std::vector<sk_tile> tiles;
   std::vector<int32_t> order;
   std::vector<int64_t> first, count;
+  std::vector<uint32_t> ws_off;  // per output rectangle: offset of its split-K partials, in 16-byte units
+  int64_t ws_f32x4 = 0;          // size of the split-K workspace, in 16-byte units
   sk_plan_params params;
   int64_t target_tile_bytes = 0;
 };

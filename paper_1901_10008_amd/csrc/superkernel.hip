@@ -35,14 +35,19 @@ struct sk_plan {
   int device = -1;
   int grid = 0;      // persistent workgroups of sk_launch
   int64_t grid_cap = 0;  // most workgroups any launch of this plan may use
+  int only_dtype = -1;   // the element type all operators share, or -1 if they differ
   double ticks_per_ms = 0.0;
-  // one device allocation: tiles | operator descriptors | counters | remaining | stamps
+  // one device allocation: tiles | operator descriptors | counters | remaining | stamps |
+  // split-K offsets | split-K arrival counters | split-K workspace
   void *blob = nullptr;
   sk_tile *d_tiles = nullptr;
   sk::DevProblem *d_probs = nullptr;
   uint32_t *d_counters = nullptr;
   uint32_t *d_remaining = nullptr;
   uint64_t *d_stamps = nullptr;
+  uint32_t *d_ws_off = nullptr;   // per output rectangle
+  uint32_t *d_arrive = nullptr;   // per output rectangle
+  sk::f32x4 *d_ws = nullptr;      // split-K partial sums (not initialised: written before it is read)
 };
 
 extern "C" {
@@ -64,6 +69,11 @@ sk_status sk_plan_create(const sk_problem *problems, int32_t n, const sk_plan_pa
     return set_error(st, err);
   }
   const sk_plan_params &prm = plan->host.params;
+  if (!plan->host.problems.empty()) {
+    plan->only_dtype = plan->host.problems[0].dtype;
+    for (const sk_problem &p : plan->host.problems)
+      if (p.dtype != plan->only_dtype) plan->only_dtype = -1;
+  }
   if (!prm.host_only) {
     hipError_t e = hipGetDevice(&plan->device);
     if (e != hipSuccess) {
@@ -78,7 +88,7 @@ sk_status sk_plan_create(const sk_problem *problems, int32_t n, const sk_plan_pa
       return hip_error("hipDeviceGetAttribute", e);
     }
     plan->ticks_per_ms = (double)clock_khz;
-    const int64_t limit = prm.grid_limit > 0 ? prm.grid_limit : 2 * (int64_t)cus;
+    const int64_t limit = prm.grid_limit > 0 ? prm.grid_limit : 4 * (int64_t)cus;
     const int64_t ntiles = (int64_t)plan->host.tiles.size();
     plan->grid_cap = limit;
     plan->grid = (int)(ntiles < limit ? ntiles : limit);
@@ -89,14 +99,19 @@ sk_status sk_plan_create(const sk_problem *problems, int32_t n, const sk_plan_pa
     const size_t off_cnt = align_up(off_probs + np * sizeof(sk::DevProblem), 256);
     const size_t off_rem = align_up(off_cnt + 2 * sizeof(uint32_t), 256);
     const size_t off_stamps = align_up(off_rem + np * sizeof(uint32_t), 256);
-    const size_t total = align_up(off_stamps + (np + 1) * sizeof(uint64_t), 256);
+    const size_t nrect = plan->host.ws_off.size();
+    const size_t off_wsoff = align_up(off_stamps + (np + 1) * sizeof(uint64_t), 256);
+    const size_t off_arrive = align_up(off_wsoff + nrect * sizeof(uint32_t), 256);
+    const size_t upload = align_up(off_arrive + nrect * sizeof(uint32_t), 256);  // everything before the workspace
+    const size_t total = upload + (size_t)plan->host.ws_f32x4 * 16;
     std::string stage;
     try {
-      stage.assign(total, '\0');
+      stage.assign(upload, '\0');
     } catch (const std::bad_alloc &) {
       delete plan;
       return set_error(SK_ERR_ALLOC, "host staging allocation failed");
     }
+    if (nrect) std::memcpy(&stage[off_wsoff], plan->host.ws_off.data(), nrect * sizeof(uint32_t));
     if (nt) std::memcpy(&stage[off_tiles], plan->host.tiles.data(), nt * sizeof(sk_tile));
     if (np) std::memcpy(&stage[off_probs], plan->host.dev.data(), np * sizeof(sk::DevProblem));
     for (size_t i = 0; i < np; ++i) {
@@ -108,7 +123,7 @@ sk_status sk_plan_create(const sk_problem *problems, int32_t n, const sk_plan_pa
       delete plan;
       return set_error(SK_ERR_ALLOC, std::string("hipMalloc: ") + hipGetErrorString(e));
     }
-    e = hipMemcpy(plan->blob, stage.data(), total, hipMemcpyHostToDevice);
+    e = hipMemcpy(plan->blob, stage.data(), upload, hipMemcpyHostToDevice);
     if (e != hipSuccess) {
       (void)hipFree(plan->blob);
       delete plan;
@@ -120,6 +135,9 @@ sk_status sk_plan_create(const sk_problem *problems, int32_t n, const sk_plan_pa
     plan->d_counters = (uint32_t *)(b + off_cnt);
     plan->d_remaining = (uint32_t *)(b + off_rem);
     plan->d_stamps = (uint64_t *)(b + off_stamps);
+    plan->d_ws_off = (uint32_t *)(b + off_wsoff);
+    plan->d_arrive = (uint32_t *)(b + off_arrive);
+    plan->d_ws = (sk::f32x4 *)(b + upload);
     plan->resident = true;
   }
   *out = plan;
@@ -149,8 +167,24 @@ static sk_status launch_range(sk_plan *plan, hipStream_t stream, uint32_t begin,
   a.tile_end = end;
   a.dynamic = dynamic ? 1u : 0u;
   a.write_start = write_start ? 1u : 0u;
-  hipLaunchKernelGGL(sk::sk_superkernel, dim3((unsigned)grid), dim3(sk::WG_THREADS), 0, stream, plan->d_tiles,
-                     plan->d_probs, a);
+  a.ws = plan->d_ws;
+  a.ws_off = plan->d_ws_off;
+  a.arrive = plan->d_arrive;
+  const dim3 g((unsigned)grid), b(sk::WG_THREADS);
+  switch (plan->only_dtype) {
+    case SK_F32:
+      hipLaunchKernelGGL(sk::sk_superkernel<SK_F32>, g, b, 0, stream, plan->d_tiles, plan->d_probs, a);
+      break;
+    case SK_BF16:
+      hipLaunchKernelGGL(sk::sk_superkernel<SK_BF16>, g, b, 0, stream, plan->d_tiles, plan->d_probs, a);
+      break;
+    case SK_F16:
+      hipLaunchKernelGGL(sk::sk_superkernel<SK_F16>, g, b, 0, stream, plan->d_tiles, plan->d_probs, a);
+      break;
+    default:
+      hipLaunchKernelGGL(sk::sk_superkernel<-1>, g, b, 0, stream, plan->d_tiles, plan->d_probs, a);
+      break;
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_error("kernel launch", e);
   return SK_OK;

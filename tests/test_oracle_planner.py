@@ -39,32 +39,63 @@ def test_hand_enumerated_skinny_plan():
     assert table == struct.pack("<IHBBIIHHIII", 0, 0, 0, 1, 0, 0, 1, 70, 0, 3, 0)
 
 
-def test_hand_enumerated_split_modes():
+def test_hand_enumerated_reduction_slices():
     prm = P.Params(tile_bytes_min=32768, tile_bytes_max=32768)   # T fixed at 32 KiB
-    # K=1024 bf16: group = 32*1024*2 = 64 KiB >= T  => wk=4, one group (32 rows) per tile
+    # K=1024 bf16: one 32-row group is 64 KiB, four groups (256 KiB) exceed T => 128-row tiles whose
+    # reduction is cut into whole 512-element chunks: 2 chunks, wanted 8 slices, so 2 slices of 512
     t = P.decode(P.plan([gemm(4, 100, 1024)], prm)[0])
-    assert [x["cls"] for x in t] == [2, 2, 2, 2]
-    assert [(x["n0"], x["n_len"]) for x in t] == [(0, 32), (32, 32), (64, 32), (96, 4)]
-    # K=256 bf16: group = 16 KiB, 2*16 >= 32 => wk=2, two groups per tile; Mg=20 => rm=2 => cls 3+1
+    assert [(x["cls"], x["n0"], x["n_len"], x["ks_idx"], x["S"], x["k0"], x["k_len"], x["out_tile_id"]) for x in t] == \
+        [(0, 0, 100, 0, 2, 0, 512, 0), (0, 0, 100, 1, 2, 512, 512, 0)]
+    # K=2304 bf16, Mg=20 (two row blocks, chunk = 256 elements): 9 chunks, four groups = 576 KiB -> wanted 18,
+    # capped at 9 slices of one chunk; two column blocks
+    t = P.decode(P.plan([gemm(20, 200, 2304)], prm)[0])
+    assert len(t) == 18 and {x["cls"] for x in t} == {3}
+    assert [(x["n0"], x["n_len"]) for x in t[::9]] == [(0, 128), (128, 72)]
+    assert [(x["ks_idx"], x["k0"], x["k_len"]) for x in t[:9]] == [(i, 256 * i, 256) for i in range(9)]
+    assert [x["out_tile_id"] for x in t] == [0] * 9 + [1] * 9
+    # K=1280 bf16, Mg=8: chunks of 512 -> 3 chunks (512, 512, 256); four groups = 320 KiB -> wanted 10 -> 3 slices
+    t = P.decode(P.plan([gemm(8, 64, 1280)], prm)[0])
+    assert [(x["ks_idx"], x["S"], x["k0"], x["k_len"]) for x in t] == [(0, 3, 0, 512), (1, 3, 512, 512), (2, 3, 1024, 256)]
+    # K=256 bf16, Mg=20: one chunk only => no split even though four groups exceed T
     t = P.decode(P.plan([gemm(20, 100, 256)], prm)[0])
-    assert [x["cls"] for x in t] == [4, 4]
-    assert [(x["n0"], x["n_len"], x["m_len"]) for x in t] == [(0, 64, 20), (64, 36, 20)]
-    # K=64 bf16: group = 4 KiB => wk=1, G = 4*(32768//(16384)) = 8 groups = 256 rows
+    assert [(x["cls"], x["n0"], x["n_len"], x["m_len"], x["S"], x["k_len"]) for x in t] == [(3, 0, 100, 20, 1, 256)]
+    # K=64 bf16: group = 4 KiB, four groups fit twice into T => 8 groups = 256 rows per tile, no split
     t = P.decode(P.plan([gemm(16, 600, 64)], prm)[0])
-    assert [x["cls"] for x in t] == [0, 0, 0]
+    assert [x["cls"] for x in t] == [0, 0, 0] and all(x["S"] == 1 for x in t)
     assert [(x["n0"], x["n_len"]) for x in t] == [(0, 256), (256, 256), (512, 88)]
+    # slices of unequal count: 5 chunks wanted in 2 slices -> 3 + 2 chunks
+    prm2 = P.Params(tile_bytes_min=3 * 65536, tile_bytes_max=3 * 65536)
+    t = P.decode(P.plan([gemm(4, 32, 2560)], prm2)[0])   # four groups = 640 KiB, T = 192 KiB -> wanted 4 -> per 2 -> 3 slices
+    assert [(x["k0"], x["k_len"]) for x in t] == [(0, 1024), (1024, 1024), (2048, 512)]
+
+
+def test_hand_enumerated_four_row_block_class():
+    prm = P.Params(tile_bytes_min=32768, tile_bytes_max=32768)
+    # Mg = 49 (7x7 image) => four row blocks (cls 6), chunk = 128 elements.
+    # Kg = 9*64 = 576 bf16: group = 36 KiB; four groups = 144 KiB -> wanted 5 slices; 5 chunks -> 5 slices
+    t = P.decode(P.plan([conv(7, 64, 256, 3)], prm)[0])
+    assert len(t) == 10 and {x["cls"] for x in t} == {6}
+    assert [(x["n0"], x["n_len"], x["ks_idx"], x["k0"], x["k_len"]) for x in t[:5]] == \
+        [(0, 128, 0, 0, 128), (0, 128, 1, 128, 128), (0, 128, 2, 256, 128), (0, 128, 3, 384, 128), (0, 128, 4, 512, 64)]
+    assert [x["n0"] for x in t[5:]] == [128] * 5
+    # Kg = 64: group = 4 KiB => 8 groups, no split
+    t = P.decode(P.plan([conv(7, 64, 300, 1)], prm)[0])
+    assert [(x["cls"], x["n0"], x["n_len"], x["S"]) for x in t] == [(6, 0, 256, 1), (6, 256, 44, 1)]
+    # M = 64 is the last skinny size, 65 goes to LDS tiles
+    assert P.decode(P.plan([gemm(64, 32, 64)], prm)[0])[0]["cls"] == 6
+    assert P.decode(P.plan([gemm(65, 32, 64)], prm)[0])[0]["cls"] == 9
+    assert P.decode(P.plan([gemm(64, 32, 64)], P.Params(skinny_max_m=32))[0])[0]["cls"] == 9
 
 
 def test_hand_enumerated_lds_tiles():
-    # Mg = 49 (7x7 conv) -> 64x128 tiles; Mg = 196 -> 128x128 tiles, rows outer, columns inner
-    t = P.decode(P.plan([conv(7, 64, 256, 1)])[0])
-    assert [(x["cls"], x["m0"], x["n0"], x["m_len"], x["n_len"]) for x in t] == \
-        [(6, 0, 0, 49, 128), (6, 0, 128, 49, 128)]
+    # Mg = 196 -> 64x128 tiles, rows outer, columns inner
     t = P.decode(P.plan([conv(14, 64, 192 + 8, 3)])[0])
     assert [(x["cls"], x["m0"], x["n0"], x["m_len"], x["n_len"], x["k_len"]) for x in t] == \
-        [(7, 0, 0, 128, 128, 576), (7, 0, 128, 128, 72, 576),
-         (7, 128, 0, 68, 128, 576), (7, 128, 128, 68, 72, 576)]
-    assert [x["out_tile_id"] for x in t] == [0, 1, 2, 3]
+        [(9, 0, 0, 64, 128, 576), (9, 0, 128, 64, 72, 576),
+         (9, 64, 0, 64, 128, 576), (9, 64, 128, 64, 72, 576),
+         (9, 128, 0, 64, 128, 576), (9, 128, 128, 64, 72, 576),
+         (9, 192, 0, 4, 128, 576), (9, 192, 128, 4, 72, 576)]
+    assert [x["out_tile_id"] for x in t] == list(range(8))
 
 
 def test_edf_order_is_stable_sort_by_deadline_then_index():
@@ -128,7 +159,7 @@ def test_coverage_checker_catches_planted_mistakes():
     table = P.plan(probs)[0]
     P.check_coverage(probs, table)
     n = len(table) // 32
-    assert n >= 4
+    assert n >= 4 and P.decode(table)[1]["n0"] == 128
     with pytest.raises(AssertionError):
         P.check_coverage(probs, table[:-32])                       # a tile dropped
     with pytest.raises(AssertionError):

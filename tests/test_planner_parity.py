@@ -79,6 +79,7 @@ RAGGED = [_g(1, 5, 3, "f32"), _g(17, 33, 129), _g(33, 130, 70, "f16"), _g(65, 12
     {},
     {"edf": 0},
     {"skinny_max_m": 16},
+    {"skinny_max_m": 32},
     {"skinny_max_m": 0},
     {"tile_bytes_min": 4096, "tile_bytes_max": 8192, "balance_div": 7},
     {"tile_bytes_min": 1 << 20, "tile_bytes_max": 1 << 22, "max_groups": 3},
@@ -151,7 +152,7 @@ def test_validation_errors():
     adj[1].C = adj[0].C + 4 * 64 * 2
     sk.sk_plan_create(adj, sk.sk_plan_params_default(host_only=1)).close()
     # parameter out of range
-    _expect(-1, ok, skinny_max_m=33)
+    _expect(-1, ok, skinny_max_m=65)
     _expect(-1, ok, balance_div=0)
     # launching a host-only plan is a state error
     with sk.sk_plan_create(ok, sk.sk_plan_params_default(host_only=1)) as plan:
