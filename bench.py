@@ -35,6 +35,9 @@ def parse():
     ap.add_argument("--no-baselines", action="store_true", help="skip sequential / multi-stream legs")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--param", action="append", default=[], help="sk_plan_params override name=value")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy, so that a rocprofv3 --pmc run of this command "
+                         "shows what FETCH_SIZE / WRITE_SIZE read for a kernel of known traffic")
     return ap.parse_args()
 
 
@@ -83,6 +86,13 @@ def main():
     t_lb = max(sum(workloads.flops(s) / PEAK_FLOPS[s.dtype] for s in specs), abytes / (PEAK_HBM_GBS * 1e9))
 
     stream = torch.cuda.current_stream().cuda_stream
+
+    if args.pmc_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)          # the kernel to look for: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- plan cost (host planning + upload), not part of the timed steps ----
     t0 = time.perf_counter()
@@ -138,7 +148,7 @@ def main():
                                  "frac": round(t_roof / (kern_ms * 1e-3), 4)},
         "roofline": {"bound": "hbm", "achieved": round(abytes / (kern_ms * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS,
                      "unit": "GB/s", "frac": round(abytes / (kern_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
-                     "traffic": None},
+                     "traffic": measured_traffic(name)},
     }
 
     if not args.no_baselines:
@@ -195,6 +205,18 @@ def main():
 
     plan.close()
     print(json.dumps(out))
+
+
+def measured_traffic(workload):
+    """HBM bytes per superkernel launch from the committed rocprofv3 --pmc summary (FETCH_SIZE and
+    WRITE_SIZE, scaled by what the same counters read for a plain copy of known size), or None."""
+    path = os.path.join(ROOT, "profiles", "superkernel_traffic.json")
+    try:
+        with open(path) as f:
+            rec = json.load(f)
+        return rec[workload]["hbm_bytes_per_launch"]
+    except (OSError, KeyError, ValueError):
+        return None
 
 
 def cpu_baseline(specs, seed, target_s):

@@ -103,7 +103,7 @@ typedef struct {
   int32_t balance_div;    /* default 2048                                                    */
   int32_t max_groups;     /* cap on 32-row weight groups per skinny tile, default 256        */
   int32_t grid_limit;     /* upper bound on persistent workgroups per launch;                */
-                          /* 0 = 4 per compute unit of the current device                    */
+                          /* 0 = 3 per compute unit of the current device                    */
   int32_t reserved;
 } sk_plan_params;
 

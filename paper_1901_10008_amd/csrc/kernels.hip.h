@@ -276,6 +276,27 @@ __device__ __forceinline__ void mma32(const u32x4 &a, const u32x4 &b, f32x16 &c)
 // and writes C.
 constexpr int SKINNY_CHUNK_BYTES = 16384;
 
+// One accumulator (16 bytes per lane, 1 KB per wave) written / read at device scope (through
+// to memory, not left in or served from an XCD's L2) as two 64-bit relaxed atomics per lane.
+// The 1 KB block holds the low halves of all 64 lanes first, then the high halves, so that
+// each of the two instructions covers 512 contiguous bytes: a write-through of scattered
+// 8-byte pieces would cost a partial-line memory write each.
+__device__ __forceinline__ void store_device_scope(f32x4 *block, int lane, const f32x4 &v) {
+  unsigned long long *q = (unsigned long long *)block;
+  __hip_atomic_store(q + lane, __builtin_bit_cast(unsigned long long, __builtin_shufflevector(v, v, 0, 1)),
+                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(q + 64 + lane, __builtin_bit_cast(unsigned long long, __builtin_shufflevector(v, v, 2, 3)),
+                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ f32x4 load_device_scope(const f32x4 *block, int lane) {
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
+  unsigned long long *q = (unsigned long long *)block;
+  const f32x2 lo = __builtin_bit_cast(f32x2, __hip_atomic_load(q + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+  const f32x2 hi =
+      __builtin_bit_cast(f32x2, __hip_atomic_load(q + 64 + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+  return f32x4{lo.x, lo.y, hi.x, hi.y};
+}
+
 struct SplitK {
   f32x4 *ws;                // partial sums of all split output rectangles
   const uint32_t *ws_off;   // per out_tile_id: offset of its partials in ws, in f32x4 units
@@ -337,113 +358,56 @@ __device__ __forceinline__ void run_skinny(const DevProblem &P, const sk_tile &T
   };
 
   const bool vec_c = (P.flags & FLAG_VEC_C) != 0;
+  const bool restage_each = nchunks > 1;
 
-  for (int it = 0; it < iters; ++it) {
+  // A wave's work is one stream of block slots: pass 0 (its first weight group) blocks
+  // 0..nslots-1, then pass 1, ...  The weight loads run NB-1 slots ahead of the MFMAs and
+  // keep running across pass boundaries, so the ring only drains at the end of the tile.
+  // --- load stream (ahead) ---
+  int p_it = 0, p_blk = 0;
+  bool p_act = false;
+  int64_t wrow[2] = {0, 0};
+  auto set_load_rows = [&](int it) {
     const int g = it * 4 + wave;
-    const bool active = g < ngroups;
-    const int n_base = (int)T.n0 + g * 32;
-
-    f32x4 acc[2][RM];
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-      for (int mb = 0; mb < RM; ++mb) acc[rb][mb] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    int64_t wrow[2];
+    p_act = it < iters && g < ngroups;
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb) {
-      int n = n_base + rb * 16 + r16;
+      int n = (int)T.n0 + g * 32 + rb * 16 + r16;
       if (n >= n_end) n = n_end - 1;  // rows past the edge repeat the last row; never stored
       wrow[rb] = (int64_t)n * P.ldb;
     }
-    // The loads are unconditional (see fetch_B): blocks past the end, and waves without a
-    // weight group, re-read the start of a row instead, so that the number of loads in
-    // flight at every point of the loop is the same on every path and the waits stay exact.
-    auto load_w = [&](int i, u32x4(&w)[4]) {
-      const int k = k0 + i * KB + q * 2 * CE;
-      const bool in0 = active && k < k_stop, in1 = active && k + CE < k_stop;
-      w[0] = fetch_B<ES, true>(P, wrow[0], k, in0);
-      w[1] = fetch_B<ES, true>(P, wrow[0], k + CE, in1);
-      w[2] = fetch_B<ES, true>(P, wrow[1], k, in0);
-      w[3] = fetch_B<ES, true>(P, wrow[1], k + CE, in1);
-    };
-
-    const bool restage = it == 0 || nchunks > 1;
-    if (restage) {
-      if (it > 0) __syncthreads();  // the previous groups' readers are done with the buffers
-      stage_load(0);
+  };
+  // The loads are unconditional (see fetch_B): slots past the end, and waves without a weight
+  // group, re-read the start of a row instead, so that the number of loads in flight at every
+  // point of the loop is the same on every path and the waits stay exact.
+  auto next_load = [&](u32x4(&w)[4]) {
+    const int k = k0 + p_blk * KB + q * 2 * CE;
+    // slots that no pass will multiply (past the end of the tile, waves without a group) all read
+    // the very first piece of the operand: one cache line for the whole wave instead of 32
+    const bool in0 = k < k_stop, in1 = k + CE < k_stop;
+    const int64_t r0 = p_act ? wrow[0] : 0, r1 = p_act ? wrow[1] : 0;
+    w[0] = fetch_B<ES, true>(P, r0, k, p_act && in0);
+    w[1] = fetch_B<ES, true>(P, r0, k + CE, p_act && in1);
+    w[2] = fetch_B<ES, true>(P, r1, k, p_act && in0);
+    w[3] = fetch_B<ES, true>(P, r1, k + CE, p_act && in1);
+    if (++p_blk == nslots) {
+      p_blk = 0;
+      ++p_it;
+      set_load_rows(p_it);
     }
-    u32x4 w[NB][4];
+  };
+  // --- compute stream ---
+  int it = 0, blk = 0, buf = 1;
+  f32x4 acc[2][RM];
 #pragma unroll
-    for (int u = 0; u < NB - 1; ++u) load_w(u, w[u]);
-
-    for (int i0 = 0; i0 < nslots; i0 += NB) {
+  for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-      for (int u = 0; u < NB; ++u) {
-        const int i = i0 + u;
-        const int c = i >> BPC_LOG2;
-        if (restage && i < nslots && (i & (BPC - 1)) == 0) {
-          // first block of chunk c: publish it, then start fetching the next chunk
-          stage_store(c);
-          __syncthreads();
-          if (c + 1 < nchunks) stage_load(c + 1);
-        }
-        load_w(i + NB - 1, w[(u + NB - 1) % NB]);
-        if (active && i < nslots) {
-          const unsigned char *abase = lds + (c & 1) * BUF + (i & (BPC - 1)) * 128 + q * 32 + r16 * LROW;
-#pragma unroll
-          for (int mb = 0; mb < RM; ++mb) {
-            const u32x4 a0 = *(const u32x4 *)(abase + mb * 16 * LROW);
-            const u32x4 a1 = *(const u32x4 *)(abase + mb * 16 * LROW + 16);
-            mma16<DT>(w[u][0], a0, acc[0][mb]);
-            mma16<DT>(w[u][1], a1, acc[0][mb]);
-            mma16<DT>(w[u][2], a0, acc[1][mb]);
-            mma16<DT>(w[u][3], a1, acc[1][mb]);
-          }
-        }
-      }
-    }
-
-    bool finish = true;
-    if (T.S > 1) {
-      // deliver this slice's partial sums; the last slice to arrive adds all of them in slice order
-      // (split rectangles have at most four weight groups, so this loop runs once for them)
-      f32x4 *mine = sp.ws + sp.ws_off[T.out_tile_id];
-      const int slot = (wave * 2 * RM) * 64 + lane;
-#pragma unroll
-      for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-        for (int mb = 0; mb < RM; ++mb)
-          mine[(size_t)T.ks_idx * (4 * 2 * RM * 64) + slot + (rb * RM + mb) * 64] = acc[rb][mb];
-      __syncthreads();
-      if (tid == 0) {
-        // release our partials / acquire the others' at device scope
-        const uint32_t prev =
-            __hip_atomic_fetch_add(&sp.arrive[T.out_tile_id], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-        *s_flag = prev;
-      }
-      __syncthreads();
-      const uint32_t prev = *s_flag;
-      finish = prev == (uint32_t)T.S - 1;
-      if (finish) {
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-          for (int mb = 0; mb < RM; ++mb) acc[rb][mb] = f32x4{0.f, 0.f, 0.f, 0.f};
-        for (int s2 = 0; s2 < T.S; ++s2) {
-#pragma unroll
-          for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-            for (int mb = 0; mb < RM; ++mb)
-              acc[rb][mb] += mine[(size_t)s2 * (4 * 2 * RM * 64) + slot + (rb * RM + mb) * 64];
-        }
-        if (tid == 0) sp.arrive[T.out_tile_id] = 0u;  // re-arm for the next launch
-      }
-    }
-
-    if (finish && active) {
-      // lane holds, per (rb, mb): row m = mb*16 + lane%16, columns n_base + rb*16 + (lane/16)*4 + 0..3
+    for (int mb = 0; mb < RM; ++mb) acc[rb][mb] = f32x4{0.f, 0.f, 0.f, 0.f};
+  auto store_pass = [&]() {
+    // lane holds, per (rb, mb): row m = mb*16 + lane%16, columns n_base + rb*16 + (lane/16)*4 + 0..3
+    const int g = it * 4 + wave;
+    const int n_base = (int)T.n0 + g * 32;
+    if (g < ngroups) {
 #pragma unroll
       for (int mb = 0; mb < RM; ++mb) {
         const int m = mb * 16 + r16;
@@ -457,7 +421,104 @@ __device__ __forceinline__ void run_skinny(const DevProblem &P, const sk_tile &T
         }
       }
     }
+  };
+
+  set_load_rows(0);
+  stage_load(0);
+  u32x4 w[NB][4];
+#pragma unroll
+  for (int u = 0; u < NB - 1; ++u) next_load(w[u]);
+  if (!restage_each) {
+    // the only activation chunk serves every pass
+    stage_store(0);
+    buf = 0;
+    __syncthreads();
   }
+
+  const int total = iters * nslots;
+  for (int i0 = 0; i0 < total; i0 += NB) {
+#pragma unroll
+    for (int u = 0; u < NB; ++u) {
+      const bool live = i0 + u < total;
+      if (live && restage_each && (blk & (BPC - 1)) == 0) {
+        // first block of a chunk: publish it, then start fetching the one after it
+        // (chunk c+1 of this pass, or chunk 0 again for the next pass)
+        buf ^= 1;
+        stage_store(buf);
+        __syncthreads();
+        const int c_next = (blk >> BPC_LOG2) + 1;
+        if (c_next < nchunks)
+          stage_load(c_next);
+        else if (it + 1 < iters)
+          stage_load(0);
+      }
+      next_load(w[(u + NB - 1) % NB]);
+      if (live) {
+        if (it * 4 + wave < ngroups) {
+          const unsigned char *abase = lds + buf * BUF + (blk & (BPC - 1)) * 128 + q * 32 + r16 * LROW;
+#pragma unroll
+          for (int mb = 0; mb < RM; ++mb) {
+            const u32x4 a0 = *(const u32x4 *)(abase + mb * 16 * LROW);
+            const u32x4 a1 = *(const u32x4 *)(abase + mb * 16 * LROW + 16);
+            mma16<DT>(w[u][0], a0, acc[0][mb]);
+            mma16<DT>(w[u][1], a1, acc[0][mb]);
+            mma16<DT>(w[u][2], a0, acc[1][mb]);
+            mma16<DT>(w[u][3], a1, acc[1][mb]);
+          }
+        }
+        if (++blk == nslots && it + 1 < iters) {
+          // this weight group is done; the next one's loads are already in flight
+          store_pass();
+#pragma unroll
+          for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int mb = 0; mb < RM; ++mb) acc[rb][mb] = f32x4{0.f, 0.f, 0.f, 0.f};
+          blk = 0;
+          ++it;
+        }
+      }
+    }
+  }
+
+  // last pass (the only one of a split rectangle, which has at most four weight groups)
+  bool finish = true;
+  if (T.S > 1) {
+    // Deliver this slice's partial sums; the last slice to arrive adds all of them in slice
+    // order.  The partials are written and read with device-scope accesses (they go through
+    // to memory, past the per-XCD L2s), so no cache-wide release/acquire is needed: each wave
+    // waits for its own stores, the workgroup meets at a barrier, one thread counts it in.
+    f32x4 *mine = sp.ws + sp.ws_off[T.out_tile_id];
+    const int slot = (wave * 2 * RM) * 64;  // this wave's 2*RM blocks of 64 x 16 bytes within a slice
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+      for (int mb = 0; mb < RM; ++mb)
+        store_device_scope(mine + (size_t)T.ks_idx * (4 * 2 * RM * 64) + slot + (rb * RM + mb) * 64, lane,
+                           acc[rb][mb]);
+    __builtin_amdgcn_s_waitcnt(0);  // all counters to zero: the stores above have completed
+    __syncthreads();
+    if (tid == 0)
+      *s_flag = __hip_atomic_fetch_add(&sp.arrive[T.out_tile_id], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    const uint32_t prev = *s_flag;
+    finish = prev == (uint32_t)T.S - 1;
+    if (finish) {
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int mb = 0; mb < RM; ++mb) acc[rb][mb] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int s2 = 0; s2 < T.S; ++s2) {
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+          for (int mb = 0; mb < RM; ++mb)
+            acc[rb][mb] += load_device_scope(mine + (size_t)s2 * (4 * 2 * RM * 64) + slot + (rb * RM + mb) * 64, lane);
+      }
+      if (tid == 0)  // re-arm for the next launch
+        __hip_atomic_store(&sp.arrive[T.out_tile_id], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
+  if (finish) store_pass();
 }
 
 // ---------------------------------------------------------------------------
@@ -668,7 +729,7 @@ __device__ __forceinline__ void run_class(const DevProblem &P, const sk_tile &T,
 // ONLY_DT >= 0: every operator of the plan has that element type (one third of the
 // code, fewer registers); ONLY_DT < 0: operators of mixed types.
 template <int ONLY_DT>
-__global__ void __launch_bounds__(WG_THREADS, 4)
+__global__ void __launch_bounds__(WG_THREADS, 3)
     sk_superkernel(const sk_tile *__restrict__ tiles, const DevProblem *__restrict__ probs, KernelArgs a) {
   __shared__ __attribute__((aligned(16))) unsigned char lds[LDS_TILE_BYTES];
   __shared__ uint32_t s_next[2];
