@@ -210,7 +210,7 @@ def main():
 def measured_traffic(workload):
     """HBM bytes per superkernel launch from the committed rocprofv3 --pmc summary (FETCH_SIZE and
     WRITE_SIZE, scaled by what the same counters read for a plain copy of known size), or None."""
-    path = os.path.join(ROOT, "profiles", "superkernel_traffic.json")
+    path = os.path.join(ROOT, "profiles", "superkernel_cfg5_traffic.txt")
     try:
         with open(path) as f:
             rec = json.load(f)
