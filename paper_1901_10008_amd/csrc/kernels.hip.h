@@ -262,8 +262,7 @@ __device__ __forceinline__ void mma32(const u32x4 &a, const u32x4 &b, f32x16 &c)
 // Weights never touch LDS: each wave streams its rows HBM -> registers -> MFMA
 // through a ring of NB reduction blocks (128 bytes per row each), so NB-1
 // blocks of loads stay in flight while one is multiplied, and every wave walks
-// along its rows in consecutive 128-byte steps.  Within a block lane slot
-// q = lane/16 owns pieces 2q and 2q+1.
+// along its rows in consecutive 128-byte steps.
 //
 // The activations (tiny, and gathered from an image for a convolution) are
 // staged once per workgroup through LDS in chunks of SKINNY_CHUNK_BYTES,
@@ -275,6 +274,27 @@ __device__ __forceinline__ void mma32(const u32x4 &a, const u32x4 &b, f32x16 &c)
 // partials in slice order (so the result does not depend on arrival order)
 // and writes C.
 constexpr int SKINNY_CHUNK_BYTES = 16384;
+
+// Two registers loaded with the full-line map hold, for a 16-row MFMA block,
+//   first : lanes r16 < 8 -> (row r16, pieces 0..3)      lanes r16 >= 8 -> (row r16-8, pieces 4..7)
+//   second: lanes r16 < 8 -> (row r16+8, pieces 0..3)    lanes r16 >= 8 -> (row r16,   pieces 4..7)
+// fix_lo gives (row r16, pieces 0..3) in every lane, fix_hi (row r16, pieces 4..7): the halves
+// that are in the wrong place come from the other register, rotated by 8 lanes within each row
+// of 16 (DPP row_ror:8, written only to the upper resp. lower 8 lanes through the bank mask).
+__device__ __forceinline__ u32x4 fix_lo(const u32x4 &first, const u32x4 &second) {
+  u32x4 r;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    r[i] = (uint32_t)__builtin_amdgcn_update_dpp((int)first[i], (int)second[i], 0x128, 0xF, 0xC, false);
+  return r;
+}
+__device__ __forceinline__ u32x4 fix_hi(const u32x4 &first, const u32x4 &second) {
+  u32x4 r;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    r[i] = (uint32_t)__builtin_amdgcn_update_dpp((int)second[i], (int)first[i], 0x128, 0xF, 0x3, false);
+  return r;
+}
 
 // One accumulator (16 bytes per lane, 1 KB per wave) written / read at device scope (through
 // to memory, not left in or served from an XCD's L2) as two 64-bit relaxed atomics per lane.
@@ -366,30 +386,32 @@ __device__ __forceinline__ void run_skinny(const DevProblem &P, const sk_tile &T
   // --- load stream (ahead) ---
   int p_it = 0, p_blk = 0;
   bool p_act = false;
-  int64_t wrow[2] = {0, 0};
+  // Load map: instruction j of a block covers rows 8j..8j+7 of the 32-row group with their full
+  // 128-byte lines: lane (r16, q) reads row 8j + r16%8, piece q + 4*(r16/8).  (Eight whole lines
+  // per instruction stream measurably better than sixteen half lines.)  The MFMA wants row
+  // r16 in lane r16 with pieces 0..3 resp. 4..7 in slot q; two DPP half-row swaps per pair of
+  // registers put the data there when the block is consumed (see fix_lo / fix_hi).
+  const int piece = q + 4 * (r16 >> 3);
+  int64_t wrow[4] = {0, 0, 0, 0};
   auto set_load_rows = [&](int it) {
     const int g = it * 4 + wave;
     p_act = it < iters && g < ngroups;
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
-      int n = (int)T.n0 + g * 32 + rb * 16 + r16;
+    for (int j = 0; j < 4; ++j) {
+      int n = (int)T.n0 + g * 32 + j * 8 + (r16 & 7);
       if (n >= n_end) n = n_end - 1;  // rows past the edge repeat the last row; never stored
-      wrow[rb] = (int64_t)n * P.ldb;
+      wrow[j] = p_act ? (int64_t)n * P.ldb : 0;
     }
   };
-  // The loads are unconditional (see fetch_B): slots past the end, and waves without a weight
-  // group, re-read the start of a row instead, so that the number of loads in flight at every
-  // point of the loop is the same on every path and the waits stay exact.
+  // The loads are unconditional (see fetch_B): slots past the end re-read the start of a row, and
+  // slots that no pass will multiply (past the end of the tile, waves without a group) all read
+  // the very first piece of the operand, so that the number of loads in flight at every point
+  // of the loop is the same on every path and the waits stay exact.
   auto next_load = [&](u32x4(&w)[4]) {
-    const int k = k0 + p_blk * KB + q * 2 * CE;
-    // slots that no pass will multiply (past the end of the tile, waves without a group) all read
-    // the very first piece of the operand: one cache line for the whole wave instead of 32
-    const bool in0 = k < k_stop, in1 = k + CE < k_stop;
-    const int64_t r0 = p_act ? wrow[0] : 0, r1 = p_act ? wrow[1] : 0;
-    w[0] = fetch_B<ES, true>(P, r0, k, p_act && in0);
-    w[1] = fetch_B<ES, true>(P, r0, k + CE, p_act && in1);
-    w[2] = fetch_B<ES, true>(P, r1, k, p_act && in0);
-    w[3] = fetch_B<ES, true>(P, r1, k + CE, p_act && in1);
+    const int k = k0 + p_blk * KB + piece * CE;
+    const bool in = p_act && k < k_stop;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) w[j] = fetch_B<ES, true>(P, wrow[j], k, in);
     if (++p_blk == nslots) {
       p_blk = 0;
       ++p_it;
@@ -455,15 +477,18 @@ __device__ __forceinline__ void run_skinny(const DevProblem &P, const sk_tile &T
       next_load(w[(u + NB - 1) % NB]);
       if (live) {
         if (it * 4 + wave < ngroups) {
-          const unsigned char *abase = lds + buf * BUF + (blk & (BPC - 1)) * 128 + q * 32 + r16 * LROW;
+          const unsigned char *abase = lds + buf * BUF + (blk & (BPC - 1)) * 128 + q * 16 + r16 * LROW;
+          // rows 16rb..16rb+15: pieces 0..3 (x) and 4..7 (y) in MFMA lane order
+          const u32x4 x0 = fix_lo(w[u][0], w[u][1]), y0 = fix_hi(w[u][0], w[u][1]);
+          const u32x4 x1 = fix_lo(w[u][2], w[u][3]), y1 = fix_hi(w[u][2], w[u][3]);
 #pragma unroll
           for (int mb = 0; mb < RM; ++mb) {
-            const u32x4 a0 = *(const u32x4 *)(abase + mb * 16 * LROW);
-            const u32x4 a1 = *(const u32x4 *)(abase + mb * 16 * LROW + 16);
-            mma16<DT>(w[u][0], a0, acc[0][mb]);
-            mma16<DT>(w[u][1], a1, acc[0][mb]);
-            mma16<DT>(w[u][2], a0, acc[1][mb]);
-            mma16<DT>(w[u][3], a1, acc[1][mb]);
+            const u32x4 a0 = *(const u32x4 *)(abase + mb * 16 * LROW);       // pieces 0..3
+            const u32x4 a1 = *(const u32x4 *)(abase + mb * 16 * LROW + 64);  // pieces 4..7
+            mma16<DT>(x0, a0, acc[0][mb]);
+            mma16<DT>(y0, a1, acc[0][mb]);
+            mma16<DT>(x1, a0, acc[1][mb]);
+            mma16<DT>(y1, a1, acc[1][mb]);
           }
         }
         if (++blk == nslots && it + 1 < iters) {
