@@ -45,6 +45,19 @@ __device__ __forceinline__ T SK_GLOBAL *as_global_mut(void *p) {
   return (T SK_GLOBAL *)(uintptr_t)p;
 }
 
+// A record that every lane reads from the same address, returned in scalar registers.
+template <class S>
+__device__ __forceinline__ S load_uniform(const S *src) {
+  static_assert(sizeof(S) % 4 == 0, "whole dwords");
+  struct Words {
+    uint32_t w[sizeof(S) / 4];
+  } v;
+  const uint32_t SK_GLOBAL *p = as_global<uint32_t>(src);
+#pragma unroll
+  for (unsigned i = 0; i < sizeof(S) / 4; ++i) v.w[i] = (uint32_t)__builtin_amdgcn_readfirstlane((int)p[i]);
+  return __builtin_bit_cast(S, v);
+}
+
 constexpr int WG_THREADS = 256;
 constexpr int LDS_ROW = 144;                  // 128 bytes of K + 16 bytes of padding (bank spread)
 constexpr int LDS_TILE_BYTES = 256 * LDS_ROW;  // 36 KB per workgroup: four workgroups share a CU's 160 KB
@@ -704,8 +717,13 @@ __device__ __forceinline__ void run_tile(const DevProblem &P, const sk_tile &T, 
 // trip, plain fp32 multiply-adds in ascending k.  Correct for everything, fast
 // for nothing.
 // ---------------------------------------------------------------------------
+// (Not inlined, and given the records' addresses in memory rather than references to the
+// caller's copies: a local whose address escapes into a call has to live in scratch memory,
+// and every later use of it in the fast paths would be a load from there.)
 template <int DT>
-__device__ void run_generic(const DevProblem &P, const sk_tile &T) {
+__device__ void run_generic(const DevProblem *P_mem, const sk_tile *T_mem) {
+  const DevProblem P = *P_mem;
+  const sk_tile T = *T_mem;
   const int m_len = T.m_len, n_len = T.n_len;
   // a split reduction is done whole by the record of its first slice; the others have nothing to do
   if (T.ks_idx != 0) return;
@@ -735,11 +753,12 @@ __device__ void run_generic(const DevProblem &P, const sk_tile &T) {
 }
 
 template <int DT>
-__device__ __forceinline__ void run_class(const DevProblem &P, const sk_tile &T, const SplitK &sp, unsigned char *lds,
+__device__ __forceinline__ void run_class(const DevProblem &P, const sk_tile &T, const DevProblem *P_mem,
+                                          const sk_tile *T_mem, const SplitK &sp, unsigned char *lds,
                                           uint32_t *s_flag) {
   const int cls = T.cls;
   if ((P.flags & (FLAG_VEC_A | FLAG_VEC_B)) != (FLAG_VEC_A | FLAG_VEC_B)) {
-    run_generic<DT>(P, T);
+    run_generic<DT>(P_mem, T_mem);
   } else if (cls == 0) {
     run_skinny<DT, 1>(P, T, sp, lds, s_flag);
   } else if (cls == 3) {
@@ -772,15 +791,18 @@ __global__ void __launch_bounds__(WG_THREADS, 3)
     uint32_t nxt = 0;
     if (a.dynamic && tid == 0) nxt = a.tile_begin + gridDim.x + atomicAdd(&a.counters[0], 1u);
 
-    const sk_tile T = tiles[t];
-    const DevProblem &P = probs[T.problem];
+    // The tile record and its operator's descriptor are the same for every lane: hold them in
+    // scalar registers, so that no later use is a memory access that the weight stream's
+    // in-order load counter would have to wait behind.
+    const sk_tile T = load_uniform(tiles + t);
+    const DevProblem P = load_uniform(probs + T.problem);
     if constexpr (ONLY_DT >= 0) {
-      run_class<ONLY_DT>(P, T, sp, lds, &s_flag);
+      run_class<ONLY_DT>(P, T, probs + T.problem, tiles + t, sp, lds, &s_flag);
     } else {
       switch (P.dtype) {
-        case SK_BF16: run_class<SK_BF16>(P, T, sp, lds, &s_flag); break;
-        case SK_F16: run_class<SK_F16>(P, T, sp, lds, &s_flag); break;
-        default: run_class<SK_F32>(P, T, sp, lds, &s_flag); break;
+        case SK_BF16: run_class<SK_BF16>(P, T, probs + T.problem, tiles + t, sp, lds, &s_flag); break;
+        case SK_F16: run_class<SK_F16>(P, T, probs + T.problem, tiles + t, sp, lds, &s_flag); break;
+        default: run_class<SK_F32>(P, T, probs + T.problem, tiles + t, sp, lds, &s_flag); break;
       }
     }
 
