@@ -58,6 +58,20 @@ __device__ __forceinline__ S load_uniform(const S *src) {
   return __builtin_bit_cast(S, v);
 }
 
+// The same from a copy in LDS.
+template <class S>
+__device__ __forceinline__ S unpack_uniform(const uint32_t *src) {
+  struct Words {
+    uint32_t w[sizeof(S) / 4];
+  } v;
+#pragma unroll
+  for (unsigned i = 0; i < sizeof(S) / 4; ++i) v.w[i] = (uint32_t)__builtin_amdgcn_readfirstlane((int)src[i]);
+  return __builtin_bit_cast(S, v);
+}
+
+constexpr int WORK_DWORDS = (int)(sizeof(TileWork) / 4);
+static_assert(WORK_DWORDS <= 64, "one dword of the record per lane");
+
 constexpr int WG_THREADS = 256;
 constexpr int LDS_ROW = 144;                  // 128 bytes of K + 16 bytes of padding (bank spread)
 constexpr int LDS_TILE_BYTES = 256 * LDS_ROW;  // 36 KB per workgroup: four workgroups share a CU's 160 KB
@@ -336,9 +350,28 @@ struct SplitK {
   uint32_t *arrive;         // per out_tile_id: slices that have delivered (re-armed by the last one)
 };
 
+// The workgroup's next work record, fetched while the current tile streams: lane i < WORK_DWORDS
+// of every wave loads dword i of the record (one register per lane).  `next` is the index the
+// tile queue returned; only thread 0 asked, so only wave 0 has the real one, and only wave 0's
+// copy is used.  issue() is called once per tile, after the tile's first loads are on their
+// way: the queue's answer has then had a load's latency to arrive, and the wait for it hides
+// behind the wait for those loads.
+struct Prefetch {
+  const TileWork *work;
+  uint32_t next;      // meaningful in lane 0 of wave 0 (and in all lanes when tiles are not handed out by the queue)
+  uint32_t last;      // last valid index of the launch
+  uint32_t word = 0;
+  __device__ __forceinline__ void issue() {
+    uint32_t idx = (uint32_t)__builtin_amdgcn_readfirstlane((int)next);
+    if (idx > last) idx = last;  // past the end of the table: the workgroup is about to leave
+    const int lane = threadIdx.x & 63;
+    word = as_global<uint32_t>(work + idx)[lane < WORK_DWORDS ? lane : 0];
+  }
+};
+
 template <int DT, int RM>
 __device__ __forceinline__ void run_skinny(const DevProblem &P, const sk_tile &T, const SplitK &sp,
-                                           unsigned char *lds, uint32_t *s_flag) {
+                                           unsigned char *lds, uint32_t *s_flag, Prefetch &pf) {
   constexpr int ES = Elem<DT>::ES;
   constexpr int CE = 16 / ES;
   constexpr int KB = 8 * CE;                        // reduction elements per block (128 bytes)
@@ -463,6 +496,7 @@ __device__ __forceinline__ void run_skinny(const DevProblem &P, const sk_tile &T
   u32x4 w[NB][4];
 #pragma unroll
   for (int u = 0; u < NB - 1; ++u) next_load(w[u]);
+  pf.issue();
   if (!restage_each) {
     // the only activation chunk serves every pass
     stage_store(0);
@@ -563,7 +597,7 @@ __device__ __forceinline__ void run_skinny(const DevProblem &P, const sk_tile &T
 // LDS-staged tiles: BM x BN outputs per workgroup, 128 bytes of K per stage
 // ---------------------------------------------------------------------------
 template <int DT, int BM, int BN, int WAVES_M, int WAVES_N>
-__device__ __forceinline__ void run_tile(const DevProblem &P, const sk_tile &T, unsigned char *lds) {
+__device__ __forceinline__ void run_tile(const DevProblem &P, const sk_tile &T, unsigned char *lds, Prefetch &pf) {
   constexpr int ES = Elem<DT>::ES;
   constexpr int CE = 16 / ES;
   constexpr int KB = 8 * CE;                  // reduction elements per stage
@@ -664,6 +698,7 @@ __device__ __forceinline__ void run_tile(const DevProblem &P, const sk_tile &T, 
   };
 
   gload(k_begin);
+  pf.issue();
   for (int kb = k_begin; kb < k_stop; kb += KB) {
     lstore();
     __syncthreads();
@@ -755,59 +790,64 @@ __device__ void run_generic(const DevProblem *P_mem, const sk_tile *T_mem) {
 template <int DT>
 __device__ __forceinline__ void run_class(const DevProblem &P, const sk_tile &T, const DevProblem *P_mem,
                                           const sk_tile *T_mem, const SplitK &sp, unsigned char *lds,
-                                          uint32_t *s_flag) {
+                                          uint32_t *s_flag, Prefetch &pf) {
   const int cls = T.cls;
   if ((P.flags & (FLAG_VEC_A | FLAG_VEC_B)) != (FLAG_VEC_A | FLAG_VEC_B)) {
+    pf.issue();
     run_generic<DT>(P_mem, T_mem);
   } else if (cls == 0) {
-    run_skinny<DT, 1>(P, T, sp, lds, s_flag);
+    run_skinny<DT, 1>(P, T, sp, lds, s_flag, pf);
   } else if (cls == 3) {
-    run_skinny<DT, 2>(P, T, sp, lds, s_flag);
+    run_skinny<DT, 2>(P, T, sp, lds, s_flag, pf);
   } else if (cls == 6) {
-    run_skinny<DT, 4>(P, T, sp, lds, s_flag);
+    run_skinny<DT, 4>(P, T, sp, lds, s_flag, pf);
   } else {
-    run_tile<DT, 64, 128, 1, 4>(P, T, lds);
+    run_tile<DT, 64, 128, 1, 4>(P, T, lds, pf);
   }
 }
 
 // ONLY_DT >= 0: every operator of the plan has that element type (one third of the
 // code, fewer registers); ONLY_DT < 0: operators of mixed types.
 template <int ONLY_DT>
-__global__ void __launch_bounds__(WG_THREADS, 3)
-    sk_superkernel(const sk_tile *__restrict__ tiles, const DevProblem *__restrict__ probs, KernelArgs a) {
+__global__ void __launch_bounds__(WG_THREADS, 3) sk_superkernel(const TileWork *__restrict__ work, KernelArgs a) {
   __shared__ __attribute__((aligned(16))) unsigned char lds[LDS_TILE_BYTES];
-  __shared__ uint32_t s_next[2];
+  __shared__ __attribute__((aligned(16))) uint32_t s_mail[2][WORK_DWORDS + 4];  // next record + its index, by parity
   __shared__ uint32_t s_flag;
   const SplitK sp{a.ws, a.ws_off, a.arrive};
 
   const int tid = threadIdx.x;
   if (a.write_start && a.stamps && blockIdx.x == 0 && tid == 0) a.stamps[a.n_problems] = wall_clock64();
 
+  // The first tile of every workgroup is fixed (its block index); further tiles come from the
+  // queue.  (The host never launches more workgroups than tiles.)
   uint32_t t = a.tile_begin + blockIdx.x;
+  TileWork W = load_uniform(work + (t < a.tile_end ? t : a.tile_end - 1u));
   int par = 0;
   while (t < a.tile_end) {
-    t = __builtin_amdgcn_readfirstlane(t);
-    // ask for the next tile now; the answer is only needed after this one
-    uint32_t nxt = 0;
-    if (a.dynamic && tid == 0) nxt = a.tile_begin + gridDim.x + atomicAdd(&a.counters[0], 1u);
-
-    // The tile record and its operator's descriptor are the same for every lane: hold them in
-    // scalar registers, so that no later use is a memory access that the weight stream's
-    // in-order load counter would have to wait behind.
-    const sk_tile T = load_uniform(tiles + t);
-    const DevProblem P = load_uniform(probs + T.problem);
+    // ask for the next tile now; the answer is used to prefetch its record during this tile
+    Prefetch pf{work, t + gridDim.x, a.tile_end - 1u};
+    if (a.dynamic) {
+      pf.next = 0u;
+      if (tid == 0) pf.next = a.tile_begin + gridDim.x + atomicAdd(&a.counters[0], 1u);
+    }
+    const sk_tile &T = W.tile;
+    const DevProblem &P = W.prob;
     if constexpr (ONLY_DT >= 0) {
-      run_class<ONLY_DT>(P, T, probs + T.problem, tiles + t, sp, lds, &s_flag);
+      run_class<ONLY_DT>(P, T, &work[t].prob, &work[t].tile, sp, lds, &s_flag, pf);
     } else {
       switch (P.dtype) {
-        case SK_BF16: run_class<SK_BF16>(P, T, probs + T.problem, tiles + t, sp, lds, &s_flag); break;
-        case SK_F16: run_class<SK_F16>(P, T, probs + T.problem, tiles + t, sp, lds, &s_flag); break;
-        default: run_class<SK_F32>(P, T, probs + T.problem, tiles + t, sp, lds, &s_flag); break;
+        case SK_BF16: run_class<SK_BF16>(P, T, &work[t].prob, &work[t].tile, sp, lds, &s_flag, pf); break;
+        case SK_F16: run_class<SK_F16>(P, T, &work[t].prob, &work[t].tile, sp, lds, &s_flag, pf); break;
+        default: run_class<SK_F32>(P, T, &work[t].prob, &work[t].tile, sp, lds, &s_flag, pf); break;
       }
     }
 
     if (a.remaining) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    if (a.dynamic && tid == 0) s_next[par] = nxt;
+    if (tid < 64) {
+      // wave 0 hands the next record to the other waves
+      if (tid < WORK_DWORDS) s_mail[par][tid] = pf.word;
+      if (tid == 0) s_mail[par][WORK_DWORDS] = pf.next;
+    }
     __syncthreads();
     if (a.remaining && tid == 0) {
       // the workgroup that retires an operator's last tile stamps it and re-arms the count
@@ -817,7 +857,8 @@ __global__ void __launch_bounds__(WG_THREADS, 3)
         a.remaining[T.problem] = (uint32_t)P.tile_count;
       }
     }
-    t = a.dynamic ? s_next[par] : t + gridDim.x;
+    t = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_mail[par][WORK_DWORDS]);
+    W = unpack_uniform<TileWork>(s_mail[par]);
     par ^= 1;
   }
 

@@ -41,6 +41,16 @@ struct DevProblem {
 };
 static_assert(sizeof(DevProblem) % 8 == 0, "DevProblem must stay 8-byte sized");
 
+// What the device reads per tile: the record of the tile table with a copy of its operator's
+// descriptor beside it, so that one fetch (and one prefetch) brings everything a workgroup
+// needs to start the tile.
+struct TileWork {
+  sk_tile tile;
+  DevProblem prob;
+  uint32_t pad[2];
+};
+static_assert(sizeof(TileWork) == 160, "TileWork layout");
+
 struct HostPlan {
   std::vector<sk_problem> problems;
   std::vector<DevProblem> dev;

@@ -37,11 +37,10 @@ struct sk_plan {
   int64_t grid_cap = 0;  // most workgroups any launch of this plan may use
   int only_dtype = -1;   // the element type all operators share, or -1 if they differ
   double ticks_per_ms = 0.0;
-  // one device allocation: tiles | operator descriptors | counters | remaining | stamps |
-  // split-K offsets | split-K arrival counters | split-K workspace
+  // one device allocation: work records (tile + its operator's descriptor) | counters |
+  // remaining | stamps | split-K offsets | split-K arrival counters | split-K workspace
   void *blob = nullptr;
-  sk_tile *d_tiles = nullptr;
-  sk::DevProblem *d_probs = nullptr;
+  sk::TileWork *d_work = nullptr;
   uint32_t *d_counters = nullptr;
   uint32_t *d_remaining = nullptr;
   uint64_t *d_stamps = nullptr;
@@ -94,9 +93,8 @@ sk_status sk_plan_create(const sk_problem *problems, int32_t n, const sk_plan_pa
     plan->grid = (int)(ntiles < limit ? ntiles : limit);
 
     const size_t nt = plan->host.tiles.size(), np = plan->host.dev.size();
-    const size_t off_tiles = 0;
-    const size_t off_probs = align_up(off_tiles + nt * sizeof(sk_tile), 256);
-    const size_t off_cnt = align_up(off_probs + np * sizeof(sk::DevProblem), 256);
+    const size_t off_work = 0;
+    const size_t off_cnt = align_up(off_work + nt * sizeof(sk::TileWork), 256);
     const size_t off_rem = align_up(off_cnt + 2 * sizeof(uint32_t), 256);
     const size_t off_stamps = align_up(off_rem + np * sizeof(uint32_t), 256);
     const size_t nrect = plan->host.ws_off.size();
@@ -112,8 +110,13 @@ sk_status sk_plan_create(const sk_problem *problems, int32_t n, const sk_plan_pa
       return set_error(SK_ERR_ALLOC, "host staging allocation failed");
     }
     if (nrect) std::memcpy(&stage[off_wsoff], plan->host.ws_off.data(), nrect * sizeof(uint32_t));
-    if (nt) std::memcpy(&stage[off_tiles], plan->host.tiles.data(), nt * sizeof(sk_tile));
-    if (np) std::memcpy(&stage[off_probs], plan->host.dev.data(), np * sizeof(sk::DevProblem));
+    for (size_t i = 0; i < nt; ++i) {
+      sk::TileWork w;
+      std::memset(&w, 0, sizeof(w));
+      w.tile = plan->host.tiles[i];
+      w.prob = plan->host.dev[w.tile.problem];
+      std::memcpy(&stage[off_work + i * sizeof(w)], &w, sizeof(w));
+    }
     for (size_t i = 0; i < np; ++i) {
       const uint32_t c = (uint32_t)plan->host.count[i];
       std::memcpy(&stage[off_rem + i * sizeof(uint32_t)], &c, sizeof(c));
@@ -130,8 +133,7 @@ sk_status sk_plan_create(const sk_problem *problems, int32_t n, const sk_plan_pa
       return hip_error("hipMemcpy", e);
     }
     char *b = (char *)plan->blob;
-    plan->d_tiles = (sk_tile *)(b + off_tiles);
-    plan->d_probs = (sk::DevProblem *)(b + off_probs);
+    plan->d_work = (sk::TileWork *)(b + off_work);
     plan->d_counters = (uint32_t *)(b + off_cnt);
     plan->d_remaining = (uint32_t *)(b + off_rem);
     plan->d_stamps = (uint64_t *)(b + off_stamps);
@@ -173,16 +175,16 @@ static sk_status launch_range(sk_plan *plan, hipStream_t stream, uint32_t begin,
   const dim3 g((unsigned)grid), b(sk::WG_THREADS);
   switch (plan->only_dtype) {
     case SK_F32:
-      hipLaunchKernelGGL(sk::sk_superkernel<SK_F32>, g, b, 0, stream, plan->d_tiles, plan->d_probs, a);
+      hipLaunchKernelGGL(sk::sk_superkernel<SK_F32>, g, b, 0, stream, plan->d_work, a);
       break;
     case SK_BF16:
-      hipLaunchKernelGGL(sk::sk_superkernel<SK_BF16>, g, b, 0, stream, plan->d_tiles, plan->d_probs, a);
+      hipLaunchKernelGGL(sk::sk_superkernel<SK_BF16>, g, b, 0, stream, plan->d_work, a);
       break;
     case SK_F16:
-      hipLaunchKernelGGL(sk::sk_superkernel<SK_F16>, g, b, 0, stream, plan->d_tiles, plan->d_probs, a);
+      hipLaunchKernelGGL(sk::sk_superkernel<SK_F16>, g, b, 0, stream, plan->d_work, a);
       break;
     default:
-      hipLaunchKernelGGL(sk::sk_superkernel<-1>, g, b, 0, stream, plan->d_tiles, plan->d_probs, a);
+      hipLaunchKernelGGL(sk::sk_superkernel<-1>, g, b, 0, stream, plan->d_work, a);
       break;
   }
   hipError_t e = hipGetLastError();
