@@ -360,11 +360,12 @@ struct Prefetch {
   const TileWork *work;
   uint32_t next;      // meaningful in lane 0 of wave 0 (and in all lanes when tiles are not handed out by the queue)
   uint32_t last;      // last valid index of the launch
+  int tid;            // this tile's copy of the thread index (see the tile loop)
   uint32_t word = 0;
   __device__ __forceinline__ void issue() {
     uint32_t idx = (uint32_t)__builtin_amdgcn_readfirstlane((int)next);
     if (idx > last) idx = last;  // past the end of the table: the workgroup is about to leave
-    const int lane = threadIdx.x & 63;
+    const int lane = tid & 63;
     word = as_global<uint32_t>(work + idx)[lane < WORK_DWORDS ? lane : 0];
   }
 };
@@ -386,7 +387,7 @@ __device__ __forceinline__ void run_skinny(const DevProblem &P, const sk_tile &T
   static_assert(ROWB == BPC * 128, "chunk geometry");
   static_assert(2 * BUF <= LDS_TILE_BYTES, "activation chunks do not fit");
 
-  const int tid = threadIdx.x;
+  const int tid = pf.tid;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps its branches scalar
   const int lane = tid & 63;
   const int r16 = lane & 15, q = lane >> 4;
@@ -608,7 +609,7 @@ __device__ __forceinline__ void run_tile(const DevProblem &P, const sk_tile &T, 
   static_assert(WAVES_M * WAVES_N == 4, "four waves per workgroup");
   static_assert((BM + BN) * LDS_ROW <= LDS_TILE_BYTES, "tile does not fit the LDS buffer");
 
-  const int tid = threadIdx.x;
+  const int tid = pf.tid;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63;
   const int wm = wave % WAVES_M, wn = wave / WAVES_M;
@@ -647,8 +648,13 @@ __device__ __forceinline__ void run_tile(const DevProblem &P, const sk_tile &T, 
       for (int i = 0; i < 16; ++i) acc[fn][fm][i] = 0.f;
 
   const int k_begin = (int)T.k0, k_stop = (int)T.k0 + (int)T.k_len;
-  u32x4 ra[A_ITERS], rb[B_ITERS];
-  bool ra_ok[A_ITERS];
+  // Operand pieces travel global memory -> registers -> LDS.  A ring of NS stages of registers
+  // keeps NS-1 stages of loads in flight while one stage is multiplied: next to workgroups
+  // that stream weights at the memory system's limit a load takes microseconds, far longer
+  // than the MFMAs of a stage.
+  constexpr int NS = 3;
+  u32x4 ra[NS][A_ITERS], rb[NS][B_ITERS];
+  bool ra_ok[NS][A_ITERS];
 
   // Implicit GEMM: the piece column of this thread walks through the filter taps
   // (r, s) and channels c as K advances; keep that position incrementally.
@@ -661,15 +667,19 @@ __device__ __forceinline__ void run_tile(const DevProblem &P, const sk_tile &T, 
     g_r = tap / P.S;
     g_s = tap - g_r * P.S;
   }
-  auto gload = [&](int kbase) {
-    const int k = kbase + c8 * CE;
+  // Loads are unconditional (stages past the end of the reduction read clamped addresses and
+  // are never stored), so the number of loads in flight is the same on every path.
+  int k_load = k_begin;  // reduction index of the next stage to load
+  auto gload = [&](u32x4(&xa)[A_ITERS], u32x4(&xb)[B_ITERS], bool(&xok)[A_ITERS]) {
+    const int k = k_load + c8 * CE;
+    k_load += KB;
     if (gvec) {
       const int64_t tap_off = ((int64_t)g_r * P.W + g_s) * P.Cin + g_c;
 #pragma unroll
       for (int i = 0; i < A_ITERS; ++i) {
-        ra_ok[i] = k < k_stop && (unsigned)(rowa[i].hb + g_r) < (unsigned)P.H &&
-                   (unsigned)(rowa[i].wb + g_s) < (unsigned)P.W;
-        ra[i] = load_piece_vec<ES, false>(P.A, ra_ok[i] ? rowa[i].base + tap_off : 0);
+        xok[i] = k < k_stop && (unsigned)(rowa[i].hb + g_r) < (unsigned)P.H &&
+                 (unsigned)(rowa[i].wb + g_s) < (unsigned)P.W;
+        xa[i] = load_piece_vec<ES, false>(P.A, xok[i] ? rowa[i].base + tap_off : 0);
       }
       g_c += KB;
       while (g_c >= P.Cin) {
@@ -682,43 +692,50 @@ __device__ __forceinline__ void run_tile(const DevProblem &P, const sk_tile &T, 
     } else {
 #pragma unroll
       for (int i = 0; i < A_ITERS; ++i) {
-        ra_ok[i] = k < k_stop;
-        ra[i] = fetch_A<ES>(P, rowa[i], k, ra_ok[i]);
+        xok[i] = k < k_stop;
+        xa[i] = fetch_A<ES>(P, rowa[i], k, xok[i]);
       }
     }
 #pragma unroll
-    for (int i = 0; i < B_ITERS; ++i) rb[i] = fetch_B<ES, false>(P, wrow[i], k, k < k_stop);
+    for (int i = 0; i < B_ITERS; ++i) xb[i] = fetch_B<ES, false>(P, wrow[i], k, k < k_stop);
   };
-  auto lstore = [&]() {
+  auto lstore = [&](const u32x4(&xa)[A_ITERS], const u32x4(&xb)[B_ITERS], const bool(&xok)[A_ITERS]) {
 #pragma unroll
     for (int i = 0; i < A_ITERS; ++i)
-      *(u32x4 *)(ldsA + (srow + 32 * i) * LDS_ROW + c8 * 16) = keep_if(ra_ok[i], ra[i]);
+      *(u32x4 *)(ldsA + (srow + 32 * i) * LDS_ROW + c8 * 16) = keep_if(xok[i], xa[i]);
 #pragma unroll
-    for (int i = 0; i < B_ITERS; ++i) *(u32x4 *)(ldsB + (srow + 32 * i) * LDS_ROW + c8 * 16) = rb[i];
+    for (int i = 0; i < B_ITERS; ++i) *(u32x4 *)(ldsB + (srow + 32 * i) * LDS_ROW + c8 * 16) = xb[i];
   };
 
-  gload(k_begin);
+#pragma unroll
+  for (int u = 0; u < NS - 1; ++u) gload(ra[u], rb[u], ra_ok[u]);
   pf.issue();
-  for (int kb = k_begin; kb < k_stop; kb += KB) {
-    lstore();
-    __syncthreads();
-    if (kb + KB < k_stop) gload(kb + KB);  // in flight while this stage is multiplied
+  const int nstages = (k_stop - k_begin + KB - 1) / KB;
+  for (int s0 = 0; s0 < nstages; s0 += NS) {
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      const int piece = (2 * kk + half) * 16;
-      u32x4 fa[FM], fb[FN];
+    for (int u = 0; u < NS; ++u) {
+      gload(ra[(u + NS - 1) % NS], rb[(u + NS - 1) % NS], ra_ok[(u + NS - 1) % NS]);
+      if (s0 + u < nstages) {
+        lstore(ra[u], rb[u], ra_ok[u]);
+        __syncthreads();
 #pragma unroll
-      for (int fm = 0; fm < FM; ++fm)
-        fa[fm] = *(const u32x4 *)(ldsA + ((wm * FM + fm) * 32 + l32) * LDS_ROW + piece);
+        for (int kk = 0; kk < 4; ++kk) {
+          const int piece = (2 * kk + half) * 16;
+          u32x4 fa[FM], fb[FN];
 #pragma unroll
-      for (int fn = 0; fn < FN; ++fn)
-        fb[fn] = *(const u32x4 *)(ldsB + ((wn * FN + fn) * 32 + l32) * LDS_ROW + piece);
+          for (int fm = 0; fm < FM; ++fm)
+            fa[fm] = *(const u32x4 *)(ldsA + ((wm * FM + fm) * 32 + l32) * LDS_ROW + piece);
 #pragma unroll
-      for (int fn = 0; fn < FN; ++fn)
+          for (int fn = 0; fn < FN; ++fn)
+            fb[fn] = *(const u32x4 *)(ldsB + ((wn * FN + fn) * 32 + l32) * LDS_ROW + piece);
 #pragma unroll
-        for (int fm = 0; fm < FM; ++fm) mma32<DT>(fb[fn], fa[fm], acc[fn][fm]);
+          for (int fn = 0; fn < FN; ++fn)
+#pragma unroll
+            for (int fm = 0; fm < FM; ++fm) mma32<DT>(fb[fn], fa[fm], acc[fn][fm]);
+        }
+        __syncthreads();
+      }
     }
-    __syncthreads();
   }
 
   // lane holds, per (fn, fm): row m = l32, columns 8*(i/4) + 4*half + (i%4)
@@ -815,8 +832,7 @@ __global__ void __launch_bounds__(WG_THREADS, 3) sk_superkernel(const TileWork *
   __shared__ uint32_t s_flag;
   const SplitK sp{a.ws, a.ws_off, a.arrive};
 
-  const int tid = threadIdx.x;
-  if (a.write_start && a.stamps && blockIdx.x == 0 && tid == 0) a.stamps[a.n_problems] = wall_clock64();
+  if (a.write_start && a.stamps && blockIdx.x == 0 && threadIdx.x == 0) a.stamps[a.n_problems] = wall_clock64();
 
   // The first tile of every workgroup is fixed (its block index); further tiles come from the
   // queue.  (The host never launches more workgroups than tiles.)
@@ -824,8 +840,14 @@ __global__ void __launch_bounds__(WG_THREADS, 3) sk_superkernel(const TileWork *
   TileWork W = load_uniform(work + (t < a.tile_end ? t : a.tile_end - 1u));
   int par = 0;
   while (t < a.tile_end) {
+    // Everything a tile derives from the thread index is derived again for each tile, from a
+    // copy the compiler cannot see through: hoisted out of this loop those values would stay
+    // live across all tile classes, spill, and every reload of a spilled register waits for all
+    // the loads and stores in flight.
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
     // ask for the next tile now; the answer is used to prefetch its record during this tile
-    Prefetch pf{work, t + gridDim.x, a.tile_end - 1u};
+    Prefetch pf{work, t + gridDim.x, a.tile_end - 1u, tid};
     if (a.dynamic) {
       pf.next = 0u;
       if (tid == 0) pf.next = a.tile_begin + gridDim.x + atomicAdd(&a.counters[0], 1u);
@@ -863,7 +885,7 @@ __global__ void __launch_bounds__(WG_THREADS, 3) sk_superkernel(const TileWork *
   }
 
   // the last workgroup to leave re-arms the queue for the next launch
-  if (a.dynamic && tid == 0) {
+  if (a.dynamic && threadIdx.x == 0) {
     const uint32_t done = atomicAdd(&a.counters[1], 1u);
     if (done == gridDim.x - 1) {
       a.counters[0] = 0u;
