@@ -350,25 +350,46 @@ struct SplitK {
   uint32_t *arrive;         // per out_tile_id: slices that have delivered (re-armed by the last one)
 };
 
-// The workgroup's next work record, fetched while the current tile streams: lane i < WORK_DWORDS
-// of every wave loads dword i of the record (one register per lane).  `next` is the index the
-// tile queue returned; only thread 0 asked, so only wave 0 has the real one, and only wave 0's
-// copy is used.  issue() is called once per tile, after the tile's first loads are on their
-// way: the queue's answer has then had a load's latency to arrive, and the wait for it hides
-// behind the wait for those loads.
+// The workgroup's next tile: claimed from the queue and its work record fetched while the
+// current tile is still streaming, in two steps that each tile class places in its main loop.
+//   claim(): thread 0 takes the next index from the queue (an atomic whose answer takes a
+//     memory round trip).  Late in the tile, not at its start: a claimed tile cannot start
+//     before its workgroup is free, so at the end of the launch tiles claimed early would
+//     wait behind long tiles while other workgroups sit idle.
+//   issue(): once the answer is there, lane i < WORK_DWORDS of every wave loads dword i of the
+//     record (one register per lane).  Only wave 0 has the real index, and only its copy is
+//     used.
+// CLAIM_LEAD / ISSUE_GAP are counted in steps of the class's main loop (a step is one to two
+// microseconds when the memory system is loaded).
 struct Prefetch {
   const TileWork *work;
-  uint32_t next;      // meaningful in lane 0 of wave 0 (and in all lanes when tiles are not handed out by the queue)
+  uint32_t *counter;  // the queue (null: tiles are not handed out by the queue)
+  uint32_t base;      // index of the first tile the queue hands out
+  uint32_t next;      // meaningful in lane 0 of wave 0 (in all lanes when there is no queue)
   uint32_t last;      // last valid index of the launch
   int tid;            // this tile's copy of the thread index (see the tile loop)
   uint32_t word = 0;
+  __device__ __forceinline__ void claim() {
+    if (counter) {
+      next = 0u;
+      if (tid == 0) next = base + atomicAdd(counter, 1u);
+    }
+  }
   __device__ __forceinline__ void issue() {
     uint32_t idx = (uint32_t)__builtin_amdgcn_readfirstlane((int)next);
     if (idx > last) idx = last;  // past the end of the table: the workgroup is about to leave
     const int lane = tid & 63;
     word = as_global<uint32_t>(work + idx)[lane < WORK_DWORDS ? lane : 0];
   }
+  // step `i` of `total` main-loop steps
+  __device__ __forceinline__ void at_step(int i, int total, int lead, int gap) {
+    const int claim_at = total > lead ? total - lead : 0;
+    const int issue_at = claim_at + gap < total ? claim_at + gap : total - 1;
+    if (i == claim_at) claim();
+    if (i == issue_at) issue();
+  }
 };
+constexpr int CLAIM_LEAD = 8, ISSUE_GAP = 4;
 
 template <int DT, int RM>
 __device__ __forceinline__ void run_skinny(const DevProblem &P, const sk_tile &T, const SplitK &sp,
@@ -497,7 +518,6 @@ __device__ __forceinline__ void run_skinny(const DevProblem &P, const sk_tile &T
   u32x4 w[NB][4];
 #pragma unroll
   for (int u = 0; u < NB - 1; ++u) next_load(w[u]);
-  pf.issue();
   if (!restage_each) {
     // the only activation chunk serves every pass
     stage_store(0);
@@ -510,6 +530,7 @@ __device__ __forceinline__ void run_skinny(const DevProblem &P, const sk_tile &T
 #pragma unroll
     for (int u = 0; u < NB; ++u) {
       const bool live = i0 + u < total;
+      pf.at_step(i0 + u, total, CLAIM_LEAD, ISSUE_GAP);
       if (live && restage_each && (blk & (BPC - 1)) == 0) {
         // first block of a chunk: publish it, then start fetching the one after it
         // (chunk c+1 of this pass, or chunk 0 again for the next pass)
@@ -709,11 +730,11 @@ __device__ __forceinline__ void run_tile(const DevProblem &P, const sk_tile &T, 
 
 #pragma unroll
   for (int u = 0; u < NS - 1; ++u) gload(ra[u], rb[u], ra_ok[u]);
-  pf.issue();
   const int nstages = (k_stop - k_begin + KB - 1) / KB;
   for (int s0 = 0; s0 < nstages; s0 += NS) {
 #pragma unroll
     for (int u = 0; u < NS; ++u) {
+      pf.at_step(s0 + u, nstages, CLAIM_LEAD, ISSUE_GAP);
       gload(ra[(u + NS - 1) % NS], rb[(u + NS - 1) % NS], ra_ok[(u + NS - 1) % NS]);
       if (s0 + u < nstages) {
         lstore(ra[u], rb[u], ra_ok[u]);
@@ -810,6 +831,7 @@ __device__ __forceinline__ void run_class(const DevProblem &P, const sk_tile &T,
                                           uint32_t *s_flag, Prefetch &pf) {
   const int cls = T.cls;
   if ((P.flags & (FLAG_VEC_A | FLAG_VEC_B)) != (FLAG_VEC_A | FLAG_VEC_B)) {
+    pf.claim();
     pf.issue();
     run_generic<DT>(P_mem, T_mem);
   } else if (cls == 0) {
@@ -846,12 +868,8 @@ __global__ void __launch_bounds__(WG_THREADS, 3) sk_superkernel(const TileWork *
     // the loads and stores in flight.
     int tid = threadIdx.x;
     asm volatile("" : "+v"(tid));
-    // ask for the next tile now; the answer is used to prefetch its record during this tile
-    Prefetch pf{work, t + gridDim.x, a.tile_end - 1u, tid};
-    if (a.dynamic) {
-      pf.next = 0u;
-      if (tid == 0) pf.next = a.tile_begin + gridDim.x + atomicAdd(&a.counters[0], 1u);
-    }
+    Prefetch pf{work, a.dynamic ? &a.counters[0] : nullptr, a.tile_begin + gridDim.x, t + gridDim.x, a.tile_end - 1u,
+                tid};
     const sk_tile &T = W.tile;
     const DevProblem &P = W.prob;
     if constexpr (ONLY_DT >= 0) {
