@@ -99,7 +99,8 @@ typedef struct {
   int32_t skinny_max_m;   /* operators with at most this many rows stream their weights      */
                           /* straight to registers ("skinny" classes); 0..64, default 64     */
   int64_t tile_bytes_max; /* skinny tiles: upper/lower clamp of the target weight bytes per  */
-  int64_t tile_bytes_min; /* tile; the target is sum(weight bytes) / balance_div             */
+  int64_t tile_bytes_min; /* tile (defaults 2 MiB, 32 KiB); the target is                    */
+                          /* sum(weight bytes) / balance_div                                 */
   int32_t balance_div;    /* default 2048                                                    */
   int32_t max_groups;     /* cap on 32-row weight groups per skinny tile, default 256        */
   int32_t grid_limit;     /* upper bound on persistent workgroups per launch;                */

@@ -48,7 +48,7 @@ CLS_TILE_64x128 = 9
 class Params:
     edf: int = 1
     skinny_max_m: int = 64          # <= 64
-    tile_bytes_max: int = 512 * 1024
+    tile_bytes_max: int = 2048 * 1024
     tile_bytes_min: int = 32 * 1024
     balance_div: int = 2048
     max_groups: int = 256

@@ -284,7 +284,7 @@ extern "C" void sk_plan_params_default(sk_plan_params *p) {
   p->stamps = 0;
   p->host_only = 0;
   p->skinny_max_m = 64;
-  p->tile_bytes_max = 512 * 1024;
+  p->tile_bytes_max = 2048 * 1024;
   p->tile_bytes_min = 32 * 1024;
   p->balance_div = 2048;
   p->max_groups = 256;

@@ -117,8 +117,10 @@ def test_target_bytes_rule():
     prm = P.Params()
     small = [gemm(1, 256, 256, "f32")]
     assert P.target_tile_bytes(small, prm) == prm.tile_bytes_min
-    big = [gemm(1, 8192, 8192)] * 8      # 8 x 128 MiB of weights / 2048 = 512 KiB -> clamped
-    assert P.target_tile_bytes(big, prm) == prm.tile_bytes_max
+    big = [gemm(1, 8192, 8192)] * 8      # 8 x 128 MiB of weights / 2048 = 512 KiB
+    assert P.target_tile_bytes(big, prm) == 512 * 1024
+    huge = [gemm(1, 8192, 8192)] * 64    # 8 GiB / 2048 = 4 MiB -> clamped to 2 MiB
+    assert P.target_tile_bytes(huge, prm) == prm.tile_bytes_max == 2048 * 1024
     mid = [gemm(1, 4096, 4096)] * 4      # 128 MiB / 2048 = 64 KiB
     assert P.target_tile_bytes(mid, prm) == 65536
 
