@@ -105,7 +105,10 @@ typedef struct {
   int32_t max_groups;     /* cap on 32-row weight groups per skinny tile, default 256        */
   int32_t grid_limit;     /* upper bound on persistent workgroups per launch;                */
                           /* 0 = 3 per compute unit of the current device                    */
-  int32_t reserved;
+  int32_t tail_div;       /* tiles shrink towards the end of the table: an operator's target */
+                          /* is also capped by (weight bytes of it and of all operators      */
+                          /* after it in execution order) / tail_div, so that the launch     */
+                          /* does not end on a few long tiles; 0 = off, default 512          */
 } sk_plan_params;
 
 /*

@@ -52,6 +52,7 @@ class Params:
     tile_bytes_min: int = 32 * 1024
     balance_div: int = 2048
     max_groups: int = 256
+    tail_div: int = 512             # 0: tiles do not shrink towards the end of the table
 
 
 def canonical(p):
@@ -76,11 +77,13 @@ def order(problems: Sequence, edf: int = 1) -> List[int]:
     return sorted(range(n), key=lambda i: (_deadline_key(problems[i].deadline_ms), i))
 
 
+def weight_bytes(p) -> int:
+    _, ng, kg = canonical(p)
+    return ng * kg * ELEM_SIZE[p.dtype]
+
+
 def target_tile_bytes(problems: Sequence, prm: Params) -> int:
-    total = 0
-    for p in problems:
-        _, ng, kg = canonical(p)
-        total += ng * kg * ELEM_SIZE[p.dtype]
+    total = sum(weight_bytes(p) for p in problems)
     return max(prm.tile_bytes_min, min(prm.tile_bytes_max, total // prm.balance_div))
 
 
@@ -111,15 +114,20 @@ def plan(problems: Sequence, prm: Params | None = None):
     """Returns (table_bytes, order, first_tile[n], tile_count[n]) -- first/count by submission index."""
     prm = prm or Params()
     n = len(problems)
-    T = target_tile_bytes(problems, prm) if n else prm.tile_bytes_min
+    T_all = target_tile_bytes(problems, prm) if n else prm.tile_bytes_min
     ordr = order(problems, prm.edf)
     first = [0] * n
     count = [0] * n
     recs = []
     out_id = 0
-    for i in ordr:
+    for pos, i in enumerate(ordr):
         p = problems[i]
         mg, ng, kg = canonical(p)
+        T = T_all
+        if prm.tail_div > 0:
+            # weight bytes of this operator and of all that execute after it
+            remaining = sum(weight_bytes(problems[j]) for j in ordr[pos:])
+            T = max(prm.tile_bytes_min, min(T_all, remaining // prm.tail_div))
         cls, BM, BN, S, slice_len = tiling(p, T, prm)
         first[i] = len(recs)
         for m0 in range(0, mg, BM):

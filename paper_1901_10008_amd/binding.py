@@ -44,7 +44,7 @@ class PlanParams(C.Structure):
         ("edf", C.c_int32), ("stamps", C.c_int32), ("host_only", C.c_int32), ("skinny_max_m", C.c_int32),
         ("tile_bytes_max", C.c_int64), ("tile_bytes_min", C.c_int64),
         ("balance_div", C.c_int32), ("max_groups", C.c_int32), ("grid_limit", C.c_int32),
-        ("reserved", C.c_int32),
+        ("tail_div", C.c_int32),
     ]
 
 

@@ -101,7 +101,7 @@ sk_status plan_host(const sk_problem *problems, int32_t n, const sk_plan_params 
     sk_plan_params_default(&prm);
   if (prm.skinny_max_m < 0 || prm.skinny_max_m > 64 || prm.tile_bytes_min < 1 ||
       prm.tile_bytes_max < prm.tile_bytes_min || prm.balance_div < 1 || prm.max_groups < 1 ||
-      prm.max_groups > 256 || prm.grid_limit < 0) {
+      prm.max_groups > 256 || prm.grid_limit < 0 || prm.tail_div < 0) {
     err = "sk_plan_params field out of range";
     return SK_ERR_INVALID_ARG;
   }
@@ -203,12 +203,23 @@ sk_status plan_host(const sk_problem *problems, int32_t n, const sk_plan_params 
     });
   }
 
+  // ---- weight bytes from each position of the order to its end ----
+  std::vector<int64_t> remaining(n + 1, 0);
+  for (int32_t pos = n - 1; pos >= 0; --pos) {
+    const int32_t i = out.order[pos];
+    remaining[pos] = remaining[pos + 1] + canon[i].Ng * canon[i].Kg * elem_size(out.problems[i].dtype);
+  }
+
   // ---- flat table ----
+  const int64_t T_all = T;
   uint32_t out_id = 0;
   for (int32_t pos = 0; pos < n; ++pos) {
     const int32_t i = out.order[pos];
     const Canon &c = canon[i];
     const int es = elem_size(out.problems[i].dtype);
+    // towards the end of the table the target shrinks with what is left to do
+    T = T_all;
+    if (prm.tail_div > 0) T = std::max<int64_t>(prm.tile_bytes_min, std::min<int64_t>(T_all, remaining[pos] / prm.tail_div));
     uint16_t cls;
     int64_t BM, BN;
     int64_t S = 1, slice_len = c.Kg;  // reduction slices per output rectangle and their length
@@ -289,4 +300,5 @@ extern "C" void sk_plan_params_default(sk_plan_params *p) {
   p->balance_div = 2048;
   p->max_groups = 256;
   p->grid_limit = 0;
+  p->tail_div = 512;
 }

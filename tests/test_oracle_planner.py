@@ -69,6 +69,33 @@ def test_hand_enumerated_reduction_slices():
     assert [(x["k0"], x["k_len"]) for x in t] == [(0, 1024), (1024, 1024), (2048, 512)]
 
 
+def test_hand_enumerated_tail_rule():
+    # three operators of 2 MiB of weights each; T_all = 6 MiB / 16 = 384 KiB.  With tail_div = 16 the operator
+    # at position 0 may use min(384, 6 MiB/16 = 384) KiB, the next min(384, 4 MiB/16 = 256) KiB and the last
+    # min(384, 2 MiB/16 = 128) KiB.  One 32-row group is 64 KiB, four groups 256 KiB: the first two operators
+    # get 128-row tiles over the whole reduction, the last one has to cut its reduction in two
+    # (two chunks of 512 elements, wanted ceil(256/128) = 2 slices).
+    prm = P.Params(tile_bytes_min=4096, tile_bytes_max=1 << 20, balance_div=16, tail_div=16)
+    ops = [gemm(1, 1024, 1024) for _ in range(3)]
+    table, order, first, count = P.plan(ops, prm)
+    assert order == [0, 1, 2] and count == [8, 8, 16] and first == [0, 8, 16]
+    t = P.decode(table)
+    assert all(x["S"] == 1 and x["k_len"] == 1024 and x["n_len"] == 128 for x in t[:16])
+    assert [(x["n0"], x["ks_idx"], x["S"], x["k0"], x["k_len"]) for x in t[16:20]] == \
+        [(0, 0, 2, 0, 512), (0, 1, 2, 512, 512), (128, 0, 2, 0, 512), (128, 1, 2, 512, 512)]
+    # the rule follows the execution order, not the submission order: with deadlines 3, 2, 1 ms the operator
+    # submitted first runs last and is the one that is cut
+    rev = [gemm(1, 1024, 1024, deadline=3.0 - i) for i in range(3)]
+    table, order, first, count = P.plan(rev, prm)
+    assert order == [2, 1, 0] and count == [16, 8, 8] and first == [16, 8, 0]
+    # tail_div = 0 switches the rule off
+    table, order, first, count = P.plan(ops, P.Params(tile_bytes_min=4096, tile_bytes_max=1 << 20, balance_div=16, tail_div=0))
+    assert count == [8, 8, 8]
+    # never below the lower clamp
+    prm3 = P.Params(tile_bytes_min=1 << 19, tile_bytes_max=1 << 20, balance_div=1, tail_div=1 << 20)
+    assert P.plan(ops, prm3)[3] == [4, 4, 4]   # T = 512 KiB everywhere: G = 4 * (512 // 256) = 8 groups = 256 rows
+
+
 def test_hand_enumerated_four_row_block_class():
     prm = P.Params(tile_bytes_min=32768, tile_bytes_max=32768)
     # Mg = 49 (7x7 image) => four row blocks (cls 6), chunk = 128 elements.

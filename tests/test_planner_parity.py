@@ -94,13 +94,22 @@ def test_plan_bytes_match_reference_ragged_and_params(prm):
 
 
 def test_permuting_operators_permutes_the_plan_consistently():
+    import dataclasses
     specs = workloads.config(4, seed=3)
     perm = list(range(len(specs)))[::-1]
-    with host_plan(specs) as a, host_plan([specs[i] for i in perm]) as b:
+    strip = lambda t, idx: sorted((idx(x["problem"]), x["cls"], x["m0"], x["n0"], x["m_len"], x["n_len"],
+                                   x["k0"], x["k_len"]) for x in t)
+    # An operator's tiles depend on its place in the execution order only through the tail rule.
+    # Without that rule any permutation of the submission order permutes the plan ...
+    with host_plan(specs, tail_div=0) as a, host_plan([specs[i] for i in perm], tail_div=0) as b:
         ta, tb = P.decode(sk.sk_plan_get_tiles(a)), P.decode(sk.sk_plan_get_tiles(b))
-        strip = lambda t, idx: sorted((idx(x["problem"]), x["cls"], x["m0"], x["n0"], x["m_len"], x["n_len"],
-                                       x["k0"], x["k_len"]) for x in t)
         assert strip(ta, lambda i: i) == strip(tb, lambda i: perm[i])
+    # ... and with it, so does one that leaves the execution order alone (all deadlines distinct).
+    dl = [dataclasses.replace(s, deadline_ms=1.0 + 0.37 * ((7 * i) % len(specs))) for i, s in enumerate(specs)]
+    with host_plan(dl) as a, host_plan([dl[i] for i in perm]) as b:
+        ta, tb = P.decode(sk.sk_plan_get_tiles(a)), P.decode(sk.sk_plan_get_tiles(b))
+        assert strip(ta, lambda i: i) == strip(tb, lambda i: perm[i])
+        assert [perm[i] for i in sk.sk_plan_get_order(b)] == sk.sk_plan_get_order(a)
 
 
 def test_empty_plan():
