@@ -404,7 +404,9 @@ __device__ __forceinline__ void run_skinny(const DevProblem &P, const sk_tile &T
   constexpr int BPC = 1 << BPC_LOG2;                // blocks per chunk: 8, 4, 2
   constexpr int PPR = ROWB / 16;                    // pieces per row and chunk
   constexpr int BUF = ROWS * LROW;                  // bytes per LDS buffer
-  constexpr int NB = RM == 4 ? 2 : 3;               // ring slots (weight blocks per wave)
+  constexpr int NB = 2;                             // ring slots: one block in flight while one is multiplied.
+  // (With every workgroup streaming, the memory system is saturated by far fewer bytes in flight
+  // than the launch holds even at this depth; deeper rings only lengthen every load's wait.)
   static_assert(ROWB == BPC * 128, "chunk geometry");
   static_assert(2 * BUF <= LDS_TILE_BYTES, "activation chunks do not fit");
 
