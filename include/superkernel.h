@@ -159,7 +159,12 @@ sk_status sk_launch(sk_plan *plan, void *hip_stream);
 /*
  * The time-multiplexing baseline (Section 4.1): the same device code, one
  * launch per operator, in submission (index) order, all on `hip_stream`.
- * Produces bit-identical outputs to sk_launch.
+ * Every operator is tiled as if it had been planned alone (the plan rule applied
+ * to that operator by itself, what a caller who launches operators one by one
+ * would get), not with the tiles of the coalesced table.  Reductions may
+ * therefore be sliced differently: outputs agree with sk_launch up to the order
+ * of summation.  The first call on a plan builds and uploads these tables
+ * (SK_ERR_ALLOC / SK_ERR_HIP as for sk_plan_create); later calls only launch.
  */
 sk_status sk_launch_sequential(sk_plan *plan, void *hip_stream);
 

@@ -286,6 +286,44 @@ sk_status plan_host(const sk_problem *problems, int32_t n, const sk_plan_params 
   return SK_OK;
 }
 
+sk_status plan_host_each_alone(const HostPlan &whole, HostPlan &out, std::string &err) {
+  const int32_t n = (int32_t)whole.problems.size();
+  out = HostPlan{};
+  out.params = whole.params;
+  out.problems = whole.problems;
+  out.dev = whole.dev;
+  out.order.resize(n);
+  std::iota(out.order.begin(), out.order.end(), 0);
+  out.first.assign(n, 0);
+  out.count.assign(n, 0);
+  out.target_tile_bytes = 0;
+  sk_plan_params prm = whole.params;
+  prm.host_only = 1;
+  uint32_t rect_base = 0;
+  for (int32_t i = 0; i < n; ++i) {
+    HostPlan one;
+    const sk_status st = plan_host(&whole.problems[i], 1, &prm, one, err);
+    if (st != SK_OK) return st;
+    out.first[i] = (int64_t)out.tiles.size();
+    out.count[i] = (int64_t)one.tiles.size();
+    for (sk_tile t : one.tiles) {
+      t.problem = (uint32_t)i;
+      t.out_tile_id += rect_base;
+      out.tiles.push_back(t);
+    }
+    for (uint32_t w : one.ws_off) out.ws_off.push_back(w + (uint32_t)out.ws_f32x4);
+    rect_base += (uint32_t)one.ws_off.size();
+    out.ws_f32x4 += one.ws_f32x4;
+    out.dev[i].tile_first = (int32_t)out.first[i];
+    out.dev[i].tile_count = (int32_t)out.count[i];
+    if (out.tiles.size() > (size_t)1 << 30 || out.ws_f32x4 > ((int64_t)1 << 31)) {
+      err = "tile table or split-K workspace too large";
+      return SK_ERR_UNSUPPORTED;
+    }
+  }
+  return SK_OK;
+}
+
 }  // namespace sk
 
 extern "C" void sk_plan_params_default(sk_plan_params *p) {

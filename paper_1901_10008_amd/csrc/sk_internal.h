@@ -67,6 +67,10 @@ struct HostPlan {
 sk_status plan_host(const sk_problem *problems, int32_t n, const sk_plan_params *params,
                     HostPlan &out, std::string &err);
 
+// The tile tables of the one-launch-per-operator baseline: every operator of `whole` planned
+// by plan_host as if it were submitted alone, concatenated in submission order.
+sk_status plan_host_each_alone(const HostPlan &whole, HostPlan &out, std::string &err);
+
 inline int elem_size(int32_t dtype) { return dtype == SK_F32 ? 4 : 2; }
 
 }  // namespace sk

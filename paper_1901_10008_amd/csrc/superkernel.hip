@@ -29,6 +29,20 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 }  // namespace
 
+// The device side of one tile table: one allocation holding
+//   work records (tile + its operator's descriptor) | queue counters | tiles left per operator |
+//   completion stamps | split-K offsets | split-K arrival counters | split-K workspace
+struct DeviceTables {
+  void *blob = nullptr;
+  sk::TileWork *work = nullptr;
+  uint32_t *counters = nullptr;
+  uint32_t *remaining = nullptr;
+  uint64_t *stamps = nullptr;
+  uint32_t *ws_off = nullptr;   // per output rectangle
+  uint32_t *arrive = nullptr;   // per output rectangle
+  sk::f32x4 *ws = nullptr;      // split-K partial sums (not initialised: written before it is read)
+};
+
 struct sk_plan {
   sk::HostPlan host;
   bool resident = false;
@@ -37,17 +51,68 @@ struct sk_plan {
   int64_t grid_cap = 0;  // most workgroups any launch of this plan may use
   int only_dtype = -1;   // the element type all operators share, or -1 if they differ
   double ticks_per_ms = 0.0;
-  // one device allocation: work records (tile + its operator's descriptor) | counters |
-  // remaining | stamps | split-K offsets | split-K arrival counters | split-K workspace
-  void *blob = nullptr;
-  sk::TileWork *d_work = nullptr;
-  uint32_t *d_counters = nullptr;
-  uint32_t *d_remaining = nullptr;
-  uint64_t *d_stamps = nullptr;
-  uint32_t *d_ws_off = nullptr;   // per output rectangle
-  uint32_t *d_arrive = nullptr;   // per output rectangle
-  sk::f32x4 *d_ws = nullptr;      // split-K partial sums (not initialised: written before it is read)
+  DeviceTables dev;
+  // the one-launch-per-operator baseline: every operator tiled as if it were alone;
+  // planned and uploaded by the first sk_launch_sequential
+  bool seq_ready = false;
+  sk::HostPlan seq_host;
+  DeviceTables seq_dev;
 };
+
+namespace {
+
+// Uploads the tables of `hp` to the current device.
+sk_status upload_tables(const sk::HostPlan &hp, DeviceTables &dt) {
+  const size_t nt = hp.tiles.size(), np = hp.dev.size(), nrect = hp.ws_off.size();
+  const size_t off_work = 0;
+  const size_t off_cnt = align_up(off_work + nt * sizeof(sk::TileWork), 256);
+  const size_t off_rem = align_up(off_cnt + 2 * sizeof(uint32_t), 256);
+  const size_t off_stamps = align_up(off_rem + np * sizeof(uint32_t), 256);
+  const size_t off_wsoff = align_up(off_stamps + (np + 1) * sizeof(uint64_t), 256);
+  const size_t off_arrive = align_up(off_wsoff + nrect * sizeof(uint32_t), 256);
+  const size_t upload = align_up(off_arrive + nrect * sizeof(uint32_t), 256);  // everything before the workspace
+  const size_t total = upload + (size_t)hp.ws_f32x4 * 16;
+  std::string stage;
+  try {
+    stage.assign(upload, '\0');
+  } catch (const std::bad_alloc &) {
+    return set_error(SK_ERR_ALLOC, "host staging allocation failed");
+  }
+  if (nrect) std::memcpy(&stage[off_wsoff], hp.ws_off.data(), nrect * sizeof(uint32_t));
+  for (size_t i = 0; i < nt; ++i) {
+    sk::TileWork w;
+    std::memset(&w, 0, sizeof(w));
+    w.tile = hp.tiles[i];
+    w.prob = hp.dev[w.tile.problem];
+    std::memcpy(&stage[off_work + i * sizeof(w)], &w, sizeof(w));
+  }
+  for (size_t i = 0; i < np; ++i) {
+    const uint32_t c = (uint32_t)hp.count[i];
+    std::memcpy(&stage[off_rem + i * sizeof(uint32_t)], &c, sizeof(c));
+  }
+  hipError_t e = hipMalloc(&dt.blob, total);
+  if (e != hipSuccess) {
+    dt.blob = nullptr;
+    return set_error(SK_ERR_ALLOC, std::string("hipMalloc: ") + hipGetErrorString(e));
+  }
+  e = hipMemcpy(dt.blob, stage.data(), upload, hipMemcpyHostToDevice);
+  if (e != hipSuccess) {
+    (void)hipFree(dt.blob);
+    dt.blob = nullptr;
+    return hip_error("hipMemcpy", e);
+  }
+  char *b = (char *)dt.blob;
+  dt.work = (sk::TileWork *)(b + off_work);
+  dt.counters = (uint32_t *)(b + off_cnt);
+  dt.remaining = (uint32_t *)(b + off_rem);
+  dt.stamps = (uint64_t *)(b + off_stamps);
+  dt.ws_off = (uint32_t *)(b + off_wsoff);
+  dt.arrive = (uint32_t *)(b + off_arrive);
+  dt.ws = (sk::f32x4 *)(b + upload);
+  return SK_OK;
+}
+
+}  // namespace
 
 extern "C" {
 
@@ -91,55 +156,11 @@ sk_status sk_plan_create(const sk_problem *problems, int32_t n, const sk_plan_pa
     const int64_t ntiles = (int64_t)plan->host.tiles.size();
     plan->grid_cap = limit;
     plan->grid = (int)(ntiles < limit ? ntiles : limit);
-
-    const size_t nt = plan->host.tiles.size(), np = plan->host.dev.size();
-    const size_t off_work = 0;
-    const size_t off_cnt = align_up(off_work + nt * sizeof(sk::TileWork), 256);
-    const size_t off_rem = align_up(off_cnt + 2 * sizeof(uint32_t), 256);
-    const size_t off_stamps = align_up(off_rem + np * sizeof(uint32_t), 256);
-    const size_t nrect = plan->host.ws_off.size();
-    const size_t off_wsoff = align_up(off_stamps + (np + 1) * sizeof(uint64_t), 256);
-    const size_t off_arrive = align_up(off_wsoff + nrect * sizeof(uint32_t), 256);
-    const size_t upload = align_up(off_arrive + nrect * sizeof(uint32_t), 256);  // everything before the workspace
-    const size_t total = upload + (size_t)plan->host.ws_f32x4 * 16;
-    std::string stage;
-    try {
-      stage.assign(upload, '\0');
-    } catch (const std::bad_alloc &) {
+    st = upload_tables(plan->host, plan->dev);
+    if (st != SK_OK) {
       delete plan;
-      return set_error(SK_ERR_ALLOC, "host staging allocation failed");
+      return st;
     }
-    if (nrect) std::memcpy(&stage[off_wsoff], plan->host.ws_off.data(), nrect * sizeof(uint32_t));
-    for (size_t i = 0; i < nt; ++i) {
-      sk::TileWork w;
-      std::memset(&w, 0, sizeof(w));
-      w.tile = plan->host.tiles[i];
-      w.prob = plan->host.dev[w.tile.problem];
-      std::memcpy(&stage[off_work + i * sizeof(w)], &w, sizeof(w));
-    }
-    for (size_t i = 0; i < np; ++i) {
-      const uint32_t c = (uint32_t)plan->host.count[i];
-      std::memcpy(&stage[off_rem + i * sizeof(uint32_t)], &c, sizeof(c));
-    }
-    e = hipMalloc(&plan->blob, total);
-    if (e != hipSuccess) {
-      delete plan;
-      return set_error(SK_ERR_ALLOC, std::string("hipMalloc: ") + hipGetErrorString(e));
-    }
-    e = hipMemcpy(plan->blob, stage.data(), upload, hipMemcpyHostToDevice);
-    if (e != hipSuccess) {
-      (void)hipFree(plan->blob);
-      delete plan;
-      return hip_error("hipMemcpy", e);
-    }
-    char *b = (char *)plan->blob;
-    plan->d_work = (sk::TileWork *)(b + off_work);
-    plan->d_counters = (uint32_t *)(b + off_cnt);
-    plan->d_remaining = (uint32_t *)(b + off_rem);
-    plan->d_stamps = (uint64_t *)(b + off_stamps);
-    plan->d_ws_off = (uint32_t *)(b + off_wsoff);
-    plan->d_arrive = (uint32_t *)(b + off_arrive);
-    plan->d_ws = (sk::f32x4 *)(b + upload);
     plan->resident = true;
   }
   *out = plan;
@@ -149,42 +170,44 @@ sk_status sk_plan_create(const sk_problem *problems, int32_t n, const sk_plan_pa
 sk_status sk_plan_destroy(sk_plan *plan) {
   if (!plan) return SK_OK;
   sk_status st = SK_OK;
-  if (plan->blob) {
-    hipError_t e = hipFree(plan->blob);
-    if (e != hipSuccess) st = hip_error("hipFree", e);
+  for (DeviceTables *dt : {&plan->dev, &plan->seq_dev}) {
+    if (dt->blob) {
+      hipError_t e = hipFree(dt->blob);
+      if (e != hipSuccess) st = hip_error("hipFree", e);
+    }
   }
   delete plan;
   return st;
 }
 
-static sk_status launch_range(sk_plan *plan, hipStream_t stream, uint32_t begin, uint32_t end, int grid, bool dynamic,
-                              bool write_start) {
+static sk_status launch_range(sk_plan *plan, const DeviceTables &dt, hipStream_t stream, uint32_t begin, uint32_t end,
+                              int grid, bool dynamic, bool write_start) {
   if (end <= begin || grid <= 0) return SK_OK;
   sk::KernelArgs a;
-  a.counters = plan->d_counters;
-  a.remaining = plan->host.params.stamps ? plan->d_remaining : nullptr;
-  a.stamps = plan->host.params.stamps ? plan->d_stamps : nullptr;
+  a.counters = dt.counters;
+  a.remaining = plan->host.params.stamps ? dt.remaining : nullptr;
+  a.stamps = plan->host.params.stamps ? plan->dev.stamps : nullptr;  // one set of stamps, whichever table ran last
   a.n_problems = (uint32_t)plan->host.dev.size();
   a.tile_begin = begin;
   a.tile_end = end;
   a.dynamic = dynamic ? 1u : 0u;
   a.write_start = write_start ? 1u : 0u;
-  a.ws = plan->d_ws;
-  a.ws_off = plan->d_ws_off;
-  a.arrive = plan->d_arrive;
+  a.ws = dt.ws;
+  a.ws_off = dt.ws_off;
+  a.arrive = dt.arrive;
   const dim3 g((unsigned)grid), b(sk::WG_THREADS);
   switch (plan->only_dtype) {
     case SK_F32:
-      hipLaunchKernelGGL(sk::sk_superkernel<SK_F32>, g, b, 0, stream, plan->d_work, a);
+      hipLaunchKernelGGL(sk::sk_superkernel<SK_F32>, g, b, 0, stream, dt.work, a);
       break;
     case SK_BF16:
-      hipLaunchKernelGGL(sk::sk_superkernel<SK_BF16>, g, b, 0, stream, plan->d_work, a);
+      hipLaunchKernelGGL(sk::sk_superkernel<SK_BF16>, g, b, 0, stream, dt.work, a);
       break;
     case SK_F16:
-      hipLaunchKernelGGL(sk::sk_superkernel<SK_F16>, g, b, 0, stream, plan->d_work, a);
+      hipLaunchKernelGGL(sk::sk_superkernel<SK_F16>, g, b, 0, stream, dt.work, a);
       break;
     default:
-      hipLaunchKernelGGL(sk::sk_superkernel<-1>, g, b, 0, stream, plan->d_work, a);
+      hipLaunchKernelGGL(sk::sk_superkernel<-1>, g, b, 0, stream, dt.work, a);
       break;
   }
   hipError_t e = hipGetLastError();
@@ -205,17 +228,31 @@ static sk_status check_launchable(sk_plan *plan) {
 sk_status sk_launch(sk_plan *plan, void *hip_stream) {
   sk_status st = check_launchable(plan);
   if (st != SK_OK) return st;
-  return launch_range(plan, (hipStream_t)hip_stream, 0u, (uint32_t)plan->host.tiles.size(), plan->grid, true, true);
+  return launch_range(plan, plan->dev, (hipStream_t)hip_stream, 0u, (uint32_t)plan->host.tiles.size(), plan->grid, true,
+                      true);
 }
 
 sk_status sk_launch_sequential(sk_plan *plan, void *hip_stream) {
   sk_status st = check_launchable(plan);
   if (st != SK_OK) return st;
-  const size_t n = plan->host.dev.size();
+  if (!plan->seq_ready) {
+    std::string err;
+    try {
+      st = sk::plan_host_each_alone(plan->host, plan->seq_host, err);
+    } catch (const std::bad_alloc &) {
+      return set_error(SK_ERR_ALLOC, "host allocation failed while planning");
+    }
+    if (st != SK_OK) return set_error(st, err);
+    st = upload_tables(plan->seq_host, plan->seq_dev);
+    if (st != SK_OK) return st;
+    plan->seq_ready = true;
+  }
+  const size_t n = plan->seq_host.dev.size();
   for (size_t i = 0; i < n; ++i) {
-    const int64_t first = plan->host.first[i], count = plan->host.count[i];
+    const int64_t first = plan->seq_host.first[i], count = plan->seq_host.count[i];
     const int grid = (int)(count < plan->grid_cap ? count : plan->grid_cap);
-    st = launch_range(plan, (hipStream_t)hip_stream, (uint32_t)first, (uint32_t)(first + count), grid, false, i == 0);
+    st = launch_range(plan, plan->seq_dev, (hipStream_t)hip_stream, (uint32_t)first, (uint32_t)(first + count), grid,
+                      false, i == 0);
     if (st != SK_OK) return st;
   }
   return SK_OK;
@@ -258,11 +295,11 @@ sk_status sk_plan_get_stamps(sk_plan *plan, uint64_t *done_ticks, uint64_t *star
     return set_error(SK_ERR_STATE, "plan was not created with stamps enabled on a device");
   const size_t n = plan->host.dev.size();
   if (done_ticks && n) {
-    hipError_t e = hipMemcpy(done_ticks, plan->d_stamps, n * sizeof(uint64_t), hipMemcpyDeviceToHost);
+    hipError_t e = hipMemcpy(done_ticks, plan->dev.stamps, n * sizeof(uint64_t), hipMemcpyDeviceToHost);
     if (e != hipSuccess) return hip_error("hipMemcpy", e);
   }
   if (start_tick) {
-    hipError_t e = hipMemcpy(start_tick, plan->d_stamps + n, sizeof(uint64_t), hipMemcpyDeviceToHost);
+    hipError_t e = hipMemcpy(start_tick, plan->dev.stamps + n, sizeof(uint64_t), hipMemcpyDeviceToHost);
     if (e != hipSuccess) return hip_error("hipMemcpy", e);
   }
   if (ticks_per_ms) *ticks_per_ms = plan->ticks_per_ms;

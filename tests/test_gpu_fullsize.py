@@ -34,8 +34,13 @@ def test_config5_full_size_sampled():
         b.reset_outputs()
         sk.sk_launch_sequential(plan, H.stream_handle())
         torch.cuda.synchronize()
+        # the baseline tiles every operator as if it were alone: same sums in another order
         for i, (x, y) in enumerate(zip(outs, b.c_bufs)):
-            assert torch.equal(x, y), f"operator {i}: sequential differs from coalesced"
+            xf, yf = x.view(torch.bfloat16).float(), y.view(torch.bfloat16).float()
+            ok = torch.isfinite(xf)  # padding between rows stays NaN in both
+            assert torch.equal(ok, torch.isfinite(yf)), f"operator {i}: sequential wrote other elements"
+            d = (xf[ok] - yf[ok]).abs().max().item()
+            assert d <= 2e-2 * xf[ok].abs().max().item(), f"operator {i}: sequential differs from coalesced by {d}"
     worst = 0.0
     for i, s in enumerate(specs):
         rows, cols, ldc, off = b.c_meta[i]

@@ -23,7 +23,8 @@ def _sync():
 
 
 def run_all_modes(specs, seed=0, label="", **batch_kw):
-    """Superkernel vs oracle; sequential and index-order plans bit-identical to it."""
+    """Superkernel vs oracle; the one-launch-per-operator baseline (its own tiling, so its own
+    summation order) vs oracle; a relaunch and the index-order plan bit-identical to the first launch."""
     b = H.Batch(specs, seed=seed, **batch_kw)
     with b.plan() as plan:
         # plan parity with the reference planner on the real addresses
@@ -43,8 +44,14 @@ def run_all_modes(specs, seed=0, label="", **batch_kw):
         b.reset_outputs()
         sk.sk_launch_sequential(plan, H.stream_handle())
         _sync()
-        for i, (x, y) in enumerate(zip(coalesced, b.all_output_bits())):
-            assert np.array_equal(x, y), f"{label}: sequential differs from coalesced on operator {i}"
+        H.check_against_oracle(b, label + " sequential")
+        # second round of the baseline (its reduction counters re-arm themselves too)
+        seq_bits = b.all_output_bits()
+        b.reset_outputs()
+        sk.sk_launch_sequential(plan, H.stream_handle())
+        _sync()
+        for i, (x, y) in enumerate(zip(seq_bits, b.all_output_bits())):
+            assert np.array_equal(x, y), f"{label}: second sequential round differs on operator {i}"
     with b.plan(edf=0) as plan:
         b.reset_outputs()
         sk.sk_launch(plan, H.stream_handle())
