@@ -104,7 +104,7 @@ typedef struct {
   int32_t balance_div;    /* default 2048                                                    */
   int32_t max_groups;     /* cap on 32-row weight groups per skinny tile, default 256        */
   int32_t grid_limit;     /* upper bound on persistent workgroups per launch;                */
-                          /* 0 = 3 per compute unit of the current device                    */
+                          /* 0 = 2 per compute unit of the current device                    */
   int32_t tail_div;       /* tiles shrink towards the end of the table: an operator's target */
                           /* is also capped by (weight bytes of it and of all operators      */
                           /* after it in execution order) / tail_div, so that the launch     */
@@ -118,7 +118,7 @@ typedef struct {
  */
 typedef struct {
   uint32_t problem;     /* index of the operator in the sk_problem array                    */
-  uint16_t cls;         /* tile class: 0, 3, 6 skinny (1, 2, 4 blocks of 16 rows), 9: 64x128 LDS tile */
+  uint16_t cls;         /* tile class: 0, 3, 6 skinny (1, 2, 4 blocks of 16 rows), 9: 128x128 LDS tile */
   uint8_t ks_idx;       /* which reduction slice of the output rectangle this record is     */
   uint8_t S;            /* number of reduction slices of the rectangle (1 = not split)      */
   uint32_t m0, n0;      /* origin of the output rectangle in the operator's [Mg,Ng] GEMM view */

@@ -40,8 +40,8 @@ assert RECORD.size == 32
 #   0, 3, 6  "skinny": all rows of a small-M operator (rm = 1, 2 or 4 blocks of 16 rows)
 #         against a block of 32*G weight rows; long reductions are cut into S slices
 #         that different workgroups take.   id = 3*log2(rm)
-#   9     64 x 128 output tile staged through LDS
-CLS_TILE_64x128 = 9
+#   9     128 x 128 output tile staged through LDS
+CLS_TILE_128x128 = 9
 
 
 @dataclass
@@ -107,7 +107,17 @@ def tiling(p, T: int, prm: Params):
             S = -(-nchunks // per)
             slice_len = per * chunk
         return 3 * rm_code, mg, 32 * G, S, slice_len
-    return CLS_TILE_64x128, 64, 128, 1, kg
+    # LDS tile: cut the reduction when the operand bytes of one tile are far beyond the target
+    S, slice_len = 1, kg
+    tb = (128 + 128) * kg * es
+    if tb > 2 * T:
+        chunk = 256
+        nchunks = -(-kg // chunk)
+        want = min(nchunks, -(-tb // T), 255)
+        per = -(-nchunks // want)
+        S = -(-nchunks // per)
+        slice_len = per * chunk
+    return CLS_TILE_128x128, 128, 128, S, slice_len
 
 
 def plan(problems: Sequence, prm: Params | None = None):

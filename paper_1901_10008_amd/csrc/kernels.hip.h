@@ -14,7 +14,7 @@
 //     Activations are staged through LDS.  The four waves of a workgroup take
 //     different 32-row weight groups; long reductions are split over several
 //     workgroups whose partial sums the last one to finish adds in fixed order.
-//   * LDS tiles (64x128): classic staged GEMM, global -> registers -> LDS ->
+//   * LDS tiles (128x128): classic staged GEMM, global -> registers -> LDS ->
 //     32x32 MFMA; the activation operand may be gathered on the fly from an
 //     NHWC image (implicit GEMM for convolutions).
 #pragma once
@@ -74,7 +74,7 @@ static_assert(WORK_DWORDS <= 64, "one dword of the record per lane");
 
 constexpr int WG_THREADS = 256;
 constexpr int LDS_ROW = 144;                  // 128 bytes of K + 16 bytes of padding (bank spread)
-constexpr int LDS_TILE_BYTES = 256 * LDS_ROW;  // 36 KB per workgroup: four workgroups share a CU's 160 KB
+constexpr int LDS_TILE_BYTES = 512 * LDS_ROW;  // 72 KB per workgroup: two workgroups share a CU's 160 KB
 
 struct KernelArgs {
   uint32_t *counters;   // [0] tiles handed out beyond the first grid-full, [1] finished workgroups
@@ -620,8 +620,18 @@ __device__ __forceinline__ void run_skinny(const DevProblem &P, const sk_tile &T
 // ---------------------------------------------------------------------------
 // LDS-staged tiles: BM x BN outputs per workgroup, 128 bytes of K per stage
 // ---------------------------------------------------------------------------
+// Operand pieces travel global memory -> registers -> LDS -> MFMA.  A ring of NS register
+// stages keeps NS-1 stages of loads in flight.  LDS holds two stages: while the MFMAs of
+// stage s read one buffer, the pieces of stage s+1 are written to the other, and one barrier
+// per stage separates "everyone has written s+1 and finished reading s" from the next round.
+//
+// A stage costs a wave its whole instruction stream (address arithmetic, LDS traffic, MFMAs,
+// barrier) back to back, so that stream is kept short: operand row pointers are formed once
+// per tile, and the position in the implicit patch matrix (filter tap r,s and channel c of
+// this thread's piece) advances by additions only -- no multiply or divide per stage.
 template <int DT, int BM, int BN, int WAVES_M, int WAVES_N>
-__device__ __forceinline__ void run_tile(const DevProblem &P, const sk_tile &T, unsigned char *lds, Prefetch &pf) {
+__device__ __forceinline__ void run_tile(const DevProblem &P, const sk_tile &T, const SplitK &sp, unsigned char *lds,
+                                         uint32_t *s_flag, Prefetch &pf) {
   constexpr int ES = Elem<DT>::ES;
   constexpr int CE = 16 / ES;
   constexpr int KB = 8 * CE;                  // reduction elements per stage
@@ -629,8 +639,10 @@ __device__ __forceinline__ void run_tile(const DevProblem &P, const sk_tile &T, 
   constexpr int FN = BN / (32 * WAVES_N);     // ... along n
   constexpr int A_ITERS = BM / 32;            // 16-byte pieces per thread per stage, activations
   constexpr int B_ITERS = BN / 32;            // ... weights
+  constexpr int STAGE = (BM + BN) * LDS_ROW;  // bytes of one stage in LDS
+  constexpr int NS = 3;
   static_assert(WAVES_M * WAVES_N == 4, "four waves per workgroup");
-  static_assert((BM + BN) * LDS_ROW <= LDS_TILE_BYTES, "tile does not fit the LDS buffer");
+  static_assert(2 * STAGE <= LDS_TILE_BYTES, "two stages do not fit the LDS buffer");
 
   const int tid = pf.tid;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -638,28 +650,31 @@ __device__ __forceinline__ void run_tile(const DevProblem &P, const sk_tile &T, 
   const int wm = wave % WAVES_M, wn = wave / WAVES_M;
   const int l32 = lane & 31, half = lane >> 5;
 
-  unsigned char *ldsA = lds;
-  unsigned char *ldsB = lds + BM * LDS_ROW;
-
   const int m0 = (int)T.m0, n0 = (int)T.n0;
   const int m_end = m0 + (int)T.m_len, n_end = n0 + (int)T.n_len;
+  const int k_begin = (int)T.k0, k_stop = (int)T.k0 + (int)T.k_len;
 
-  // staging map: thread -> piece c of rows (tid/8) + 32*i
+  // staging map: thread -> piece c8 of rows (tid/8) + 32*i
   const int c8 = tid & 7;
   const int srow = tid >> 3;
-  RowA rowa[A_ITERS];
+  const bool gvec = P.gather != 0;
+  const char SK_GLOBAL *pa[A_ITERS];  // row start (for a convolution: the pixel under filter tap (0,0), may lie outside the image)
+  int hb[A_ITERS], wb[A_ITERS];
 #pragma unroll
   for (int i = 0; i < A_ITERS; ++i) {
     int m = m0 + srow + 32 * i;
     if (m >= m_end) m = m_end - 1;  // rows past the edge repeat the last row; never stored
-    rowa[i] = row_of(P, m);
+    const RowA r = row_of(P, m);
+    pa[i] = as_global<char>(P.A) + r.base * ES;
+    hb[i] = r.hb;
+    wb[i] = r.wb;
   }
-  int64_t wrow[B_ITERS];
+  const char SK_GLOBAL *pb[B_ITERS];
 #pragma unroll
   for (int i = 0; i < B_ITERS; ++i) {
     int n = n0 + srow + 32 * i;
     if (n >= n_end) n = n_end - 1;
-    wrow[i] = (int64_t)n * P.ldb;
+    pb[i] = as_global<char>(P.B) + (int64_t)n * P.ldb * ES;
   }
 
   f32x16 acc[FN][FM];
@@ -670,95 +685,143 @@ __device__ __forceinline__ void run_tile(const DevProblem &P, const sk_tile &T, 
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[fn][fm][i] = 0.f;
 
-  const int k_begin = (int)T.k0, k_stop = (int)T.k0 + (int)T.k_len;
-  // Operand pieces travel global memory -> registers -> LDS.  A ring of NS stages of registers
-  // keeps NS-1 stages of loads in flight while one stage is multiplied: next to workgroups
-  // that stream weights at the memory system's limit a load takes microseconds, far longer
-  // than the MFMAs of a stage.
-  constexpr int NS = 3;
-  u32x4 ra[NS][A_ITERS], rb[NS][B_ITERS];
-  bool ra_ok[NS][A_ITERS];
-
-  // Implicit GEMM: the piece column of this thread walks through the filter taps
-  // (r, s) and channels c as K advances; keep that position incrementally.
-  const bool gvec = P.gather != 0;
+  // position of this thread's piece in the patch row: tap (g_r, g_s), channel g_c;
+  // tap_off = ((g_r*W + g_s)*Cin + g_c) elements from the pixel under tap (0,0)
   int g_r = 0, g_s = 0, g_c = 0;
+  int64_t tap_off = 0;
+  const int64_t next_filter_row = (int64_t)(P.W - P.S) * P.Cin;
   if (gvec) {
     const int k = k_begin + c8 * CE;
     const int tap = k / P.Cin;
     g_c = k - tap * P.Cin;
     g_r = tap / P.S;
     g_s = tap - g_r * P.S;
+    tap_off = ((int64_t)g_r * P.W + g_s) * P.Cin + g_c;
   }
+  u32x4 ra[NS][A_ITERS], rb[NS][B_ITERS];
+  bool ra_ok[NS][A_ITERS];
   // Loads are unconditional (stages past the end of the reduction read clamped addresses and
-  // are never stored), so the number of loads in flight is the same on every path.
-  int k_load = k_begin;  // reduction index of the next stage to load
+  // are never multiplied), so the number of loads in flight is the same on every path.
+  int k_load = k_begin + c8 * CE;  // reduction index of this thread's piece in the next stage to load
   auto gload = [&](u32x4(&xa)[A_ITERS], u32x4(&xb)[B_ITERS], bool(&xok)[A_ITERS]) {
-    const int k = k_load + c8 * CE;
-    k_load += KB;
+    const bool in = k_load < k_stop;
     if (gvec) {
-      const int64_t tap_off = ((int64_t)g_r * P.W + g_s) * P.Cin + g_c;
 #pragma unroll
       for (int i = 0; i < A_ITERS; ++i) {
-        xok[i] = k < k_stop && (unsigned)(rowa[i].hb + g_r) < (unsigned)P.H &&
-                 (unsigned)(rowa[i].wb + g_s) < (unsigned)P.W;
-        xa[i] = load_piece_vec<ES, false>(P.A, xok[i] ? rowa[i].base + tap_off : 0);
+        xok[i] = in && (unsigned)(hb[i] + g_r) < (unsigned)P.H && (unsigned)(wb[i] + g_s) < (unsigned)P.W;
+        const char SK_GLOBAL *q = pa[i] + tap_off * ES;
+        xa[i] = *(const u32x4 SK_GLOBAL *)(xok[i] ? q : as_global<char>(P.A));
       }
       g_c += KB;
+      tap_off += KB;
       while (g_c >= P.Cin) {
         g_c -= P.Cin;
         if (++g_s == P.S) {
           g_s = 0;
           ++g_r;
+          tap_off += next_filter_row;
         }
       }
     } else {
 #pragma unroll
       for (int i = 0; i < A_ITERS; ++i) {
-        xok[i] = k < k_stop;
-        xa[i] = fetch_A<ES>(P, rowa[i], k, xok[i]);
+        xok[i] = in;
+        xa[i] = *(const u32x4 SK_GLOBAL *)(pa[i] + (int64_t)(in ? k_load : 0) * ES);
       }
     }
 #pragma unroll
-    for (int i = 0; i < B_ITERS; ++i) xb[i] = fetch_B<ES, false>(P, wrow[i], k, k < k_stop);
+    for (int i = 0; i < B_ITERS; ++i) xb[i] = *(const u32x4 SK_GLOBAL *)(pb[i] + (int64_t)(in ? k_load : 0) * ES);
+    k_load += KB;
   };
-  auto lstore = [&](const u32x4(&xa)[A_ITERS], const u32x4(&xb)[B_ITERS], const bool(&xok)[A_ITERS]) {
+  auto lstore = [&](int buf, const u32x4(&xa)[A_ITERS], const u32x4(&xb)[B_ITERS], const bool(&xok)[A_ITERS]) {
+    unsigned char *a = lds + buf * STAGE + srow * LDS_ROW + c8 * 16;
+    unsigned char *bb = a + BM * LDS_ROW;
 #pragma unroll
-    for (int i = 0; i < A_ITERS; ++i)
-      *(u32x4 *)(ldsA + (srow + 32 * i) * LDS_ROW + c8 * 16) = keep_if(xok[i], xa[i]);
+    for (int i = 0; i < A_ITERS; ++i) *(u32x4 *)(a + 32 * i * LDS_ROW) = keep_if(xok[i], xa[i]);
 #pragma unroll
-    for (int i = 0; i < B_ITERS; ++i) *(u32x4 *)(ldsB + (srow + 32 * i) * LDS_ROW + c8 * 16) = xb[i];
+    for (int i = 0; i < B_ITERS; ++i) *(u32x4 *)(bb + 32 * i * LDS_ROW) = xb[i];
   };
 
+  const int nstages = (k_stop - k_begin + KB - 1) / KB;
 #pragma unroll
   for (int u = 0; u < NS - 1; ++u) gload(ra[u], rb[u], ra_ok[u]);
-  const int nstages = (k_stop - k_begin + KB - 1) / KB;
+  lstore(0, ra[0], rb[0], ra_ok[0]);
+  __syncthreads();
+  int buf = 0;
   for (int s0 = 0; s0 < nstages; s0 += NS) {
 #pragma unroll
     for (int u = 0; u < NS; ++u) {
       pf.at_step(s0 + u, nstages, CLAIM_LEAD, ISSUE_GAP);
       gload(ra[(u + NS - 1) % NS], rb[(u + NS - 1) % NS], ra_ok[(u + NS - 1) % NS]);
       if (s0 + u < nstages) {
-        lstore(ra[u], rb[u], ra_ok[u]);
-        __syncthreads();
+        // stage s0+u is in LDS buffer `buf`; put stage s0+u+1 (possibly past the end: zeros
+        // times finite weights, never multiplied) into the other one while this one is used
+        const unsigned char *la = lds + buf * STAGE;
+        const unsigned char *lb = la + BM * LDS_ROW;
+        lstore(buf ^ 1, ra[(u + 1) % NS], rb[(u + 1) % NS], ra_ok[(u + 1) % NS]);
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
           const int piece = (2 * kk + half) * 16;
           u32x4 fa[FM], fb[FN];
 #pragma unroll
           for (int fm = 0; fm < FM; ++fm)
-            fa[fm] = *(const u32x4 *)(ldsA + ((wm * FM + fm) * 32 + l32) * LDS_ROW + piece);
+            fa[fm] = *(const u32x4 *)(la + ((wm * FM + fm) * 32 + l32) * LDS_ROW + piece);
 #pragma unroll
           for (int fn = 0; fn < FN; ++fn)
-            fb[fn] = *(const u32x4 *)(ldsB + ((wn * FN + fn) * 32 + l32) * LDS_ROW + piece);
+            fb[fn] = *(const u32x4 *)(lb + ((wn * FN + fn) * 32 + l32) * LDS_ROW + piece);
 #pragma unroll
           for (int fn = 0; fn < FN; ++fn)
 #pragma unroll
             for (int fm = 0; fm < FM; ++fm) mma32<DT>(fb[fn], fa[fm], acc[fn][fm]);
         }
         __syncthreads();
+        buf ^= 1;
       }
     }
+  }
+
+  if (T.S > 1) {
+    // A slice of a split reduction: same hand-over as in the skinny classes.  Partial sums go to
+    // the workspace in register layout with device-scope stores (a slice is FN*FM*4 blocks of
+    // 64 x 16 bytes per wave); the last slice to arrive adds all of them in slice order.
+    constexpr int PER_WAVE = FN * FM * 4;          // 1 KB blocks per wave and slice
+    constexpr int PER_SLICE = 4 * PER_WAVE * 64;   // f32x4 units per slice
+    f32x4 *mine = sp.ws + sp.ws_off[T.out_tile_id] + wave * PER_WAVE * 64;
+#pragma unroll
+    for (int fn = 0; fn < FN; ++fn)
+#pragma unroll
+      for (int fm = 0; fm < FM; ++fm)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const f32x4 v = {acc[fn][fm][4 * j], acc[fn][fm][4 * j + 1], acc[fn][fm][4 * j + 2], acc[fn][fm][4 * j + 3]};
+          store_device_scope(mine + (size_t)T.ks_idx * PER_SLICE + ((fn * FM + fm) * 4 + j) * 64, lane, v);
+        }
+    __builtin_amdgcn_s_waitcnt(0);  // all counters to zero: the stores above have completed
+    __syncthreads();
+    if (tid == 0)
+      *s_flag = __hip_atomic_fetch_add(&sp.arrive[T.out_tile_id], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (*s_flag != (uint32_t)T.S - 1) return;
+#pragma unroll
+    for (int fn = 0; fn < FN; ++fn)
+#pragma unroll
+      for (int fm = 0; fm < FM; ++fm)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[fn][fm][i] = 0.f;
+    for (int s2 = 0; s2 < T.S; ++s2) {
+#pragma unroll
+      for (int fn = 0; fn < FN; ++fn)
+#pragma unroll
+        for (int fm = 0; fm < FM; ++fm)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const f32x4 v = load_device_scope(mine + (size_t)s2 * PER_SLICE + ((fn * FM + fm) * 4 + j) * 64, lane);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[fn][fm][4 * j + e] += v[e];
+          }
+    }
+    if (tid == 0)  // re-arm for the next launch
+      __hip_atomic_store(&sp.arrive[T.out_tile_id], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
 
   // lane holds, per (fn, fm): row m = l32, columns 8*(i/4) + 4*half + (i%4)
@@ -843,14 +906,14 @@ __device__ __forceinline__ void run_class(const DevProblem &P, const sk_tile &T,
   } else if (cls == 6) {
     run_skinny<DT, 4>(P, T, sp, lds, s_flag, pf);
   } else {
-    run_tile<DT, 64, 128, 1, 4>(P, T, lds, pf);
+    run_tile<DT, 128, 128, 2, 2>(P, T, sp, lds, s_flag, pf);
   }
 }
 
 // ONLY_DT >= 0: every operator of the plan has that element type (one third of the
 // code, fewer registers); ONLY_DT < 0: operators of mixed types.
 template <int ONLY_DT>
-__global__ void __launch_bounds__(WG_THREADS, 3) sk_superkernel(const TileWork *__restrict__ work, KernelArgs a) {
+__global__ void __launch_bounds__(WG_THREADS, 2) sk_superkernel(const TileWork *__restrict__ work, KernelArgs a) {
   __shared__ __attribute__((aligned(16))) unsigned char lds[LDS_TILE_BYTES];
   __shared__ __attribute__((aligned(16))) uint32_t s_mail[2][WORK_DWORDS + 4];  // next record + its index, by parity
   __shared__ uint32_t s_flag;

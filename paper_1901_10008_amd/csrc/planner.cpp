@@ -243,9 +243,19 @@ sk_status plan_host(const sk_problem *problems, int32_t n, const sk_plan_params 
       BM = c.Mg;
       BN = 32 * G;
     } else {
-      cls = CLS_TILE_64x128;
-      BM = 64;
+      cls = CLS_TILE_128x128;
+      BM = 128;
       BN = 128;
+      // operand bytes of one tile over the whole reduction; far beyond the target: cut the reduction
+      const int64_t tb = (BM + BN) * c.Kg * es;
+      if (tb > 2 * T) {
+        const int64_t chunk = 256;  // reduction elements: whole stages of every element type
+        const int64_t nchunks = (c.Kg + chunk - 1) / chunk;
+        const int64_t want = std::min<int64_t>(std::min<int64_t>(nchunks, (tb + T - 1) / T), 255);
+        const int64_t per = (nchunks + want - 1) / want;
+        S = (nchunks + per - 1) / per;
+        slice_len = per * chunk;
+      }
     }
     out.first[i] = (int64_t)out.tiles.size();
     for (int64_t m0 = 0; m0 < c.Mg; m0 += BM) {
@@ -267,8 +277,9 @@ sk_status plan_host(const sk_problem *problems, int32_t n, const sk_plan_params 
         }
         if (S > 1) {
           // partial sums of this rectangle: S slices x 4 waves x (2 * rm) accumulators x 64 lanes, 16 bytes each
+          // (LDS tiles: S slices x 256 threads x 16 accumulator quads)
           out.ws_off.push_back((uint32_t)out.ws_f32x4);
-          out.ws_f32x4 += S * 4 * 2 * ((int64_t)1 << (cls / 3)) * 64;
+          out.ws_f32x4 += cls == CLS_TILE_128x128 ? S * 4096 : S * 4 * 2 * ((int64_t)1 << (cls / 3)) * 64;
         } else {
           out.ws_off.push_back(0u);
         }

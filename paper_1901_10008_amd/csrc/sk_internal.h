@@ -18,7 +18,7 @@ enum : int32_t {
 
 enum : uint16_t {
   CLS_SKINNY_FIRST = 0,  // 0..8: 3*log2(rm) + log2(wk), rm = 1, 2, 4 blocks of 16 activation rows
-  CLS_TILE_64x128 = 9,
+  CLS_TILE_128x128 = 9,
 };
 
 // Device-side description of one operator in its canonical GEMM view

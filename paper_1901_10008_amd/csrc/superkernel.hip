@@ -152,7 +152,7 @@ sk_status sk_plan_create(const sk_problem *problems, int32_t n, const sk_plan_pa
       return hip_error("hipDeviceGetAttribute", e);
     }
     plan->ticks_per_ms = (double)clock_khz;
-    const int64_t limit = prm.grid_limit > 0 ? prm.grid_limit : 3 * (int64_t)cus;
+    const int64_t limit = prm.grid_limit > 0 ? prm.grid_limit : 2 * (int64_t)cus;
     const int64_t ntiles = (int64_t)plan->host.tiles.size();
     plan->grid_cap = limit;
     plan->grid = (int)(ntiles < limit ? ntiles : limit);

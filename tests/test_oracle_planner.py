@@ -115,14 +115,31 @@ def test_hand_enumerated_four_row_block_class():
 
 
 def test_hand_enumerated_lds_tiles():
-    # Mg = 196 -> 64x128 tiles, rows outer, columns inner
-    t = P.decode(P.plan([conv(14, 64, 192 + 8, 3)])[0])
+    # Mg = 196 -> 128x128 tiles, rows outer, columns inner (target of 1 MiB: reduction not cut)
+    whole = P.Params(tile_bytes_min=1 << 20, tile_bytes_max=1 << 20)
+    t = P.decode(P.plan([conv(14, 64, 192 + 8, 3)], whole)[0])
     assert [(x["cls"], x["m0"], x["n0"], x["m_len"], x["n_len"], x["k_len"]) for x in t] == \
-        [(9, 0, 0, 64, 128, 576), (9, 0, 128, 64, 72, 576),
-         (9, 64, 0, 64, 128, 576), (9, 64, 128, 64, 72, 576),
-         (9, 128, 0, 64, 128, 576), (9, 128, 128, 64, 72, 576),
-         (9, 192, 0, 4, 128, 576), (9, 192, 128, 4, 72, 576)]
-    assert [x["out_tile_id"] for x in t] == list(range(8))
+        [(9, 0, 0, 128, 128, 576), (9, 0, 128, 128, 72, 576),
+         (9, 128, 0, 68, 128, 576), (9, 128, 128, 68, 72, 576)]
+    assert [x["out_tile_id"] for x in t] == list(range(4))
+    assert all(x["S"] == 1 and x["k0"] == 0 for x in t)
+    # the operands of one tile are 256 rows x 576 x 2 B = 288 KiB.  Target 128 KiB: 288 > 2*128, so the
+    # reduction is cut in whole 256-element chunks: 3 chunks, wanted ceil(288/128) = 3 slices of one chunk
+    prm = P.Params(tile_bytes_min=128 << 10, tile_bytes_max=128 << 10)
+    t = P.decode(P.plan([conv(14, 64, 192 + 8, 3)], prm)[0])
+    assert len(t) == 12
+    assert [(x["m0"], x["n0"], x["ks_idx"], x["S"], x["k0"], x["k_len"], x["out_tile_id"]) for x in t[:6]] == \
+        [(0, 0, 0, 3, 0, 256, 0), (0, 0, 1, 3, 256, 256, 0), (0, 0, 2, 3, 512, 64, 0),
+         (0, 128, 0, 3, 0, 256, 1), (0, 128, 1, 3, 256, 256, 1), (0, 128, 2, 3, 512, 64, 1)]
+    # target 160 KiB: 288 <= 2*160, not cut
+    prm = P.Params(tile_bytes_min=160 << 10, tile_bytes_max=160 << 10)
+    assert all(x["S"] == 1 for x in P.decode(P.plan([conv(14, 64, 192 + 8, 3)], prm)[0]))
+    # Kg = 4608 (3x3x512), target 1 MiB: operands 2304 KiB > 2 MiB; 18 chunks, wanted ceil(2304/1024) = 3,
+    # six chunks per slice
+    t = P.decode(P.plan([conv(14, 512, 128, 3)], whole)[0])
+    assert [(x["m0"], x["ks_idx"], x["S"], x["k0"], x["k_len"]) for x in t] == \
+        [(0, 0, 3, 0, 1536), (0, 1, 3, 1536, 1536), (0, 2, 3, 3072, 1536),
+         (128, 0, 3, 0, 1536), (128, 1, 3, 1536, 1536), (128, 2, 3, 3072, 1536)]
 
 
 def test_edf_order_is_stable_sort_by_deadline_then_index():
