@@ -108,9 +108,21 @@ struct Elem<SK_F16> {
 };
 
 __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
-  uint32_t u = __builtin_bit_cast(uint32_t, f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;  // NaN stays NaN
-  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;                    // nearest, ties to even
+  __bf16 h = (__bf16)f;  // v_cvt_pk_bf16_f32: nearest, ties to even; NaN stays NaN
+  return (uint32_t)__builtin_bit_cast(uint16_t, h);
+}
+// Two outputs packed into one dword (lower column in the low half).
+template <int DT>
+__device__ __forceinline__ uint32_t cvt_pack(float lo, float hi) {
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
+  const f32x2 v = {lo, hi};
+  if constexpr (DT == SK_BF16) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+  } else {
+    typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
+  }
 }
 __device__ __forceinline__ uint32_t f32_to_f16_bits(float f) {
   _Float16 h = (_Float16)f;  // v_cvt_f16_f32: nearest, ties to even
@@ -134,8 +146,8 @@ __device__ __forceinline__ void store4(void *C, int64_t row_off, int n, int n_en
       *(f32x4 SK_GLOBAL *)p = v;
     } else {
       u32x2 o;
-      o.x = cvt_bits<DT>(v.x) | (cvt_bits<DT>(v.y) << 16);
-      o.y = cvt_bits<DT>(v.z) | (cvt_bits<DT>(v.w) << 16);
+      o.x = cvt_pack<DT>(v.x, v.y);
+      o.y = cvt_pack<DT>(v.z, v.w);
       *(u32x2 SK_GLOBAL *)p = o;
     }
   } else {
@@ -170,8 +182,8 @@ __device__ __forceinline__ u32x4 load_piece_vec(const void *base, int64_t off) {
 // and their values are not touched before they are consumed (a select right behind a
 // load makes the wave wait for it at once).  So: addresses are clamped to a readable
 // place, activation pieces that must read as zero (beyond K, in the padding, rows past
-// Mg) are zeroed when they are written to LDS, and weight pieces are never zeroed at
-// all: a weight piece beyond K only ever meets an activation piece that is zero.
+// Mg) are zeroed when they are written to LDS, and weight pieces beyond K are read from
+// a piece of zeros in device memory instead of from their row.
 __device__ __forceinline__ u32x4 keep_if(bool ok, const u32x4 &v) {
   u32x4 r;
 #pragma unroll
@@ -179,11 +191,18 @@ __device__ __forceinline__ u32x4 keep_if(bool ok, const u32x4 &v) {
   return r;
 }
 
-// Weight piece: row n of Bs[Ng,Kg], elements k .. k+CE-1; where !ok the start of the
-// same row is read instead (finite data that will be multiplied by zeros).
+// Weight piece: row n of Bs[Ng,Kg], elements k .. k+CE-1; where !ok (beyond K, idle slots of the
+// ring) a piece of zeros is read instead, so that a weight row that holds an infinity does
+// not meet 0 * inf there.
+__device__ __attribute__((aligned(16))) const uint32_t g_zero_piece[4] = {0u, 0u, 0u, 0u};
 template <int ES, bool NT>
 __device__ __forceinline__ u32x4 fetch_B(const DevProblem &P, int64_t row_off, int k, bool ok) {
-  return load_piece_vec<ES, NT>(P.B, row_off + (ok ? k : 0));
+  const char SK_GLOBAL *p = as_global<char>(P.B) + (row_off + k) * ES;
+  const u32x4 SK_GLOBAL *q = (const u32x4 SK_GLOBAL *)(ok ? p : as_global<char>(g_zero_piece));
+  if constexpr (NT)
+    return __builtin_nontemporal_load(q);
+  else
+    return *q;
 }
 
 // Where row m of the activation operand starts.
@@ -301,6 +320,7 @@ __device__ __forceinline__ void mma32(const u32x4 &a, const u32x4 &b, f32x16 &c)
 // partials in slice order (so the result does not depend on arrival order)
 // and writes C.
 constexpr int SKINNY_CHUNK_BYTES = 16384;
+constexpr int ilog2(int x) { return x <= 1 ? 0 : 1 + ilog2(x >> 1); }
 
 // Two registers loaded with the full-line map hold, for a 16-row MFMA block,
 //   first : lanes r16 < 8 -> (row r16, pieces 0..3)      lanes r16 >= 8 -> (row r16-8, pieces 4..7)
@@ -400,7 +420,7 @@ __device__ __forceinline__ void run_skinny(const DevProblem &P, const sk_tile &T
   constexpr int ROWS = 16 * RM;                     // activation rows held in LDS
   constexpr int ROWB = SKINNY_CHUNK_BYTES / ROWS;   // bytes of K per row and chunk
   constexpr int LROW = ROWB + 16;                   // padded LDS row (bank spread)
-  constexpr int BPC_LOG2 = RM == 1 ? 3 : (RM == 2 ? 2 : 1);
+  constexpr int BPC_LOG2 = ilog2(ROWB / 128);
   constexpr int BPC = 1 << BPC_LOG2;                // blocks per chunk: 8, 4, 2
   constexpr int PPR = ROWB / 16;                    // pieces per row and chunk
   constexpr int BUF = ROWS * LROW;                  // bytes per LDS buffer
@@ -424,19 +444,20 @@ __device__ __forceinline__ void run_skinny(const DevProblem &P, const sk_tile &T
   const int nchunks = (nblocks + BPC - 1) >> BPC_LOG2;
   const int nslots = nchunks << BPC_LOG2;  // block slots per wave (blocks past the end read as zero)
 
-  // staging map: thread -> four consecutive pieces (64 bytes) of one activation row
-  constexpr int TPR = PPR / 4;  // threads per row
+  // staging map: thread -> SPT consecutive pieces of one activation row
+  constexpr int SPT = SKINNY_CHUNK_BYTES / (WG_THREADS * 16);
+  constexpr int TPR = PPR / SPT;  // threads per row
   const int s_row = tid / TPR;
-  const int s_piece = (tid % TPR) * 4;
+  const int s_piece = (tid % TPR) * SPT;
   const bool s_ok = s_row < P.Mg;
   const RowA srow = row_of(P, s_ok ? s_row : 0);
   const int s_lds = s_row * LROW + s_piece * 16;
-  u32x4 ar[4];
-  bool ar_ok[4];
+  u32x4 ar[SPT];
+  bool ar_ok[SPT];
   auto stage_load = [&](int c) {
     const int k = k0 + ((c << BPC_LOG2) * 8 + s_piece) * CE;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < SPT; ++i) {
       ar_ok[i] = s_ok && k + i * CE < k_stop;
       ar[i] = fetch_A<ES>(P, srow, k + i * CE, ar_ok[i]);
     }
@@ -444,7 +465,7 @@ __device__ __forceinline__ void run_skinny(const DevProblem &P, const sk_tile &T
   auto stage_store = [&](int c) {
     unsigned char *base = lds + (c & 1) * BUF + s_lds;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) *(u32x4 *)(base + i * 16) = keep_if(ar_ok[i], ar[i]);
+    for (int i = 0; i < SPT; ++i) *(u32x4 *)(base + i * 16) = keep_if(ar_ok[i], ar[i]);
   };
 
   const bool vec_c = (P.flags & FLAG_VEC_C) != 0;
@@ -730,7 +751,8 @@ __device__ __forceinline__ void run_tile(const DevProblem &P, const sk_tile &T, 
       }
     }
 #pragma unroll
-    for (int i = 0; i < B_ITERS; ++i) xb[i] = *(const u32x4 SK_GLOBAL *)(pb[i] + (int64_t)(in ? k_load : 0) * ES);
+    for (int i = 0; i < B_ITERS; ++i)
+      xb[i] = *(const u32x4 SK_GLOBAL *)(in ? pb[i] + (int64_t)k_load * ES : as_global<char>(g_zero_piece));
     k_load += KB;
   };
   auto lstore = [&](int buf, const u32x4(&xa)[A_ITERS], const u32x4(&xb)[B_ITERS], const bool(&xok)[A_ITERS]) {

@@ -164,6 +164,60 @@ def test_exact_integer_products():
         assert np.array_equal(b.output(0), want), dtype
 
 
+@pytest.mark.parametrize("dtype,keep,extra", [("bf16", 8, 8), ("f16", 11, 10)])
+def test_outputs_round_to_nearest_even(dtype, keep, extra):
+    """Accumulators with more bits than the output type, exact in fp32: the stored pattern must be the
+    round-to-nearest-even one, bit for bit (ties both ways, carries into the exponent, overflow to inf)."""
+    rng = np.random.default_rng(7)
+    n = 4096
+    # x = sign * 1.f * 2^e with `keep + extra` significant bits
+    mant = rng.integers(1 << (keep + extra - 1), 1 << (keep + extra), size=n).astype(np.int64)
+    half = 1 << (extra - 1)
+    mant[:512] = (mant[:512] >> extra << extra) | half                       # exact ties, upper part even or odd
+    mant[512:640] = (1 << (keep + extra)) - 1 - rng.integers(0, half, size=128)  # round up into the next binade
+    e = rng.integers(0, 6, size=n)
+    x = (mant.astype(np.float64) * np.exp2(e - (keep + extra - 1))).astype(np.float32)
+    x *= np.where(rng.integers(0, 2, size=n) == 1, -1.0, 1.0).astype(np.float32)
+    if dtype == "bf16":
+        x[640:648] = np.array([0x7F7FFF00, 0x7F7F8000, 0x7F7F7F00, 0x7F7F0000, 0xFF7FFF00, 0x00800000,
+                               0x7F800000, 0xFF800000], dtype=np.uint32).view(np.float32)
+    trunc_mask = np.uint32(0xFFFF0000) if dtype == "bf16" else None
+    if dtype == "bf16":
+        hi = (x.view(np.uint32) & trunc_mask).view(np.float32)
+    else:
+        hi = (mant >> extra << extra).astype(np.float64) * np.exp2(e - (keep + extra - 1))
+        hi = (np.sign(x) * hi).astype(np.float32)
+    with np.errstate(invalid="ignore"):
+        rem = np.where(np.isfinite(x), x - hi, 0.0).astype(np.float32)
+    hb, hv = Q.round_to(dtype, hi)
+    rb, rv = Q.round_to(dtype, rem)
+    assert np.array_equal(hv, hi) and np.array_equal(rv, rem), "test values must be exact in the input type"
+    want_bits, _ = Q.round_to(dtype, x)
+    K = 16
+    for M in (1, 40, 70):                      # one, four row blocks; LDS tile
+        A = np.zeros((M, K), dtype=np.float32)
+        A[:, 0] = 1.0
+        A[:, 1] = 1.0
+        B = np.zeros((n, K), dtype=np.float32)
+        B[:, 0] = hi
+        B[:, 1] = rem
+        spec = g(M, n, K, dtype)
+        b = H.Batch([spec], seed=0)
+        bitsA, _ = Q.round_to(dtype, A)
+        bitsB, _ = Q.round_to(dtype, B)
+        b.bufs[0].zero_()
+        b.bufs[1].zero_()
+        b.bufs[0][:M * K] = torch.from_numpy(bitsA.view(np.int16).ravel()).to("cuda")
+        b.bufs[1][:n * K] = torch.from_numpy(bitsB.view(np.int16).ravel()).to("cuda")
+        with b.plan() as plan:
+            sk.sk_launch(plan, H.stream_handle())
+            _sync()
+        got = b.output_bits(0)
+        for m in range(M):
+            bad = np.nonzero(got[m] != want_bits.view(got.dtype))[0]
+            assert bad.size == 0, (dtype, M, m, bad[:5], x[bad[:5]], got[m][bad[:5]], want_bits[bad[:5]])
+
+
 def test_completion_stamps():
     specs = workloads.config(5, seed=0)[:24]
     b = H.Batch(specs, seed=0)
