@@ -113,7 +113,7 @@ def tiling(p, T: int, prm: Params):
     if tb > 2 * T:
         chunk = 256
         nchunks = -(-kg // chunk)
-        want = min(nchunks, -(-tb // T), 255)
+        want = min(nchunks, -(-tb // T), 255, max(1, kg // 1024))   # slices of at least 1024 elements
         per = -(-nchunks // want)
         S = -(-nchunks // per)
         slice_len = per * chunk

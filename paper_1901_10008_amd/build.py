@@ -15,6 +15,10 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-fno-gpu-rdc", "-Wall", "-Wno-unused-function",
+    # The tile queue's atomic is issued by one thread and its answer is wanted several loop steps
+    # later.  The compiler's wave-level atomic combining reads the answer back at once, which
+    # makes the wave wait for every load in flight at that point.
+    "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
 ]
 
 

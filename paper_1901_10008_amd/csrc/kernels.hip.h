@@ -195,10 +195,17 @@ __device__ __forceinline__ u32x4 keep_if(bool ok, const u32x4 &v) {
 // ring) a piece of zeros is read instead, so that a weight row that holds an infinity does
 // not meet 0 * inf there.
 __device__ __attribute__((aligned(16))) const uint32_t g_zero_piece[4] = {0u, 0u, 0u, 0u};
+// Its address in vector registers.  (Given the symbol itself, the compiler selects between the two
+// places with a branch and a load in either arm, and then waits for every load in flight.)
+__device__ __forceinline__ uintptr_t zero_piece_address() {
+  uintptr_t z = (uintptr_t)g_zero_piece;
+  asm volatile("" : "+v"(z));
+  return z;
+}
 template <int ES, bool NT>
-__device__ __forceinline__ u32x4 fetch_B(const DevProblem &P, int64_t row_off, int k, bool ok) {
-  const char SK_GLOBAL *p = as_global<char>(P.B) + (row_off + k) * ES;
-  const u32x4 SK_GLOBAL *q = (const u32x4 SK_GLOBAL *)(ok ? p : as_global<char>(g_zero_piece));
+__device__ __forceinline__ u32x4 fetch_B(const DevProblem &P, int64_t row_off, int k, bool ok, uintptr_t zeros) {
+  const uintptr_t p = (uintptr_t)P.B + (uintptr_t)((row_off + k) * ES);
+  const u32x4 SK_GLOBAL *q = (const u32x4 SK_GLOBAL *)(ok ? p : zeros);
   if constexpr (NT)
     return __builtin_nontemporal_load(q);
   else
@@ -384,19 +391,22 @@ struct SplitK {
 struct Prefetch {
   const TileWork *work;
   uint32_t *counter;  // the queue (null: tiles are not handed out by the queue)
-  uint32_t base;      // index of the first tile the queue hands out
-  uint32_t next;      // meaningful in lane 0 of wave 0 (in all lanes when there is no queue)
+  uint32_t base;      // index of the first tile the queue hands out (0 when there is no queue)
+  uint32_t next;      // next tile's index minus `base`; meaningful in lane 0 of wave 0 (in all lanes when there
+                      // is no queue).  The queue's answer is left untouched until issue() needs it: anything
+                      // computed from it at once would make the wave wait for the atomic, and with it for
+                      // every load in flight.
   uint32_t last;      // last valid index of the launch
   int tid;            // this tile's copy of the thread index (see the tile loop)
   uint32_t word = 0;
   __device__ __forceinline__ void claim() {
     if (counter) {
       next = 0u;
-      if (tid == 0) next = base + atomicAdd(counter, 1u);
+      if (tid == 0) next = atomicAdd(counter, 1u);
     }
   }
   __device__ __forceinline__ void issue() {
-    uint32_t idx = (uint32_t)__builtin_amdgcn_readfirstlane((int)next);
+    uint32_t idx = (uint32_t)__builtin_amdgcn_readfirstlane((int)next) + base;
     if (idx > last) idx = last;  // past the end of the table: the workgroup is about to leave
     const int lane = tid & 63;
     word = as_global<uint32_t>(work + idx)[lane < WORK_DWORDS ? lane : 0];
@@ -483,6 +493,7 @@ __device__ __forceinline__ void run_skinny(const DevProblem &P, const sk_tile &T
   // r16 in lane r16 with pieces 0..3 resp. 4..7 in slot q; two DPP half-row swaps per pair of
   // registers put the data there when the block is consumed (see fix_lo / fix_hi).
   const int piece = q + 4 * (r16 >> 3);
+  const uintptr_t zeros = zero_piece_address();
   int64_t wrow[4] = {0, 0, 0, 0};
   auto set_load_rows = [&](int it) {
     const int g = it * 4 + wave;
@@ -502,7 +513,7 @@ __device__ __forceinline__ void run_skinny(const DevProblem &P, const sk_tile &T
     const int k = k0 + p_blk * KB + piece * CE;
     const bool in = p_act && k < k_stop;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) w[j] = fetch_B<ES, true>(P, wrow[j], k, in);
+    for (int j = 0; j < 4; ++j) w[j] = fetch_B<ES, true>(P, wrow[j], k, in, zeros);
     if (++p_blk == nslots) {
       p_blk = 0;
       ++p_it;
@@ -721,6 +732,7 @@ __device__ __forceinline__ void run_tile(const DevProblem &P, const sk_tile &T, 
   }
   u32x4 ra[NS][A_ITERS], rb[NS][B_ITERS];
   bool ra_ok[NS][A_ITERS];
+  const uintptr_t zeros = zero_piece_address();
   // Loads are unconditional (stages past the end of the reduction read clamped addresses and
   // are never multiplied), so the number of loads in flight is the same on every path.
   int k_load = k_begin + c8 * CE;  // reduction index of this thread's piece in the next stage to load
@@ -752,7 +764,7 @@ __device__ __forceinline__ void run_tile(const DevProblem &P, const sk_tile &T, 
     }
 #pragma unroll
     for (int i = 0; i < B_ITERS; ++i)
-      xb[i] = *(const u32x4 SK_GLOBAL *)(in ? pb[i] + (int64_t)k_load * ES : as_global<char>(g_zero_piece));
+      xb[i] = *(const u32x4 SK_GLOBAL *)(in ? (uintptr_t)pb[i] + (uintptr_t)((int64_t)k_load * ES) : zeros);
     k_load += KB;
   };
   auto lstore = [&](int buf, const u32x4(&xa)[A_ITERS], const u32x4(&xb)[B_ITERS], const bool(&xok)[A_ITERS]) {
@@ -955,8 +967,8 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sk_superkernel(const TileWork *
     // the loads and stores in flight.
     int tid = threadIdx.x;
     asm volatile("" : "+v"(tid));
-    Prefetch pf{work, a.dynamic ? &a.counters[0] : nullptr, a.tile_begin + gridDim.x, t + gridDim.x, a.tile_end - 1u,
-                tid};
+    Prefetch pf{work, a.dynamic ? &a.counters[0] : nullptr, a.dynamic ? a.tile_begin + gridDim.x : 0u, t + gridDim.x,
+                a.tile_end - 1u, tid};
     const sk_tile &T = W.tile;
     const DevProblem &P = W.prob;
     if constexpr (ONLY_DT >= 0) {
@@ -973,7 +985,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sk_superkernel(const TileWork *
     if (tid < 64) {
       // wave 0 hands the next record to the other waves
       if (tid < WORK_DWORDS) s_mail[par][tid] = pf.word;
-      if (tid == 0) s_mail[par][WORK_DWORDS] = pf.next;
+      if (tid == 0) s_mail[par][WORK_DWORDS] = pf.next + pf.base;
     }
     __syncthreads();
     if (a.remaining && tid == 0) {

@@ -251,7 +251,9 @@ sk_status plan_host(const sk_problem *problems, int32_t n, const sk_plan_params 
       if (tb > 2 * T) {
         const int64_t chunk = 256;  // reduction elements: whole stages of every element type
         const int64_t nchunks = (c.Kg + chunk - 1) / chunk;
-        const int64_t want = std::min<int64_t>(std::min<int64_t>(nchunks, (tb + T - 1) / T), 255);
+        // a slice hands over 64 KB of partial sums: never shorter than 1024 reduction elements
+        int64_t want = std::min<int64_t>(std::min<int64_t>(nchunks, (tb + T - 1) / T), 255);
+        want = std::min<int64_t>(want, std::max<int64_t>(1, c.Kg / 1024));
         const int64_t per = (nchunks + want - 1) / want;
         S = (nchunks + per - 1) / per;
         slice_len = per * chunk;

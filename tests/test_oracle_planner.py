@@ -123,17 +123,18 @@ def test_hand_enumerated_lds_tiles():
          (9, 128, 0, 68, 128, 576), (9, 128, 128, 68, 72, 576)]
     assert [x["out_tile_id"] for x in t] == list(range(4))
     assert all(x["S"] == 1 and x["k0"] == 0 for x in t)
-    # the operands of one tile are 256 rows x 576 x 2 B = 288 KiB.  Target 128 KiB: 288 > 2*128, so the
-    # reduction is cut in whole 256-element chunks: 3 chunks, wanted ceil(288/128) = 3 slices of one chunk
-    prm = P.Params(tile_bytes_min=128 << 10, tile_bytes_max=128 << 10)
-    t = P.decode(P.plan([conv(14, 64, 192 + 8, 3)], prm)[0])
-    assert len(t) == 12
-    assert [(x["m0"], x["n0"], x["ks_idx"], x["S"], x["k0"], x["k_len"], x["out_tile_id"]) for x in t[:6]] == \
-        [(0, 0, 0, 3, 0, 256, 0), (0, 0, 1, 3, 256, 256, 0), (0, 0, 2, 3, 512, 64, 0),
-         (0, 128, 0, 3, 0, 256, 1), (0, 128, 1, 3, 256, 256, 1), (0, 128, 2, 3, 512, 64, 1)]
-    # target 160 KiB: 288 <= 2*160, not cut
-    prm = P.Params(tile_bytes_min=160 << 10, tile_bytes_max=160 << 10)
+    # a short reduction is never cut, however small the target (a slice hands over 64 KB of partial sums
+    # and is at least 1024 elements long): Kg = 576
+    prm = P.Params(tile_bytes_min=32 << 10, tile_bytes_max=32 << 10)
     assert all(x["S"] == 1 for x in P.decode(P.plan([conv(14, 64, 192 + 8, 3)], prm)[0]))
+    # Kg = 2304 (3x3x256): operands 1152 KiB, target 32 KiB: 9 chunks of 256, wanted min(9, 36, 2304 // 1024 = 2)
+    # = 2 slices: five and four chunks
+    t = P.decode(P.plan([conv(14, 256, 128, 3)], prm)[0])
+    assert [(x["m0"], x["ks_idx"], x["S"], x["k0"], x["k_len"], x["out_tile_id"]) for x in t] == \
+        [(0, 0, 2, 0, 1280, 0), (0, 1, 2, 1280, 1024, 0), (128, 0, 2, 0, 1280, 1), (128, 1, 2, 1280, 1024, 1)]
+    # not cut while the operands stay within twice the target: 1152 KiB <= 2 * 576 KiB
+    prm = P.Params(tile_bytes_min=576 << 10, tile_bytes_max=576 << 10)
+    assert all(x["S"] == 1 for x in P.decode(P.plan([conv(14, 256, 128, 3)], prm)[0]))
     # Kg = 4608 (3x3x512), target 1 MiB: operands 2304 KiB > 2 MiB; 18 chunks, wanted ceil(2304/1024) = 3,
     # six chunks per slice
     t = P.decode(P.plan([conv(14, 512, 128, 3)], whole)[0])
