@@ -400,10 +400,9 @@ struct Prefetch {
   int tid;            // this tile's copy of the thread index (see the tile loop)
   uint32_t word = 0;
   __device__ __forceinline__ void claim() {
-    if (counter) {
-      next = 0u;
-      if (tid == 0) next = atomicAdd(counter, 1u);
-    }
+    // (lanes other than thread 0 keep whatever `next` held: it is never used, and any
+    // instruction that touched the register here would have to wait for an earlier answer)
+    if (counter && tid == 0) next = atomicAdd(counter, 1u);
   }
   __device__ __forceinline__ void issue() {
     uint32_t idx = (uint32_t)__builtin_amdgcn_readfirstlane((int)next) + base;
