@@ -180,16 +180,9 @@ __device__ __forceinline__ u32x4 load_piece_vec(const void *base, int64_t off) {
 // Loads in the MFMA paths are never placed under a branch (a conditional load makes the
 // compiler wait for it at the end of the branch, which serialises the loads of a stage)
 // and their values are not touched before they are consumed (a select right behind a
-// load makes the wave wait for it at once).  So: addresses are clamped to a readable
-// place, activation pieces that must read as zero (beyond K, in the padding, rows past
-// Mg) are zeroed when they are written to LDS, and weight pieces beyond K are read from
-// a piece of zeros in device memory instead of from their row.
-__device__ __forceinline__ u32x4 keep_if(bool ok, const u32x4 &v) {
-  u32x4 r;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) r[i] = ok ? v[i] : 0u;
-  return r;
-}
+// load makes the wave wait for it at once).  So a piece that must read as zero (beyond K,
+// in a convolution's padding, rows past Mg, idle slots of a ring) is not masked after the
+// load: its address is replaced by that of a piece of zeros in device memory.
 
 // Weight piece: row n of Bs[Ng,Kg], elements k .. k+CE-1; where !ok (beyond K, idle slots of the
 // ring) a piece of zeros is read instead, so that a weight row that holds an infinity does
@@ -248,14 +241,14 @@ __device__ __forceinline__ bool patch_offset(const DevProblem &P, const RowA &ro
   return (unsigned)h < (unsigned)P.H && (unsigned)w < (unsigned)P.W;
 }
 
-// Activation piece: elements k .. k+CE-1 of row `row` of A'.  `ok` comes back false where
-// the piece must read as zero (caller said so, or the tap falls into the padding); the
-// caller zeroes it with keep_if when it writes the piece to LDS.
+// Activation piece: elements k .. k+CE-1 of row `row` of A'.  Where the piece must read as
+// zero (`ok` false on entry, or the tap falls into the padding) the piece of zeros is loaded.
 template <int ES>
-__device__ __forceinline__ u32x4 fetch_A(const DevProblem &P, const RowA &row, int k, bool &ok) {
+__device__ __forceinline__ u32x4 fetch_A(const DevProblem &P, const RowA &row, int k, bool ok, uintptr_t zeros) {
   int64_t off = row.base + k;
   if (P.gather) ok = patch_offset(P, row, k, off) && ok;
-  return load_piece_vec<ES, false>(P.A, ok ? off : 0);
+  const uintptr_t p = (uintptr_t)P.A + (uintptr_t)(off * ES);
+  return *(const u32x4 SK_GLOBAL *)(ok ? p : zeros);
 }
 
 // Single elements as float, for run_generic.
@@ -458,6 +451,7 @@ __device__ __forceinline__ void run_skinny(const DevProblem &P, const sk_tile &T
   const int nchunks = (nblocks + BPC - 1) >> BPC_LOG2;
   const int nslots = nchunks << BPC_LOG2;  // block slots per wave (blocks past the end read as zero)
 
+  const uintptr_t zeros = zero_piece_address();
   // staging map: thread -> SPT consecutive pieces of one activation row
   constexpr int SPT = CHUNK_BYTES / (WG_THREADS * 16);
   constexpr int TPR = PPR / SPT;  // threads per row
@@ -467,19 +461,17 @@ __device__ __forceinline__ void run_skinny(const DevProblem &P, const sk_tile &T
   const RowA srow = row_of(P, s_ok ? s_row : 0);
   const int s_lds = s_row * LROW + s_piece * 16;
   u32x4 ar[SPT];
-  bool ar_ok[SPT];
   auto stage_load = [&](int c) {
     const int k = k0 + ((c << BPC_LOG2) * 8 + s_piece) * CE;
 #pragma unroll
     for (int i = 0; i < SPT; ++i) {
-      ar_ok[i] = s_ok && k + i * CE < k_stop;
-      ar[i] = fetch_A<ES>(P, srow, k + i * CE, ar_ok[i]);
+      ar[i] = fetch_A<ES>(P, srow, k + i * CE, s_ok && k + i * CE < k_stop, zeros);
     }
   };
   auto stage_store = [&](int c) {
     unsigned char *base = lds + (c & 1) * BUF + s_lds;
 #pragma unroll
-    for (int i = 0; i < SPT; ++i) *(u32x4 *)(base + i * 16) = keep_if(ar_ok[i], ar[i]);
+    for (int i = 0; i < SPT; ++i) *(u32x4 *)(base + i * 16) = ar[i];
   };
 
   const bool vec_c = (P.flags & FLAG_VEC_C) != 0;
@@ -497,7 +489,6 @@ __device__ __forceinline__ void run_skinny(const DevProblem &P, const sk_tile &T
   // r16 in lane r16 with pieces 0..3 resp. 4..7 in slot q; two DPP half-row swaps per pair of
   // registers put the data there when the block is consumed (see fix_lo / fix_hi).
   const int piece = q + 4 * (r16 >> 3);
-  const uintptr_t zeros = zero_piece_address();
   int64_t wrow[4] = {0, 0, 0, 0};
   auto set_load_rows = [&](int it) {
     const int g = it * 4 + wave;
@@ -735,19 +726,17 @@ __device__ __forceinline__ void run_tile(const DevProblem &P, const sk_tile &T, 
     tap_off = ((int64_t)g_r * P.W + g_s) * P.Cin + g_c;
   }
   u32x4 ra[NS][A_ITERS], rb[NS][B_ITERS];
-  bool ra_ok[NS][A_ITERS];
   const uintptr_t zeros = zero_piece_address();
   // Loads are unconditional (stages past the end of the reduction read clamped addresses and
   // are never multiplied), so the number of loads in flight is the same on every path.
   int k_load = k_begin + c8 * CE;  // reduction index of this thread's piece in the next stage to load
-  auto gload = [&](u32x4(&xa)[A_ITERS], u32x4(&xb)[B_ITERS], bool(&xok)[A_ITERS]) {
+  auto gload = [&](u32x4(&xa)[A_ITERS], u32x4(&xb)[B_ITERS]) {
     const bool in = k_load < k_stop;
     if (gvec) {
 #pragma unroll
       for (int i = 0; i < A_ITERS; ++i) {
-        xok[i] = in && (unsigned)(hb[i] + g_r) < (unsigned)P.H && (unsigned)(wb[i] + g_s) < (unsigned)P.W;
-        const char SK_GLOBAL *q = pa[i] + tap_off * ES;
-        xa[i] = *(const u32x4 SK_GLOBAL *)(xok[i] ? q : as_global<char>(P.A));
+        const bool ok = in && (unsigned)(hb[i] + g_r) < (unsigned)P.H && (unsigned)(wb[i] + g_s) < (unsigned)P.W;
+        xa[i] = *(const u32x4 SK_GLOBAL *)(ok ? (uintptr_t)pa[i] + (uintptr_t)(tap_off * ES) : zeros);
       }
       g_c += KB;
       tap_off += KB;
@@ -761,42 +750,40 @@ __device__ __forceinline__ void run_tile(const DevProblem &P, const sk_tile &T, 
       }
     } else {
 #pragma unroll
-      for (int i = 0; i < A_ITERS; ++i) {
-        xok[i] = in;
-        xa[i] = *(const u32x4 SK_GLOBAL *)(pa[i] + (int64_t)(in ? k_load : 0) * ES);
-      }
+      for (int i = 0; i < A_ITERS; ++i)
+        xa[i] = *(const u32x4 SK_GLOBAL *)(in ? (uintptr_t)pa[i] + (uintptr_t)((int64_t)k_load * ES) : zeros);
     }
 #pragma unroll
     for (int i = 0; i < B_ITERS; ++i)
       xb[i] = *(const u32x4 SK_GLOBAL *)(in ? (uintptr_t)pb[i] + (uintptr_t)((int64_t)k_load * ES) : zeros);
     k_load += KB;
   };
-  auto lstore = [&](int buf, const u32x4(&xa)[A_ITERS], const u32x4(&xb)[B_ITERS], const bool(&xok)[A_ITERS]) {
+  auto lstore = [&](int buf, const u32x4(&xa)[A_ITERS], const u32x4(&xb)[B_ITERS]) {
     unsigned char *a = lds + buf * STAGE + srow * LDS_ROW + c8 * 16;
     unsigned char *bb = a + BM * LDS_ROW;
 #pragma unroll
-    for (int i = 0; i < A_ITERS; ++i) *(u32x4 *)(a + 32 * i * LDS_ROW) = keep_if(xok[i], xa[i]);
+    for (int i = 0; i < A_ITERS; ++i) *(u32x4 *)(a + 32 * i * LDS_ROW) = xa[i];
 #pragma unroll
     for (int i = 0; i < B_ITERS; ++i) *(u32x4 *)(bb + 32 * i * LDS_ROW) = xb[i];
   };
 
   const int nstages = (k_stop - k_begin + KB - 1) / KB;
 #pragma unroll
-  for (int u = 0; u < NS - 1; ++u) gload(ra[u], rb[u], ra_ok[u]);
-  lstore(0, ra[0], rb[0], ra_ok[0]);
+  for (int u = 0; u < NS - 1; ++u) gload(ra[u], rb[u]);
+  lstore(0, ra[0], rb[0]);
   __syncthreads();
   int buf = 0;
   for (int s0 = 0; s0 < nstages; s0 += NS) {
 #pragma unroll
     for (int u = 0; u < NS; ++u) {
       pf.at_step(s0 + u, nstages, CLAIM_LEAD, ISSUE_GAP);
-      gload(ra[(u + NS - 1) % NS], rb[(u + NS - 1) % NS], ra_ok[(u + NS - 1) % NS]);
+      gload(ra[(u + NS - 1) % NS], rb[(u + NS - 1) % NS]);
       if (s0 + u < nstages) {
         // stage s0+u is in LDS buffer `buf`; put stage s0+u+1 (possibly past the end: zeros
         // times finite weights, never multiplied) into the other one while this one is used
         const unsigned char *la = lds + buf * STAGE;
         const unsigned char *lb = la + BM * LDS_ROW;
-        lstore(buf ^ 1, ra[(u + 1) % NS], rb[(u + 1) % NS], ra_ok[(u + 1) % NS]);
+        lstore(buf ^ 1, ra[(u + 1) % NS], rb[(u + 1) % NS]);
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
           const int piece = (2 * kk + half) * 16;
