@@ -783,21 +783,27 @@ __device__ __forceinline__ void run_tile(const DevProblem &P, const sk_tile &T, 
         // times finite weights, never multiplied) into the other one while this one is used
         const unsigned char *la = lds + buf * STAGE;
         const unsigned char *lb = la + BM * LDS_ROW;
+        // operand fragments of the first quarter of the stage are requested before the next
+        // stage is written, those of quarter kk+1 before the MFMAs of quarter kk
+        u32x4 fa[2][FM], fb[2][FN];
+        auto frag = [&](int kk, u32x4(&xa)[FM], u32x4(&xb)[FN]) {
+          const int piece = (2 * kk + half) * 16;
+#pragma unroll
+          for (int fm = 0; fm < FM; ++fm)
+            xa[fm] = *(const u32x4 *)(la + ((wm * FM + fm) * 32 + l32) * LDS_ROW + piece);
+#pragma unroll
+          for (int fn = 0; fn < FN; ++fn)
+            xb[fn] = *(const u32x4 *)(lb + ((wn * FN + fn) * 32 + l32) * LDS_ROW + piece);
+        };
+        frag(0, fa[0], fb[0]);
         lstore(buf ^ 1, ra[(u + 1) % NS], rb[(u + 1) % NS]);
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-          const int piece = (2 * kk + half) * 16;
-          u32x4 fa[FM], fb[FN];
-#pragma unroll
-          for (int fm = 0; fm < FM; ++fm)
-            fa[fm] = *(const u32x4 *)(la + ((wm * FM + fm) * 32 + l32) * LDS_ROW + piece);
-#pragma unroll
-          for (int fn = 0; fn < FN; ++fn)
-            fb[fn] = *(const u32x4 *)(lb + ((wn * FN + fn) * 32 + l32) * LDS_ROW + piece);
+          if (kk + 1 < 4) frag(kk + 1, fa[(kk + 1) & 1], fb[(kk + 1) & 1]);
 #pragma unroll
           for (int fn = 0; fn < FN; ++fn)
 #pragma unroll
-            for (int fm = 0; fm < FM; ++fm) mma32<DT>(fb[fn], fa[fm], acc[fn][fm]);
+            for (int fm = 0; fm < FM; ++fm) mma32<DT>(fb[kk & 1][fn], fa[kk & 1][fm], acc[fn][fm]);
         }
         __syncthreads();
         buf ^= 1;
@@ -850,6 +856,65 @@ __device__ __forceinline__ void run_tile(const DevProblem &P, const sk_tile &T, 
   }
 
   // lane holds, per (fn, fm): row m = l32, columns 8*(i/4) + 4*half + (i%4)
+  //
+  // Written from the accumulators a store instruction would cover 32 rows with 16 bytes each.
+  // Where C allows 16-byte stores the tile goes through LDS instead (free by now: every wave has
+  // passed the last stage's barrier) and leaves as whole rows: 16 lanes x 16 bytes side by side.
+  constexpr int OROW = BN * ES + 16;  // padded row of the output tile in LDS
+  static_assert(BM * OROW <= LDS_TILE_BYTES, "output tile does not fit the LDS buffer");
+  const bool wide = ((uintptr_t)P.C % 16 == 0) && ((P.ldc * ES) % 16 == 0);
+  if (wide) {
+#pragma unroll
+    for (int fm = 0; fm < FM; ++fm) {
+      const int r = (wm * FM + fm) * 32 + l32;
+#pragma unroll
+      for (int fn = 0; fn < FN; ++fn) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int c = (wn * FN + fn) * 32 + 8 * j + 4 * half;
+          unsigned char *q = lds + r * OROW + c * ES;
+          if constexpr (ES == 4) {
+            *(f32x4 *)q = f32x4{acc[fn][fm][4 * j], acc[fn][fm][4 * j + 1], acc[fn][fm][4 * j + 2], acc[fn][fm][4 * j + 3]};
+          } else {
+            u32x2 o;
+            o.x = cvt_pack<DT>(acc[fn][fm][4 * j], acc[fn][fm][4 * j + 1]);
+            o.y = cvt_pack<DT>(acc[fn][fm][4 * j + 2], acc[fn][fm][4 * j + 3]);
+            *(u32x2 *)q = o;
+          }
+        }
+      }
+    }
+    __syncthreads();
+    constexpr int PIECES = BN * ES / 16;             // 16-byte pieces per output row
+    constexpr int RPI = WG_THREADS / PIECES;         // rows per store instruction
+    const int pc = tid % PIECES, pr = tid / PIECES;
+    const int n = n0 + pc * CE;
+#pragma unroll
+    for (int i = 0; i < BM / RPI; ++i) {
+      const int r = pr + i * RPI;
+      const int m = m0 + r;
+      if (m < m_end && n < n_end) {
+        const u32x4 v = *(const u32x4 *)(lds + r * OROW + pc * 16);
+        char SK_GLOBAL *dst = as_global_mut<char>(P.C) + ((int64_t)m * P.ldc + n) * ES;
+        if (n + CE <= n_end) {
+          *(u32x4 SK_GLOBAL *)dst = v;
+        } else {
+          // ragged right edge: element by element
+#pragma unroll
+          for (int e = 0; e < CE; ++e) {
+            if (n + e < n_end) {
+              if constexpr (ES == 4)
+                ((uint32_t SK_GLOBAL *)dst)[e] = v[e];
+              else
+                ((uint16_t SK_GLOBAL *)dst)[e] = (uint16_t)(v[e / 2] >> (16 * (e & 1)));
+            }
+          }
+        }
+      }
+    }
+    // (the barrier at the end of every tile keeps the next tile's LDS writes behind these reads)
+    return;
+  }
   const bool vec_c = (P.flags & FLAG_VEC_C) != 0;
 #pragma unroll
   for (int fm = 0; fm < FM; ++fm) {
