@@ -52,7 +52,7 @@ class Params:
     tile_bytes_min: int = 32 * 1024
     balance_div: int = 2048
     max_groups: int = 256
-    tail_div: int = 512             # 0: tiles do not shrink towards the end of the table
+    tail_div: int = 384             # 0: tiles do not shrink towards the end of the table
 
 
 def canonical(p):

@@ -351,5 +351,5 @@ extern "C" void sk_plan_params_default(sk_plan_params *p) {
   p->balance_div = 2048;
   p->max_groups = 256;
   p->grid_limit = 0;
-  p->tail_div = 512;
+  p->tail_div = 384;
 }
