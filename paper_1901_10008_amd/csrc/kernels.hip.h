@@ -576,17 +576,26 @@ __device__ __forceinline__ void run_skinny(const DevProblem &P, const sk_tile &T
       if (live) {
         if (it * 4 + wave < ngroups) {
           const unsigned char *abase = lds + buf * BUF + (blk & (BPC - 1)) * 128 + q * 16 + r16 * LROW;
+          // All activation pieces of the block are requested from LDS first, each into registers
+          // of its own (read one row block at a time into the same registers, every read would
+          // wait for the MFMAs of the row block before it), and before the weights are touched:
+          // the LDS round trip then overlaps the wait for the weight block.
+          u32x4 a0[RM], a1[RM];
+#pragma unroll
+          for (int mb = 0; mb < RM; ++mb) {
+            a0[mb] = *(const u32x4 *)(abase + mb * 16 * LROW);       // pieces 0..3
+            a1[mb] = *(const u32x4 *)(abase + mb * 16 * LROW + 64);  // pieces 4..7
+          }
+          __builtin_amdgcn_sched_barrier(0);  // (the scheduler would sink the reads back to their uses)
           // rows 16rb..16rb+15: pieces 0..3 (x) and 4..7 (y) in MFMA lane order
           const u32x4 x0 = fix_lo(w[u][0], w[u][1]), y0 = fix_hi(w[u][0], w[u][1]);
           const u32x4 x1 = fix_lo(w[u][2], w[u][3]), y1 = fix_hi(w[u][2], w[u][3]);
 #pragma unroll
           for (int mb = 0; mb < RM; ++mb) {
-            const u32x4 a0 = *(const u32x4 *)(abase + mb * 16 * LROW);       // pieces 0..3
-            const u32x4 a1 = *(const u32x4 *)(abase + mb * 16 * LROW + 64);  // pieces 4..7
-            mma16<DT>(x0, a0, acc[0][mb]);
-            mma16<DT>(y0, a1, acc[0][mb]);
-            mma16<DT>(x1, a0, acc[1][mb]);
-            mma16<DT>(y1, a1, acc[1][mb]);
+            mma16<DT>(x0, a0[mb], acc[0][mb]);
+            mma16<DT>(x1, a0[mb], acc[1][mb]);
+            mma16<DT>(y0, a1[mb], acc[0][mb]);
+            mma16<DT>(y1, a1[mb], acc[1][mb]);
           }
         }
         if (++blk == nslots && it + 1 < iters) {
