@@ -108,6 +108,42 @@ def test_misaligned_and_strided_operands():
     run_all_modes(convs, seed=11, label="misaligned conv", a_off=4, b_off=4, c_off=4)
 
 
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_random_mixes_under_random_plan_parameters(seed):
+    """Seeded random operator lists under random plan parameters (small tile targets force split reductions in
+    every class, including the LDS tiles; tiny group caps force many passes): outputs against the oracle."""
+    rng = np.random.default_rng(500 + seed)
+    dts = ["bf16", "f16", "f32"]
+    specs = []
+    for _ in range(14):
+        dt = dts[int(rng.integers(0, 3))]
+        d = float(rng.choice([np.inf, 0.5, 0.5, 2.0]))
+        if rng.random() < 0.6:
+            m = int(rng.choice([1, 7, 16, 17, 33, 64, 65, 130, 260]))
+            n = int(rng.choice([5, 33, 128, 129, 500, 1024]))
+            k = int(rng.choice([8, 64, 72, 256, 1000, 2048, 4096]))
+            specs.append(g(m, n, k, dt, d=d))
+        else:
+            hw = int(rng.choice([4, 7, 9, 14, 20]))
+            r = int(rng.choice([1, 3]))
+            specs.append(c(hw, hw, int(rng.choice([8, 16, 64, 128, 256])), int(rng.choice([8, 40, 128, 136])),
+                           r, r, r // 2, r // 2, dt, nb=int(rng.integers(1, 3)), d=d))
+    tmin = int(rng.choice([4096, 32768, 1 << 17]))
+    prm = {"skinny_max_m": int(rng.choice([16, 32, 64])), "tile_bytes_min": tmin,
+           "tile_bytes_max": tmin * int(rng.choice([1, 4, 16])), "balance_div": int(rng.choice([16, 2048])),
+           "max_groups": int(rng.choice([4, 8, 256])), "tail_div": int(rng.choice([0, 8, 384])),
+           "grid_limit": int(rng.choice([0, 7, 100]))}
+    b = H.Batch(specs, seed=seed)
+    with b.plan(**prm) as plan:
+        ref = {k: v for k, v in prm.items() if k != "grid_limit"}
+        assert sk.sk_plan_get_tiles(plan) == P.plan(specs, P.Params(**ref))[0]
+        for launch in (sk.sk_launch, sk.sk_launch_sequential, sk.sk_launch):
+            b.reset_outputs()
+            launch(plan, H.stream_handle())
+            _sync()
+            H.check_against_oracle(b, f"random mix {seed} {prm}")
+
+
 def test_single_and_empty_plans():
     run_all_modes([g(1, 64, 64)], seed=3, label="single")
     with sk.sk_plan_create([], None) as plan:

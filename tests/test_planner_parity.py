@@ -93,6 +93,45 @@ def test_plan_bytes_match_reference_ragged_and_params(prm):
         P.check_coverage(RAGGED, table)
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_plan_bytes_match_reference_on_random_mixes(seed):
+    """Seeded random operator lists (odd sizes, all element types, tied / missing / non-finite deadlines) under
+    random plan parameters: the two planners must agree byte for byte, and the table must cover every output
+    exactly once."""
+    import numpy as np
+    rng = np.random.default_rng(1000 + seed)
+    dts = ["bf16", "f16", "f32"]
+    deadlines = [math.inf, 0.0, -1.0, float("nan"), 0.5, 0.5, 1.25, 3.0]
+    specs = []
+    for _ in range(int(rng.integers(1, 24))):
+        d = deadlines[int(rng.integers(0, len(deadlines)))]
+        dt = dts[int(rng.integers(0, 3))]
+        if rng.random() < 0.6:
+            m = int(rng.choice([1, 2, 7, 16, 17, 31, 32, 33, 63, 64, 65, 100, 129, 300]))
+            n = int(rng.choice([1, 5, 31, 32, 33, 127, 128, 129, 500, 1024, 4097]))
+            k = int(rng.choice([1, 3, 8, 63, 64, 65, 256, 1000, 1024, 4096, 9000]))
+            specs.append(_g(m, n, k, dt, d))
+        else:
+            h, w = int(rng.integers(1, 30)), int(rng.integers(1, 30))
+            r, sq = int(rng.choice([1, 3, 5])), int(rng.choice([1, 3]))
+            ph, pw = int(rng.integers(0, 3)), int(rng.integers(0, 2))
+            if h + 2 * ph - r + 1 < 1 or w + 2 * pw - sq + 1 < 1:
+                r, sq, ph, pw = 1, 1, 0, 0
+            cin, cout = int(rng.choice([1, 3, 8, 64, 200, 512])), int(rng.choice([1, 7, 64, 130, 256]))
+            specs.append(_c(h, w, cin, cout, r, sq, ph, pw, dt, nb=int(rng.integers(1, 3)), d=d))
+    tmin = int(rng.choice([1024, 4096, 32768, 1 << 18]))
+    prm = {"edf": int(rng.integers(0, 2)), "skinny_max_m": int(rng.choice([0, 8, 16, 32, 64])),
+           "tile_bytes_min": tmin, "tile_bytes_max": tmin * int(rng.choice([1, 2, 16, 64])),
+           "balance_div": int(rng.choice([1, 7, 64, 2048])), "max_groups": int(rng.choice([1, 3, 4, 64, 256])),
+           "tail_div": int(rng.choice([0, 1, 16, 384, 5000]))}
+    with host_plan(specs, **prm) as plan:
+        table, order, first, count = P.plan(specs, ref_params(**prm))
+        assert sk.sk_plan_get_tiles(plan) == table, prm
+        assert sk.sk_plan_get_order(plan) == order
+        assert sk.sk_plan_get_ranges(plan) == (first, count)
+        P.check_coverage(specs, table)
+
+
 def test_permuting_operators_permutes_the_plan_consistently():
     import dataclasses
     specs = workloads.config(4, seed=3)
