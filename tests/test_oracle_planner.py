@@ -170,7 +170,7 @@ def test_target_bytes_rule():
     assert P.target_tile_bytes(mid, prm) == 65536
 
 
-@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5, 6])
 def test_coverage_on_every_config(idx):
     probs = workloads.config(idx, seed=0)
     table, order, first, count = P.plan(probs)

@@ -166,12 +166,25 @@ def _cfg5(seed):
     return out
 
 
+def _cfg6(seed):
+    # LSTM-cell-shaped matrix-vector products at batch 1 (the second workload the paper's
+    # Section 5.3 evaluates): one operator = the four gates of one cell, [x_t ; h_{t-1}] (K = 2h)
+    # against the stacked gate weights (N = 4h), fp16.
+    g = _rng(seed, 6)
+    out = []
+    for _ in range(64):
+        h = int(g.choice([256, 512, 1024, 2048]))
+        out.append(_gemm("f16", 1, 4 * h, 2 * h, ("normal", 1.0), ("normal", 1.0 / math.sqrt(2 * h)), tag="lstm-matvec"))
+    return out
+
+
 _RECIPES = {
     "cfg1_fp32_gemm4": _cfg1,
     "cfg2_bf16_gemm16": _cfg2,
     "cfg3_resnet_conv8": _cfg3,
     "cfg4_bert_linear32": _cfg4,
     "cfg5_mixed256_edf": _cfg5,
+    "cfg6_lstm_matvec64": _cfg6,
 }
 
 
@@ -180,7 +193,7 @@ def config_names() -> List[str]:
 
 
 def config(name_or_index, seed: int = 0, dtype: str | None = None) -> List[Problem]:
-    """Problem list for one of the five mixes (by name or 1-based index)."""
+    """Problem list for one of the mixes (by name or 1-based index)."""
     if isinstance(name_or_index, int):
         name = config_names()[name_or_index - 1]
     else:
