@@ -101,7 +101,7 @@ typedef struct {
   int64_t tile_bytes_max; /* skinny tiles: upper/lower clamp of the target weight bytes per  */
   int64_t tile_bytes_min; /* tile (defaults 2 MiB, 32 KiB); the target is                    */
                           /* sum(weight bytes) / balance_div                                 */
-  int32_t balance_div;    /* default 2048                                                    */
+  int32_t balance_div;    /* default 512                                                     */
   int32_t max_groups;     /* cap on 32-row weight groups per skinny tile, default 256        */
   int32_t grid_limit;     /* upper bound on persistent workgroups per launch;                */
                           /* 0 = 2 per compute unit of the current device                    */

@@ -50,7 +50,7 @@ class Params:
     skinny_max_m: int = 64          # <= 64
     tile_bytes_max: int = 2048 * 1024
     tile_bytes_min: int = 32 * 1024
-    balance_div: int = 2048
+    balance_div: int = 512
     max_groups: int = 256
     tail_div: int = 384             # 0: tiles do not shrink towards the end of the table
 

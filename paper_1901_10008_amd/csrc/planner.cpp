@@ -348,7 +348,7 @@ extern "C" void sk_plan_params_default(sk_plan_params *p) {
   p->skinny_max_m = 64;
   p->tile_bytes_max = 2048 * 1024;
   p->tile_bytes_min = 32 * 1024;
-  p->balance_div = 2048;
+  p->balance_div = 512;
   p->max_groups = 256;
   p->grid_limit = 0;
   p->tail_div = 384;

@@ -144,6 +144,22 @@ def test_random_mixes_under_random_plan_parameters(seed):
             H.check_against_oracle(b, f"random mix {seed} {prm}")
 
 
+def test_tuner_sweeps_plan_parameters():
+    from paper_1901_10008_amd import tune
+    specs = workloads.config(2, seed=0)
+    b = H.Batch(specs, seed=0)
+    grid = {"tile_bytes_max": (256 << 10, 2 << 20), "tail_div": (0, 384)}
+    best, res = tune.tune(b.problems, grid, rounds=2, launches=2, stream=H.stream_handle())
+    assert len(res) == 4 and all(t > 0 and n > 0 for _, t, n in res)
+    assert res[0][0] == best and res[0][1] == min(t for _, t, _ in res)
+    assert set(best) == {"tile_bytes_max", "tail_div"}
+    # the tuner only times launches: outputs are whatever the last plan wrote, and still right
+    H.check_against_oracle(b, "after tuning")
+    rep = tune.cotenancy(b.problems, 0, (1 << 15, 1 << 18, 1 << 21), rounds=2, launches=2, stream=H.stream_handle())
+    assert len(rep["solo_us"]) == 3 and len(rep["mix_us"]) == 3
+    assert rep["solo_penalty_with_mix_best"] >= 1.0 and rep["mix_penalty_with_solo_best"] >= 1.0
+
+
 def test_single_and_empty_plans():
     run_all_modes([g(1, 64, 64)], seed=3, label="single")
     with sk.sk_plan_create([], None) as plan:

@@ -162,12 +162,14 @@ def test_target_bytes_rule():
     prm = P.Params()
     small = [gemm(1, 256, 256, "f32")]
     assert P.target_tile_bytes(small, prm) == prm.tile_bytes_min
-    big = [gemm(1, 8192, 8192)] * 8      # 8 x 128 MiB of weights / 2048 = 512 KiB
+    assert prm.balance_div == 512
+    big = [gemm(1, 8192, 8192)] * 2      # 2 x 128 MiB of weights / 512 = 512 KiB
     assert P.target_tile_bytes(big, prm) == 512 * 1024
-    huge = [gemm(1, 8192, 8192)] * 64    # 8 GiB / 2048 = 4 MiB -> clamped to 2 MiB
+    huge = [gemm(1, 8192, 8192)] * 16    # 2 GiB / 512 = 4 MiB -> clamped to 2 MiB
     assert P.target_tile_bytes(huge, prm) == prm.tile_bytes_max == 2048 * 1024
-    mid = [gemm(1, 4096, 4096)] * 4      # 128 MiB / 2048 = 64 KiB
+    mid = [gemm(1, 4096, 4096)]          # 32 MiB / 512 = 64 KiB
     assert P.target_tile_bytes(mid, prm) == 65536
+    assert P.target_tile_bytes(mid * 4, P.Params(balance_div=2048)) == 65536
 
 
 @pytest.mark.parametrize("idx", [1, 2, 3, 4, 5, 6])
