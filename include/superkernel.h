@@ -145,7 +145,20 @@ void sk_plan_params_default(sk_plan_params *params);
  */
 sk_status sk_plan_create(const sk_problem *problems, int32_t n, const sk_plan_params *params,
                          sk_plan **out);
-sk_status sk_plan_destroy(sk_plan *plan); /* NULL is accepted */
+/*
+ * Destroys the plan; NULL is accepted.  Waits first for the plan's launches
+ * (they may still be reading its tables): for the latest one if all went to
+ * one stream, for the whole device if they went to several streams or into a
+ * stream capture.  Other plans' launches keep running.  Then hands the device
+ * tables to a per-process pool from which later plans on the
+ * same device are served: a runtime that plans once per launch (Section 5's
+ * just-in-time coalescing) would otherwise pay a device allocation per launch.
+ * The pool keeps at most 32 blocks and 512 MiB; older blocks are freed.
+ */
+sk_status sk_plan_destroy(sk_plan *plan);
+
+/* Frees every pooled table block (all devices).  Plans that exist are not touched. */
+sk_status sk_release_cached_memory(void);
 
 /*
  * Run every operator of the plan in ONE kernel launch on `hip_stream`

@@ -24,6 +24,7 @@ from .binding import (  # noqa: F401
     sk_plan_get_stamps,
     sk_plan_grid,
     sk_plan_params_default,
+    sk_release_cached_memory,
     sk_strerror,
     sk_last_error,
     SK_F32, SK_BF16, SK_F16, SK_GEMM, SK_CONV2D_NHWC,

@@ -15,7 +15,7 @@ DTYPE_CODE = {"f32": SK_F32, "bf16": SK_BF16, "f16": SK_F16}
 EXPORTED_SYMBOLS = [
     "sk_plan_params_default", "sk_plan_create", "sk_plan_destroy", "sk_launch", "sk_launch_sequential",
     "sk_plan_num_tiles", "sk_plan_num_problems", "sk_plan_get_tiles", "sk_plan_get_order",
-    "sk_plan_get_ranges", "sk_plan_grid", "sk_plan_get_stamps", "sk_strerror", "sk_last_error",
+    "sk_plan_get_ranges", "sk_plan_grid", "sk_plan_get_stamps", "sk_release_cached_memory", "sk_strerror", "sk_last_error",
 ]
 
 
@@ -90,6 +90,8 @@ def lib():
     L.sk_plan_get_ranges.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
     L.sk_plan_get_stamps.restype = C.c_int
     L.sk_plan_get_stamps.argtypes = [vp, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_double)]
+    L.sk_release_cached_memory.restype = C.c_int
+    L.sk_release_cached_memory.argtypes = []
     L.sk_strerror.restype = C.c_char_p
     L.sk_strerror.argtypes = [C.c_int]
     L.sk_last_error.restype = C.c_char_p
@@ -168,7 +170,7 @@ class Plan:
 
 def sk_plan_create(problems: Sequence[sk_problem], params: PlanParams | None = None, keepalive=None) -> Plan:
     n = len(problems)
-    arr = (sk_problem * max(n, 1))(*problems)
+    arr = problems if isinstance(problems, C.Array) else (sk_problem * max(n, 1))(*problems)
     out = C.c_void_p()
     st = lib().sk_plan_create(arr if n else None, n, C.byref(params) if params is not None else None, C.byref(out))
     _check(st)
@@ -177,6 +179,10 @@ def sk_plan_create(problems: Sequence[sk_problem], params: PlanParams | None = N
 
 def sk_plan_destroy(plan: Plan) -> None:
     plan.close()
+
+
+def sk_release_cached_memory() -> None:
+    _check(lib().sk_release_cached_memory())
 
 
 def sk_launch(plan: Plan, stream: int = 0) -> None:

@@ -4,8 +4,10 @@
 
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
+#include <vector>
 
 #include "kernels.hip.h"
 #include "sk_internal.h"
@@ -27,6 +29,97 @@ sk_status hip_error(const char *what, hipError_t e) {
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// Table memory is recycled.  A runtime that coalesces whatever is ready (Section 5) creates and
+// destroys a plan per launch, and a hipMalloc of a size not seen before costs several hundred
+// microseconds, more than planning and uploading a small table together.  Freed tables go to a
+// bounded per-process list; a new table takes the smallest listed block of its device that
+// holds it without wasting more than half.
+class TablePool {
+ public:
+  // Block sizes: four steps per power of two, at least 64 KiB.
+  static size_t block_size(size_t need) {
+    size_t p = 64 * 1024;
+    while (p < need) p <<= 1;
+    if (p == 64 * 1024) return p;
+    const size_t q = p / 8;  // p/2 < need <= p: steps of p/8 above p/2
+    return align_up(need, q);
+  }
+  hipError_t acquire(int device, size_t need, void **ptr, size_t *cap) {
+    {
+      std::lock_guard<std::mutex> g(mu_);
+      int best = -1;
+      for (size_t i = 0; i < free_.size(); ++i)
+        if (free_[i].device == device && free_[i].cap >= need && free_[i].cap / 2 <= need &&
+            (best < 0 || free_[i].cap < free_[(size_t)best].cap))
+          best = (int)i;
+      if (best >= 0) {
+        *ptr = free_[(size_t)best].ptr;
+        *cap = free_[(size_t)best].cap;
+        held_ -= *cap;
+        free_.erase(free_.begin() + best);
+        return hipSuccess;
+      }
+    }
+    *cap = block_size(need);
+    return hipMalloc(ptr, *cap);
+  }
+  // The caller has made sure no kernel still uses the block.
+  hipError_t release(int device, void *ptr, size_t cap) {
+    std::vector<Entry> drop;
+    {
+      std::lock_guard<std::mutex> g(mu_);
+      if (cap > MAX_HELD) {
+        drop.push_back({device, ptr, cap});
+      } else {
+        free_.push_back({device, ptr, cap});
+        held_ += cap;
+        while (held_ > MAX_HELD || free_.size() > MAX_BLOCKS) {  // oldest first
+          drop.push_back(free_.front());
+          held_ -= free_.front().cap;
+          free_.erase(free_.begin());
+        }
+      }
+    }
+    hipError_t st = hipSuccess;
+    for (const Entry &e : drop) {
+      hipError_t r = hipFree(e.ptr);
+      if (r != hipSuccess) st = r;
+    }
+    return st;
+  }
+  hipError_t trim() {
+    std::vector<Entry> drop;
+    {
+      std::lock_guard<std::mutex> g(mu_);
+      drop.swap(free_);
+      held_ = 0;
+    }
+    hipError_t st = hipSuccess;
+    for (const Entry &e : drop) {
+      hipError_t r = hipFree(e.ptr);
+      if (r != hipSuccess) st = r;
+    }
+    return st;
+  }
+
+ private:
+  struct Entry {
+    int device;
+    void *ptr;
+    size_t cap;
+  };
+  static constexpr size_t MAX_HELD = (size_t)512 << 20;
+  static constexpr size_t MAX_BLOCKS = 32;
+  std::mutex mu_;
+  std::vector<Entry> free_;
+  size_t held_ = 0;
+};
+
+TablePool &table_pool() {
+  static TablePool *pool = new TablePool();  // never destroyed: the runtime may already be gone at exit
+  return *pool;
+}
+
 }  // namespace
 
 // The device side of one tile table: one allocation holding
@@ -34,6 +127,7 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 //   completion stamps | split-K offsets | split-K arrival counters | split-K workspace
 struct DeviceTables {
   void *blob = nullptr;
+  size_t blob_bytes = 0;  // size of the pooled block behind `blob`
   sk::TileWork *work = nullptr;
   uint32_t *counters = nullptr;
   uint32_t *remaining = nullptr;
@@ -57,12 +151,17 @@ struct sk_plan {
   bool seq_ready = false;
   sk::HostPlan seq_host;
   DeviceTables seq_dev;
+  // what sk_plan_destroy has to wait for: an event behind the latest launch, as long as all
+  // launches went to one stream outside graph capture; otherwise the whole device
+  hipEvent_t last_use = nullptr;
+  hipStream_t last_stream = nullptr;
+  bool wait_for_device = false;
 };
 
 namespace {
 
-// Uploads the tables of `hp` to the current device.
-sk_status upload_tables(const sk::HostPlan &hp, DeviceTables &dt) {
+// Uploads the tables of `hp` to the current device (`device`).
+sk_status upload_tables(const sk::HostPlan &hp, int device, DeviceTables &dt) {
   const size_t nt = hp.tiles.size(), np = hp.dev.size(), nrect = hp.ws_off.size();
   const size_t off_work = 0;
   const size_t off_cnt = align_up(off_work + nt * sizeof(sk::TileWork), 256);
@@ -90,14 +189,14 @@ sk_status upload_tables(const sk::HostPlan &hp, DeviceTables &dt) {
     const uint32_t c = (uint32_t)hp.count[i];
     std::memcpy(&stage[off_rem + i * sizeof(uint32_t)], &c, sizeof(c));
   }
-  hipError_t e = hipMalloc(&dt.blob, total);
+  hipError_t e = table_pool().acquire(device, total, &dt.blob, &dt.blob_bytes);
   if (e != hipSuccess) {
     dt.blob = nullptr;
     return set_error(SK_ERR_ALLOC, std::string("hipMalloc: ") + hipGetErrorString(e));
   }
   e = hipMemcpy(dt.blob, stage.data(), upload, hipMemcpyHostToDevice);
   if (e != hipSuccess) {
-    (void)hipFree(dt.blob);
+    (void)table_pool().release(device, dt.blob, dt.blob_bytes);
     dt.blob = nullptr;
     return hip_error("hipMemcpy", e);
   }
@@ -156,7 +255,7 @@ sk_status sk_plan_create(const sk_problem *problems, int32_t n, const sk_plan_pa
     const int64_t ntiles = (int64_t)plan->host.tiles.size();
     plan->grid_cap = limit;
     plan->grid = (int)(ntiles < limit ? ntiles : limit);
-    st = upload_tables(plan->host, plan->dev);
+    st = upload_tables(plan->host, plan->device, plan->dev);
     if (st != SK_OK) {
       delete plan;
       return st;
@@ -170,14 +269,38 @@ sk_status sk_plan_create(const sk_problem *problems, int32_t n, const sk_plan_pa
 sk_status sk_plan_destroy(sk_plan *plan) {
   if (!plan) return SK_OK;
   sk_status st = SK_OK;
-  for (DeviceTables *dt : {&plan->dev, &plan->seq_dev}) {
-    if (dt->blob) {
-      hipError_t e = hipFree(dt->blob);
-      if (e != hipSuccess) st = hip_error("hipFree", e);
+  if (plan->dev.blob || plan->seq_dev.blob) {
+    // the tables go back to the pool, where the next plan may overwrite them at once:
+    // wait for every launch that may still read them
+    hipError_t e = hipSuccess;
+    int cur = -1;
+    if (plan->wait_for_device) {
+      e = hipGetDevice(&cur);
+      if (e == hipSuccess && cur != plan->device) e = hipSetDevice(plan->device);
+      if (e == hipSuccess) e = hipDeviceSynchronize();
+      if (cur >= 0 && cur != plan->device) (void)hipSetDevice(cur);
+    } else if (plan->last_use) {
+      e = hipEventSynchronize(plan->last_use);
+    }
+    if (e != hipSuccess) st = hip_error("waiting for the plan's launches", e);
+    for (DeviceTables *dt : {&plan->dev, &plan->seq_dev}) {
+      if (!dt->blob) continue;
+      // after a failed wait the block is neither reused nor freed under a running kernel
+      if (st == SK_OK) {
+        e = table_pool().release(plan->device, dt->blob, dt->blob_bytes);
+        if (e != hipSuccess) st = hip_error("hipFree", e);
+      }
     }
   }
+  if (plan->last_use) (void)hipEventDestroy(plan->last_use);
   delete plan;
   return st;
+}
+
+sk_status sk_release_cached_memory(void) {
+  hipError_t e = table_pool().trim();
+  if (e != hipSuccess) return hip_error("hipFree", e);
+  return SK_OK;
 }
 
 static sk_status launch_range(sk_plan *plan, const DeviceTables &dt, hipStream_t stream, uint32_t begin, uint32_t end,
@@ -215,6 +338,24 @@ static sk_status launch_range(sk_plan *plan, const DeviceTables &dt, hipStream_t
   return SK_OK;
 }
 
+// Remembers the launch that sk_plan_destroy must wait for.
+static void note_use(sk_plan *plan, hipStream_t stream) {
+  if (plan->wait_for_device) return;
+  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(stream, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone ||
+      (plan->last_use && stream != plan->last_stream)) {
+    plan->wait_for_device = true;  // replays of a graph or a second stream: not covered by one event
+    return;
+  }
+  if (!plan->last_use && hipEventCreateWithFlags(&plan->last_use, hipEventDisableTiming) != hipSuccess) {
+    plan->last_use = nullptr;
+    plan->wait_for_device = true;
+    return;
+  }
+  plan->last_stream = stream;
+  if (hipEventRecord(plan->last_use, stream) != hipSuccess) plan->wait_for_device = true;
+}
+
 static sk_status check_launchable(sk_plan *plan) {
   if (!plan) return set_error(SK_ERR_INVALID_ARG, "plan is null");
   if (!plan->resident) return set_error(SK_ERR_STATE, "plan was created host-only; it has no device tables");
@@ -228,8 +369,10 @@ static sk_status check_launchable(sk_plan *plan) {
 sk_status sk_launch(sk_plan *plan, void *hip_stream) {
   sk_status st = check_launchable(plan);
   if (st != SK_OK) return st;
-  return launch_range(plan, plan->dev, (hipStream_t)hip_stream, 0u, (uint32_t)plan->host.tiles.size(), plan->grid, true,
-                      true);
+  st = launch_range(plan, plan->dev, (hipStream_t)hip_stream, 0u, (uint32_t)plan->host.tiles.size(), plan->grid, true,
+                    true);
+  if (st == SK_OK && !plan->host.tiles.empty()) note_use(plan, (hipStream_t)hip_stream);
+  return st;
 }
 
 sk_status sk_launch_sequential(sk_plan *plan, void *hip_stream) {
@@ -243,7 +386,7 @@ sk_status sk_launch_sequential(sk_plan *plan, void *hip_stream) {
       return set_error(SK_ERR_ALLOC, "host allocation failed while planning");
     }
     if (st != SK_OK) return set_error(st, err);
-    st = upload_tables(plan->seq_host, plan->seq_dev);
+    st = upload_tables(plan->seq_host, plan->device, plan->seq_dev);
     if (st != SK_OK) return st;
     plan->seq_ready = true;
   }
@@ -253,8 +396,12 @@ sk_status sk_launch_sequential(sk_plan *plan, void *hip_stream) {
     const int grid = (int)(count < plan->grid_cap ? count : plan->grid_cap);
     st = launch_range(plan, plan->seq_dev, (hipStream_t)hip_stream, (uint32_t)first, (uint32_t)(first + count), grid,
                       false, i == 0);
-    if (st != SK_OK) return st;
+    if (st != SK_OK) {
+      plan->wait_for_device = true;  // some launches are out
+      return st;
+    }
   }
+  if (n) note_use(plan, (hipStream_t)hip_stream);
   return SK_OK;
 }
 
@@ -294,13 +441,18 @@ sk_status sk_plan_get_stamps(sk_plan *plan, uint64_t *done_ticks, uint64_t *star
   if (!plan->resident || !plan->host.params.stamps)
     return set_error(SK_ERR_STATE, "plan was not created with stamps enabled on a device");
   const size_t n = plan->host.dev.size();
-  if (done_ticks && n) {
-    hipError_t e = hipMemcpy(done_ticks, plan->dev.stamps, n * sizeof(uint64_t), hipMemcpyDeviceToHost);
+  if (done_ticks || start_tick) {
+    // one copy for both: the start stamp follows the n completion stamps
+    std::vector<uint64_t> host;
+    try {
+      host.resize(n + 1);
+    } catch (const std::bad_alloc &) {
+      return set_error(SK_ERR_ALLOC, "host allocation failed");
+    }
+    hipError_t e = hipMemcpy(host.data(), plan->dev.stamps, (n + 1) * sizeof(uint64_t), hipMemcpyDeviceToHost);
     if (e != hipSuccess) return hip_error("hipMemcpy", e);
-  }
-  if (start_tick) {
-    hipError_t e = hipMemcpy(start_tick, plan->dev.stamps + n, sizeof(uint64_t), hipMemcpyDeviceToHost);
-    if (e != hipSuccess) return hip_error("hipMemcpy", e);
+    if (done_ticks && n) std::memcpy(done_ticks, host.data(), n * sizeof(uint64_t));
+    if (start_tick) *start_tick = host[n];
   }
   if (ticks_per_ms) *ticks_per_ms = plan->ticks_per_ms;
   return SK_OK;

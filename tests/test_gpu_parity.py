@@ -160,6 +160,46 @@ def test_tuner_sweeps_plan_parameters():
     assert rep["solo_penalty_with_mix_best"] >= 1.0 and rep["mix_penalty_with_solo_best"] >= 1.0
 
 
+def test_arrival_trace_policies():
+    """Operators arriving over time under the three batching policies: every arrival is served, and whatever
+    the batching, the outputs are the oracle's."""
+    from paper_1901_10008_amd import serve
+    specs = workloads.config(2, seed=0)
+    b = H.Batch(specs, seed=0)
+    trace = serve.poisson_trace([workloads.algorithmic_bytes(s) for s in specs], 60, rate_per_ms=40.0, seed=1)
+    assert len(trace) == 60 and all(x.t_ms < y.t_ms for x, y in zip(trace, trace[1:]))
+    for policy, pipeline in (("sequential", True), ("coalesce", True), ("ooo", True), ("coalesce", False)):
+        b.reset_outputs()
+        rep = serve.run_trace(b.problems, trace, policy, pipeline=pipeline)
+        _sync()
+        assert rep["operators"] == 60 and 0.0 <= rep["met_fraction"] <= 1.0
+        assert rep["launches"] == 60 if policy == "sequential" else rep["launches"] <= 60
+        served = {a.index for a in trace}
+        H.check_against_oracle(b, "trace " + policy, only=served)
+
+
+def test_recycled_plan_tables():
+    """Destroyed plans hand their device tables to the next plan.  A recycled block holds the last plan's
+    queue counters, split-K arrival counts and partial sums; results must not depend on them.  A plan may
+    be destroyed while its launch still runs."""
+    big = workloads.config(2, seed=3)[:10] + workloads.config(3, seed=1)[:4]
+    small = workloads.config(2, seed=4)[:7]
+    bb, bs = H.Batch(big, seed=3), H.Batch(small, seed=4)
+    split = {"tile_bytes_min": 4096, "tile_bytes_max": 4096}  # many reduction slices: arrival counters in use
+    for rnd in range(3):
+        for b, prm in ((bb, split), (bs, split), (bb, {}), (bs, {"stamps": 1}), (bb, split)):
+            b.reset_outputs()
+            plan = b.plan(**prm)
+            sk.sk_launch(plan, H.stream_handle())
+            plan.close()           # no synchronisation by the caller
+            _sync()
+            H.check_against_oracle(b, f"recycled round {rnd} {prm}")
+        if rnd == 1:
+            sk.sk_release_cached_memory()
+    sk.sk_release_cached_memory()
+    sk.sk_release_cached_memory()  # empty pool
+
+
 def test_single_and_empty_plans():
     run_all_modes([g(1, 64, 64)], seed=3, label="single")
     with sk.sk_plan_create([], None) as plan:
