@@ -145,8 +145,11 @@ def run_trace(pool_problems, trace: Sequence[Arrival], policy: str, cap_ms: floa
                     used.append(free[a.index].pop())
                     total += a.bytes
             if batch:
-                chosen = {id(a) for a in batch}
-                pending = [a for a in pending if id(a) not in chosen]
+                if policy == "sequential":
+                    pending.pop(0)
+                else:
+                    chosen = {id(a) for a in batch}
+                    pending = [a for a in pending if id(a) not in chosen]
                 ev = torch.cuda.Event()
                 if policy == "sequential":
                     sk.sk_launch(solo[batch[0].index], stream)
@@ -174,9 +177,9 @@ def run_trace(pool_problems, trace: Sequence[Arrival], policy: str, cap_ms: floa
             continue
         if not inflight and not pending and nxt < len(trace):
             time.sleep(max(0.0, (trace[nxt].t_ms - now()) * 1e-3))
+    span = now()
     for pl in solo.values():
         pl.close()
-    span = now()
     latencies.sort()
     n = len(latencies)
     return {"policy": policy, "operators": n, "launches": launches, "met_fraction": round(met / n, 4),
