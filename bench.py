@@ -29,12 +29,19 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=5, help="1..6 (default 5: 256 mixed operators, EDF)")
+    ap.add_argument("--config", type=int, default=5, help="1..7 (default 5: 256 mixed operators, EDF)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-baselines", action="store_true", help="skip sequential / multi-stream legs")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--param", action="append", default=[], help="sk_plan_params override name=value")
+    ap.add_argument("--copies", type=int, default=1,
+                    help="independent copies of all buffers, one plan each, launched in rotation (cold-cache timing of "
+                         "workloads that fit the 256 MB last-level cache)")
+    ap.add_argument("--cold", action="store_true", help="--copies = enough for 512 MB of operands (at most 256)")
+    ap.add_argument("--replicate", type=int, default=1,
+                    help="put this many independent copies of the workload into ONE plan (steady-state rate of a "
+                         "workload too small to outlast a launch)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy, so that a rocprofv3 --pmc run of this command "
                          "shows what FETCH_SIZE / WRITE_SIZE read for a kernel of known traffic")
@@ -58,20 +65,32 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
-    specs = workloads.config(args.config, seed=args.seed)
+    base_specs = workloads.config(args.config, seed=args.seed)
+    specs = base_specs * max(1, args.replicate)
     name = workloads.config_names()[args.config - 1]
     tdt = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}
-    A, B, Cs, problems = [], [], [], []
-    for i, s in enumerate(specs):
-        a32, b32 = workloads.draw_device(s, args.seed, i, dev)
-        a = a32.to(tdt[s.dtype]).contiguous()
-        b = b32.to(tdt[s.dtype]).contiguous()
-        del a32, b32
-        c = torch.empty(s.c_shape, dtype=tdt[s.dtype], device=dev)
-        A.append(a)
-        B.append(b)
-        Cs.append(c)
-        problems.append(sk.make_problem(s, a.data_ptr(), b.data_ptr(), c.data_ptr()))
+    copies = max(1, args.copies)
+    if args.cold:
+        copies = max(copies, min(256, -(-(512 << 20) // sum(workloads.algorithmic_bytes(s) for s in specs))))
+    keep, all_problems = [], []
+    drawn = {}
+    for c in range(copies):
+        probs = []
+        for i, s in enumerate(specs):
+            j = i % len(base_specs)
+            if j not in drawn:
+                a32, b32 = workloads.draw_device(s, args.seed, j, dev)
+                drawn[j] = (a32.to(tdt[s.dtype]).contiguous(), b32.to(tdt[s.dtype]).contiguous())
+                del a32, b32
+            a, b = drawn[j]
+            if c or i >= len(base_specs):  # every copy has operands of its own
+                a, b = a.clone(), b.clone()
+            cbuf = torch.empty(s.c_shape, dtype=tdt[s.dtype], device=dev)
+            keep += [a, b, cbuf]
+            probs.append(sk.make_problem(s, a.data_ptr(), b.data_ptr(), cbuf.data_ptr()))
+        all_problems.append(probs)
+    del drawn
+    problems = all_problems[0]
     torch.cuda.synchronize()
 
     overrides = {}
@@ -105,8 +124,14 @@ def main():
     plan_first_ms = plan_times[0]
     plan_ms = sorted(plan_times[1:])[len(plan_times[1:]) // 2]
 
-    plan = sk.sk_plan_create(problems, sk.sk_plan_params_default(**overrides))
+    plans = [sk.sk_plan_create(pr, sk.sk_plan_params_default(**overrides)) for pr in all_problems]
+    plan = plans[0]
     ntiles = sk.sk_plan_num_tiles(plan)
+    turn = [0]
+
+    def next_plan():
+        turn[0] += 1
+        return plans[turn[0] % copies]
 
     def timed(fn, steps, warmup):
         for _ in range(warmup):
@@ -123,7 +148,7 @@ def main():
         dev_ms = [e0.elapsed_time(e1) for e0, e1 in evs]
         return wall * 1e3, dev_ms
 
-    wall_ms, dev_ms = timed(lambda: sk.sk_launch(plan, stream), args.steps, args.warmup)
+    wall_ms, dev_ms = timed(lambda: sk.sk_launch(next_plan(), stream), args.steps, args.warmup)
     kern_ms = sum(dev_ms) / len(dev_ms)
     value = flops / (wall_ms * 1e-3) / 1e12
 
@@ -141,7 +166,8 @@ def main():
         "dtype": specs[0].dtype if len({s.dtype for s in specs}) == 1 else "mixed",
         "data": "synthetic",
         "config": {"workload": name, "operators": len(specs), "tiles": ntiles, "grid": sk.sk_plan_grid(plan),
-                   "seed": args.seed, "gflop": round(flops / 1e9, 3), "algorithmic_MB": round(abytes / 1e6, 2),
+                   "seed": args.seed, "copies_in_rotation": copies, "copies_in_one_plan": max(1, args.replicate),
+                   "gflop": round(flops / 1e9, 3), "algorithmic_MB": round(abytes / 1e6, 2),
                    "params": overrides},
         "kernel_ms": {"mean": round(kern_ms, 5), "min": round(min(dev_ms), 5),
                       "median": round(sorted(dev_ms)[len(dev_ms) // 2], 5)},
@@ -158,7 +184,10 @@ def main():
 
     if not args.no_baselines:
         seq_steps = max(3, args.steps // 3)
-        seq_wall, seq_dev = timed(lambda: sk.sk_launch_sequential(plan, stream), seq_steps, 1)
+        for pl in plans:  # the first sequential launch of a plan builds its tables
+            sk.sk_launch_sequential(pl, stream)
+        torch.cuda.synchronize()
+        seq_wall, seq_dev = timed(lambda: sk.sk_launch_sequential(next_plan(), stream), seq_steps, 1)
         out["sequential"] = {"ms": round(seq_wall, 5), "tflops": round(flops / (seq_wall * 1e-3) / 1e12, 3),
                              "speedup": round(seq_wall / wall_ms, 3)}
 
@@ -208,7 +237,8 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(specs, args.seed, args.cpu_seconds)
 
-    plan.close()
+    for pl in plans:
+        pl.close()
     print(json.dumps(out))
 
 
@@ -265,7 +295,7 @@ def cpu_baseline(specs, seed, target_s):
         if s.op == "gemm":
             R.gemm(av, bv)
         else:
-            R.conv2d_nhwc(av, bv, s.pad_h, s.pad_w)
+            R.conv2d_nhwc(av, bv, s.pad_h, s.pad_w, stride=s.stride)
     dt = time.perf_counter() - t0
     return {"value": round(acc / dt / 1e12, 6), "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
             "sample": f"{len(chosen)} of {len(specs)} operators of the same mix in submission order "

@@ -63,10 +63,14 @@ typedef enum { SK_GEMM = 0, SK_CONV2D_NHWC = 1 } sk_op;
  *   lda, ldb, ldc are row strides in ELEMENTS; 0 means packed (K, K, N).
  *   The conv fields are ignored.
  *
- * SK_CONV2D_NHWC:  Y = conv(X, W), cross-correlation, stride 1, dilation 1, one
- *   group, zero padding, no bias:  A = X[Nb,H,Wd,Cin],  B = W[Cout,R,S,Cin],
- *   C = Y[Nb,Ho,Wo,Cout] with Ho = H + 2*pad_h - R + 1, Wo = Wd + 2*pad_w - S + 1,
- *   all dense.  M, N, K and the strides are ignored.  It is executed as the
+ * SK_CONV2D_NHWC:  Y = conv(X, W), cross-correlation, dilation 1, one group,
+ *   zero padding, no bias:  A = X[Nb,H,Wd,Cin],  B = W[Cout,R,S,Cin],
+ *   Y[b,ho,wo,co] = sum_{r,s,c} X[b, ho*stride-pad_h+r, wo*stride-pad_w+s, c] * W[co,r,s,c],
+ *   C = Y[Nb,Ho,Wo,Cout] with Ho = (H + 2*pad_h - R) / stride + 1 and
+ *   Wo = (Wd + 2*pad_w - S) / stride + 1 (integer division), all dense.
+ *   stride applies to both directions; 0 means 1 (the residual networks the
+ *   paper serves in Section 5.3 have layers of stride 1 and 2).
+ *   M, N, K and the row strides are ignored.  It is executed as the
  *   GEMM with rows (b*Ho+ho)*Wo+wo, columns co and reduction index
  *   (r*S+s)*Cin+c, without materialising the patch matrix.
  *
@@ -80,7 +84,7 @@ typedef struct {
   int32_t M, N, K;
   int64_t lda, ldb, ldc;
   int32_t Nb, H, Wd, Cin, Cout, R, S, pad_h, pad_w;
-  int32_t reserved;
+  int32_t stride;
   const void *A; /* device, read only */
   const void *B; /* device, read only */
   void *C;       /* device, written   */

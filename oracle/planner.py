@@ -59,8 +59,9 @@ def canonical(p):
     """(Mg, Ng, Kg) of an operator description with .op/.M/.N/.K or conv fields."""
     if p.op == "gemm":
         return p.M, p.N, p.K
-    ho = p.H + 2 * p.pad_h - p.R + 1
-    wo = p.W + 2 * p.pad_w - p.S + 1
+    st = getattr(p, "stride", 1) or 1
+    ho = (p.H + 2 * p.pad_h - p.R) // st + 1
+    wo = (p.W + 2 * p.pad_w - p.S) // st + 1
     return p.Nb * ho * wo, p.Cout, p.R * p.S * p.Cin
 
 

@@ -11,7 +11,7 @@ Conventions (the paper fixes none of them; these are this build's reading):
   * GEMM  C[m,n] = sum_k A[m,k] * B[n,k]; the weight operand is stored
     K-contiguous as [N,K]; alpha = 1, beta = 0.
   * Convolution is cross-correlation over NHWC activations and [Cout,R,S,Cin]
-    filters, stride 1, dilation 1, one group, zero padding, no bias.
+    filters, one stride for both directions, dilation 1, one group, zero padding, no bias.
   * The GEMM that backs a convolution has rows m = (b*Ho + ho)*Wo + wo,
     columns n = co and reduction index k = (r*S + s)*Cin + c.
 """
@@ -37,7 +37,7 @@ def _load():
             ctypes.c_void_p, ctypes.c_long, ctypes.c_void_p, ctypes.c_long,
             ctypes.c_void_p, ctypes.c_long, ctypes.c_void_p]
         lib.sk_oracle_conv2d_nhwc.restype = None
-        lib.sk_oracle_conv2d_nhwc.argtypes = [ctypes.c_int] * 9 + [ctypes.c_void_p] * 4
+        lib.sk_oracle_conv2d_nhwc.argtypes = [ctypes.c_int] * 10 + [ctypes.c_void_p] * 4
         _lib = lib
     return _lib
 
@@ -70,19 +70,19 @@ def gemm(A, B, want_mag: bool = False):
     return (C, S) if want_mag else C
 
 
-def conv2d_nhwc(X, W, pad_h: int, pad_w: int, want_mag: bool = False):
-    """X [Nb,H,W,Cin], W [Cout,R,S,Cin] -> Y fp64 [Nb,Ho,Wo,Cout]."""
+def conv2d_nhwc(X, W, pad_h: int, pad_w: int, want_mag: bool = False, stride: int = 1):
+    """X [Nb,H,W,Cin], W [Cout,R,S,Cin] -> Y fp64 [Nb,Ho,Wo,Cout]; filter positions `stride` apart."""
     X = _f32(X)
     W = _f32(W)
     Nb, H, Wd, Cin = X.shape
     Cout, R, S, Cin2 = W.shape
     assert Cin == Cin2
-    Ho = H + 2 * pad_h - R + 1
-    Wo = Wd + 2 * pad_w - S + 1
-    assert Ho >= 1 and Wo >= 1
+    assert stride >= 1 and H + 2 * pad_h >= R and Wd + 2 * pad_w >= S
+    Ho = (H + 2 * pad_h - R) // stride + 1
+    Wo = (Wd + 2 * pad_w - S) // stride + 1
     Y = np.empty((Nb, Ho, Wo, Cout), dtype=np.float64)
     Sm = np.empty_like(Y) if want_mag else None
-    _load().sk_oracle_conv2d_nhwc(Nb, H, Wd, Cin, Cout, R, S, pad_h, pad_w,
+    _load().sk_oracle_conv2d_nhwc(Nb, H, Wd, Cin, Cout, R, S, pad_h, pad_w, stride,
                                   X.ctypes.data, W.ctypes.data, Y.ctypes.data,
                                   Sm.ctypes.data if want_mag else None)
     return (Y, Sm) if want_mag else Y
@@ -103,13 +103,13 @@ def gemm_py(A, B):
     return np.array(C, dtype=np.float64)
 
 
-def conv2d_nhwc_py(X, W, pad_h, pad_w):
+def conv2d_nhwc_py(X, W, pad_h, pad_w, stride=1):
     X = np.asarray(X, dtype=np.float64)
     W = np.asarray(W, dtype=np.float64)
     Nb, H, Wd, Cin = X.shape
     Cout, R, S, _ = W.shape
-    Ho = H + 2 * pad_h - R + 1
-    Wo = Wd + 2 * pad_w - S + 1
+    Ho = (H + 2 * pad_h - R) // stride + 1
+    Wo = (Wd + 2 * pad_w - S) // stride + 1
     Y = np.zeros((Nb, Ho, Wo, Cout), dtype=np.float64)
     for b in range(Nb):
         for ho in range(Ho):
@@ -118,8 +118,8 @@ def conv2d_nhwc_py(X, W, pad_h, pad_w):
                     s = 0.0
                     for r in range(R):
                         for t in range(S):
-                            h = ho - pad_h + r
-                            w = wo - pad_w + t
+                            h = ho * stride - pad_h + r
+                            w = wo * stride - pad_w + t
                             if 0 <= h < H and 0 <= w < Wd:
                                 for c in range(Cin):
                                     s += X[b, h, w, c] * W[co, r, t, c]
@@ -141,7 +141,7 @@ def gemm_at(A_row, B_row):
     return s, mag
 
 
-def conv2d_at(X, W_co, b, ho, wo, pad_h, pad_w):
+def conv2d_at(X, W_co, b, ho, wo, pad_h, pad_w, stride=1):
     """One output element Y[b,ho,wo,co] from the full X and filter W[co] ([R,S,Cin])."""
     X = np.asarray(X)
     W_co = np.asarray(W_co)
@@ -150,11 +150,11 @@ def conv2d_at(X, W_co, b, ho, wo, pad_h, pad_w):
     s = 0.0
     mag = 0.0
     for r in range(R):
-        h = ho - pad_h + r
+        h = ho * stride - pad_h + r
         if h < 0 or h >= H:
             continue
         for t in range(S):
-            w = wo - pad_w + t
+            w = wo * stride - pad_w + t
             if w < 0 or w >= Wd:
                 continue
             x = X[b, h, w, :].astype(np.float64)
@@ -165,15 +165,15 @@ def conv2d_at(X, W_co, b, ho, wo, pad_h, pad_w):
     return s, mag
 
 
-def patch_matrix(X, R, S, pad_h, pad_w):
+def patch_matrix(X, R, S, pad_h, pad_w, stride=1):
     """Explicit patch (im2col) matrix [Nb*Ho*Wo, R*S*Cin] with k = (r*S+s)*Cin + c.
 
     Only used to pin the direct convolution against patch-matrix x GEMM.
     """
     X = np.asarray(X)
     Nb, H, Wd, Cin = X.shape
-    Ho = H + 2 * pad_h - R + 1
-    Wo = Wd + 2 * pad_w - S + 1
+    Ho = (H + 2 * pad_h - R) // stride + 1
+    Wo = (Wd + 2 * pad_w - S) // stride + 1
     P = np.zeros((Nb * Ho * Wo, R * S * Cin), dtype=X.dtype)
     for b in range(Nb):
         for ho in range(Ho):
@@ -181,8 +181,8 @@ def patch_matrix(X, R, S, pad_h, pad_w):
                 m = (b * Ho + ho) * Wo + wo
                 for r in range(R):
                     for t in range(S):
-                        h = ho - pad_h + r
-                        w = wo - pad_w + t
+                        h = ho * stride - pad_h + r
+                        w = wo * stride - pad_w + t
                         if 0 <= h < H and 0 <= w < Wd:
                             k0 = (r * S + t) * Cin
                             P[m, k0:k0 + Cin] = X[b, h, w, :]

@@ -52,19 +52,20 @@ void sk_oracle_gemm(int M, int N, int K,
 }
 
 /* Direct NHWC convolution (cross-correlation: the filter is NOT flipped),
- * stride 1, dilation 1, one group, zero padding:
- *   Y[b,ho,wo,co] = sum_{r,s,c} X[b, ho-pad_h+r, wo-pad_w+s, c] * W[co,r,s,c]
+ * the same stride in both directions, dilation 1, one group, zero padding:
+ *   Y[b,ho,wo,co] = sum_{r,s,c} X[b, ho*stride-pad_h+r, wo*stride-pad_w+s, c] * W[co,r,s,c]
  * where taps that fall outside the image contribute nothing.
- *   Ho = H + 2*pad_h - R + 1,  Wo = W + 2*pad_w - S + 1.
+ *   Ho = (H + 2*pad_h - R) / stride + 1,  Wo = (W + 2*pad_w - S) / stride + 1
+ * (integer division: the filter positions that fit the padded image).
  * X is [Nb,H,W,Cin], W is [Cout,R,S,Cin], Y (and Sabs, if non-NULL) are
  * [Nb,Ho,Wo,Cout], all dense. */
 void sk_oracle_conv2d_nhwc(int Nb, int H, int W, int Cin, int Cout,
-                           int R, int S, int pad_h, int pad_w,
+                           int R, int S, int pad_h, int pad_w, int stride,
                            const float *X, const float *Wt,
                            double *Y, double *Sabs)
 {
-    const int Ho = H + 2 * pad_h - R + 1;
-    const int Wo = W + 2 * pad_w - S + 1;
+    const int Ho = (H + 2 * pad_h - R) / stride + 1;
+    const int Wo = (W + 2 * pad_w - S) / stride + 1;
 #pragma omp parallel for collapse(2) schedule(dynamic, 1)
     for (int b = 0; b < Nb; ++b) {
         for (int ho = 0; ho < Ho; ++ho) {
@@ -72,10 +73,10 @@ void sk_oracle_conv2d_nhwc(int Nb, int H, int W, int Cin, int Cout,
                 for (int co = 0; co < Cout; ++co) {
                     double sum = 0.0, mag = 0.0;
                     for (int r = 0; r < R; ++r) {
-                        const int h = ho - pad_h + r;
+                        const int h = ho * stride - pad_h + r;
                         if (h < 0 || h >= H) continue;
                         for (int s = 0; s < S; ++s) {
-                            const int w = wo - pad_w + s;
+                            const int w = wo * stride - pad_w + s;
                             if (w < 0 || w >= W) continue;
                             const float *x = X + (((size_t)b * H + h) * W + w) * Cin;
                             const float *f = Wt + (((size_t)co * R + r) * S + s) * Cin;

@@ -33,7 +33,7 @@ class sk_problem(C.Structure):
         ("lda", C.c_int64), ("ldb", C.c_int64), ("ldc", C.c_int64),
         ("Nb", C.c_int32), ("H", C.c_int32), ("Wd", C.c_int32), ("Cin", C.c_int32), ("Cout", C.c_int32),
         ("R", C.c_int32), ("S", C.c_int32), ("pad_h", C.c_int32), ("pad_w", C.c_int32),
-        ("reserved", C.c_int32),
+        ("stride", C.c_int32),
         ("A", C.c_void_p), ("B", C.c_void_p), ("C", C.c_void_p),
         ("deadline_ms", C.c_double),
     ]
@@ -135,6 +135,7 @@ def make_problem(spec, A: int, B: int, Cptr: int, lda: int = 0, ldb: int = 0, ld
         p.op = SK_CONV2D_NHWC
         p.Nb, p.H, p.Wd, p.Cin, p.Cout = spec.Nb, spec.H, spec.W, spec.Cin, spec.Cout
         p.R, p.S, p.pad_h, p.pad_w = spec.R, spec.S, spec.pad_h, spec.pad_w
+        p.stride = getattr(spec, "stride", 1)
     else:
         raise ValueError(spec.op)
     p.A, p.B, p.C = A, B, Cptr

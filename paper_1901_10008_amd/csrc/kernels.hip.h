@@ -207,8 +207,8 @@ __device__ __forceinline__ u32x4 fetch_B(const DevProblem &P, int64_t row_off, i
 
 // Where row m of the activation operand starts.
 struct RowA {
-  int64_t base;  // plain: m*lda.  gather: offset of pixel (b, ho-pad_h, wo-pad_w, 0); may be negative
-  int hb, wb;    // gather: ho-pad_h, wo-pad_w
+  int64_t base;  // plain: m*lda.  gather: offset of pixel (b, hb, wb, 0), the one under filter tap (0,0); may be negative
+  int hb, wb;    // gather: ho*stride-pad_h, wo*stride-pad_w
 };
 
 __device__ __forceinline__ RowA row_of(const DevProblem &P, int m) {
@@ -223,8 +223,8 @@ __device__ __forceinline__ RowA row_of(const DevProblem &P, int m) {
     const int rem = m - b * hw;
     const int ho = rem / P.Wo;
     const int wo = rem - ho * P.Wo;
-    r.hb = ho - P.pad_h;
-    r.wb = wo - P.pad_w;
+    r.hb = ho * P.stride - P.pad_h;
+    r.wb = wo * P.stride - P.pad_w;
     r.base = (((int64_t)b * P.H + r.hb) * P.W + r.wb) * P.Cin;
   }
   return r;
@@ -964,22 +964,27 @@ __device__ void run_generic(const DevProblem *P_mem, const sk_tile *T_mem) {
   const int m_len = T.m_len, n_len = T.n_len;
   // a split reduction is done whole by the record of its first slice; the others have nothing to do
   if (T.ks_idx != 0) return;
-  const int k_begin = 0, k_stop = P.Kg;
   for (int idx = threadIdx.x; idx < m_len * n_len; idx += WG_THREADS) {
     const int m = (int)T.m0 + idx / n_len;
     const int n = (int)T.n0 + idx % n_len;
     const RowA row = row_of(P, m);
     const int64_t wrow = (int64_t)n * P.ldb;
     float acc = 0.f;
-    for (int k = k_begin; k < k_stop; ++k) {
-      float a = 0.f;
-      if (!P.gather) {
-        a = load_elem<DT>(P.A, row.base + k);
-      } else {
-        int64_t off;
-        if (patch_offset(P, row, k, off)) a = load_elem<DT>(P.A, off);
+    if (!P.gather) {
+      for (int k = 0; k < P.Kg; ++k)
+        acc = __builtin_fmaf(load_elem<DT>(P.A, row.base + k), load_elem<DT>(P.B, wrow + k), acc);
+    } else {
+      // taps in the order of the reduction index; those in the padding contribute nothing
+      for (int r = 0; r < P.R; ++r) {
+        if ((unsigned)(row.hb + r) >= (unsigned)P.H) continue;
+        for (int t = 0; t < P.S; ++t) {
+          if ((unsigned)(row.wb + t) >= (unsigned)P.W) continue;
+          const int64_t xa = row.base + ((int64_t)r * P.W + t) * P.Cin;
+          const int64_t wb = wrow + (int64_t)(r * P.S + t) * P.Cin;
+          for (int c = 0; c < P.Cin; ++c)
+            acc = __builtin_fmaf(load_elem<DT>(P.A, xa + c), load_elem<DT>(P.B, wb + c), acc);
+        }
       }
-      acc = __builtin_fmaf(a, load_elem<DT>(P.B, wrow + k), acc);
     }
     char SK_GLOBAL *c = as_global_mut<char>(P.C) + ((int64_t)m * P.ldc + n) * Elem<DT>::ES;
     if constexpr (DT == SK_F32)

@@ -56,8 +56,15 @@ sk_status canonicalise(const sk_problem &p, int32_t i, Canon &c, std::string &er
       err = at(i) + "convolution dimensions must be >= 1 and padding >= 0";
       return SK_ERR_INVALID_ARG;
     }
-    const int64_t Ho = (int64_t)p.H + 2 * (int64_t)p.pad_h - p.R + 1;
-    const int64_t Wo = (int64_t)p.Wd + 2 * (int64_t)p.pad_w - p.S + 1;
+    if (p.stride < 0 || p.stride > 1 << 10) {
+      err = at(i) + "stride must be 0 (meaning 1) or 1..1024";
+      return SK_ERR_INVALID_ARG;
+    }
+    const int64_t st = p.stride ? p.stride : 1;
+    const int64_t span_h = (int64_t)p.H + 2 * (int64_t)p.pad_h - p.R;
+    const int64_t span_w = (int64_t)p.Wd + 2 * (int64_t)p.pad_w - p.S;
+    const int64_t Ho = span_h < 0 ? 0 : span_h / st + 1;
+    const int64_t Wo = span_w < 0 ? 0 : span_w / st + 1;
     if (Ho < 1 || Wo < 1) {
       err = at(i) + "filter larger than the padded image";
       return SK_ERR_INVALID_ARG;
@@ -148,8 +155,9 @@ sk_status plan_host(const sk_problem *problems, int32_t n, const sk_plan_params 
       d.S = p.S;
       d.pad_h = p.pad_h;
       d.pad_w = p.pad_w;
-      // a 1x1 filter without padding reads the image as a plain [pixels, Cin] matrix
-      d.gather = !(p.R == 1 && p.S == 1 && p.pad_h == 0 && p.pad_w == 0);
+      d.stride = p.stride ? p.stride : 1;
+      // a 1x1 filter without padding or stride reads the image as a plain [pixels, Cin] matrix
+      d.gather = !(p.R == 1 && p.S == 1 && p.pad_h == 0 && p.pad_w == 0 && d.stride == 1);
       d.lda = p.Cin;
     }
     int32_t flags = 0;

@@ -37,7 +37,7 @@ struct DevProblem {
   int32_t H, W, Cin, Ho, Wo, R, S, pad_h, pad_w;
   int32_t flags;
   int32_t tile_first, tile_count;
-  int32_t pad0;
+  int32_t stride;  // of a convolution, both directions (>= 1)
 };
 static_assert(sizeof(DevProblem) % 8 == 0, "DevProblem must stay 8-byte sized");
 

@@ -129,7 +129,7 @@ class Batch:
             if s.op == "gemm":
                 self._ref[i] = R.gemm(self.a_val[i], self.b_val[i], want_mag=True)
             else:
-                Y, S = R.conv2d_nhwc(self.a_val[i], self.b_val[i], s.pad_h, s.pad_w, want_mag=True)
+                Y, S = R.conv2d_nhwc(self.a_val[i], self.b_val[i], s.pad_h, s.pad_w, want_mag=True, stride=s.stride)
                 self._ref[i] = (Y.reshape(-1, s.Cout), S.reshape(-1, s.Cout))
         return self._ref[i]
 

@@ -57,7 +57,7 @@ def test_config5_full_size_sampled():
         else:
             X = b.dA[i].float().cpu().numpy()
             W = b.dB[i][torch.as_tensor(ns, device="cuda")].float().cpu().numpy()
-            Y, Sm = R.conv2d_nhwc(X, W, s.pad_h, s.pad_w, want_mag=True)
+            Y, Sm = R.conv2d_nhwc(X, W, s.pad_h, s.pad_w, want_mag=True, stride=s.stride)
             ref, mag = Y.reshape(rows, -1), Sm.reshape(rows, -1)
             got = out[:, torch.as_tensor(ns, device="cuda")]
             kg = s.R * s.S * s.Cin

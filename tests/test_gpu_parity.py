@@ -61,7 +61,7 @@ def run_all_modes(specs, seed=0, label="", **batch_kw):
     return worst
 
 
-@pytest.mark.parametrize("idx", [1, 2, 3, 4, 6])
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 6, 7])
 def test_config_matches_oracle(idx):
     specs = workloads.config(idx, seed=0)
     worst = run_all_modes(specs, seed=0, label=f"config {idx}")
@@ -79,9 +79,9 @@ def g(m, n, k, dtype="bf16", d=math.inf, a=("normal", 1.0), b=("normal", 0.05)):
     return Problem(op="gemm", dtype=dtype, M=m, N=n, K=k, deadline_ms=d, a_dist=a, b_dist=b)
 
 
-def c(h, w, cin, cout, r, s, ph, pw, dtype="bf16", nb=1, d=math.inf):
+def c(h, w, cin, cout, r, s, ph, pw, dtype="bf16", nb=1, d=math.inf, st=1):
     return Problem(op="conv", dtype=dtype, Nb=nb, H=h, W=w, Cin=cin, Cout=cout, R=r, S=s, pad_h=ph, pad_w=pw,
-                   deadline_ms=d, a_dist=("uniform", 0.0, 1.0), b_dist=("normal", 0.1))
+                   stride=st, deadline_ms=d, a_dist=("uniform", 0.0, 1.0), b_dist=("normal", 0.1))
 
 
 RAGGED = [
@@ -91,6 +91,9 @@ RAGGED = [
     c(5, 5, 3, 7, 3, 3, 1, 1), c(9, 9, 8, 130, 1, 1, 0, 0, d=0.25), c(13, 11, 16, 40, 3, 3, 1, 1, nb=2),
     c(6, 6, 4, 4, 3, 1, 0, 0, "f32"), c(4, 4, 8, 8, 1, 1, 1, 1), c(7, 7, 24, 20, 3, 3, 1, 1, "f16"),
     c(5, 4, 8, 16, 3, 3, 0, 0), c(3, 3, 16, 8, 3, 3, 2, 2), c(10, 10, 5, 6, 3, 3, 1, 1, "f32", nb=3),
+    # strides: skinny and LDS-tile classes, 1x1 and 3x3, extents that do not divide, the generic path
+    c(9, 8, 16, 40, 3, 3, 1, 1, st=2), c(8, 8, 32, 24, 1, 1, 0, 0, st=2, nb=2), c(30, 29, 8, 130, 3, 3, 1, 1, st=2),
+    c(28, 28, 64, 64, 1, 1, 0, 0, "f16", st=2), c(11, 11, 8, 8, 3, 3, 0, 0, "f32", st=3), c(9, 9, 5, 6, 3, 3, 1, 1, st=2),
 ]
 
 

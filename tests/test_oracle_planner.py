@@ -24,6 +24,16 @@ def test_canonical_view_of_conv_and_gemm():
     assert P.canonical(conv(7, 512, 512, 3)) == (49, 512, 4608)
     c = NS(op="conv", dtype="bf16", Nb=2, H=8, W=6, Cin=4, Cout=3, R=3, S=3, pad_h=0, pad_w=1, deadline_ms=0)
     assert P.canonical(c) == (2 * 6 * 6, 3, 36)
+    # stride: the residual networks' down-sampling layers (56x56 -> 28x28), and extents that do not divide
+    c = NS(op="conv", dtype="bf16", Nb=1, H=56, W=56, Cin=64, Cout=128, R=3, S=3, pad_h=1, pad_w=1, stride=2,
+           deadline_ms=0)
+    assert P.canonical(c) == (28 * 28, 128, 576)
+    c = NS(op="conv", dtype="bf16", Nb=1, H=56, W=56, Cin=256, Cout=512, R=1, S=1, pad_h=0, pad_w=0, stride=2,
+           deadline_ms=0)
+    assert P.canonical(c) == (28 * 28, 512, 256)
+    c = NS(op="conv", dtype="bf16", Nb=3, H=7, W=10, Cin=2, Cout=5, R=3, S=3, pad_h=0, pad_w=0, stride=3,
+           deadline_ms=0)
+    assert P.canonical(c) == (3 * 2 * 3, 5, 18)   # rows 0,3 and columns 0,3,6 fit
 
 
 def test_hand_enumerated_skinny_plan():
@@ -172,7 +182,7 @@ def test_target_bytes_rule():
     assert P.target_tile_bytes(mid * 4, P.Params(balance_div=2048)) == 65536
 
 
-@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5, 6, 7])
 def test_coverage_on_every_config(idx):
     probs = workloads.config(idx, seed=0)
     table, order, first, count = P.plan(probs)

@@ -43,6 +43,44 @@ def test_conv_hand_examples(hand):
         assert np.array_equal(R.conv2d_nhwc_py(X, W, case["pad"], case["pad"]), want)
 
 
+def test_strided_conv_hand_examples(hand):
+    for case in hand["conv_strided"]:
+        X = np.array(case["X_hw"], dtype=np.float32)[None, :, :, None]
+        W = np.array(case["W_rs"], dtype=np.float32)[None, :, :, None]
+        want = np.array(case["Y_hw"], dtype=np.float64)[None, :, :, None]
+        Y = R.conv2d_nhwc(X, W, case["pad"], case["pad"], stride=case["stride"])
+        assert Y.shape == want.shape and np.array_equal(Y, want), case["name"]
+        assert np.array_equal(R.conv2d_nhwc_py(X, W, case["pad"], case["pad"], case["stride"]), want)
+
+
+@pytest.mark.parametrize("cfg", [
+    dict(H=7, W=7, R=3, S=3, ph=1, pw=1, st=2), dict(H=6, W=9, R=3, S=3, ph=1, pw=1, st=2),
+    dict(H=6, W=6, R=3, S=3, ph=0, pw=0, st=2), dict(H=8, W=5, R=1, S=1, ph=0, pw=0, st=2),
+    dict(H=11, W=10, R=3, S=1, ph=1, pw=0, st=3), dict(H=9, W=9, R=5, S=3, ph=2, pw=1, st=4),
+])
+def test_strided_conv_is_the_unit_stride_result_at_every_stride_th_position(cfg):
+    """Y_s[ho, wo] = Y_1[s*ho, s*wo] (same terms, same order: exact), and the output extent is the number
+    of filter positions that fit; for a 1x1 filter this is plain subsampling of the image."""
+    g = np.random.default_rng(11)
+    X = g.standard_normal((2, cfg["H"], cfg["W"], 3)).astype(np.float32)
+    W = g.standard_normal((4, cfg["R"], cfg["S"], 3)).astype(np.float32)
+    st = cfg["st"]
+    Y1, S1 = R.conv2d_nhwc(X, W, cfg["ph"], cfg["pw"], want_mag=True)
+    Ys, Ss = R.conv2d_nhwc(X, W, cfg["ph"], cfg["pw"], want_mag=True, stride=st)
+    assert Ys.shape == Y1[:, ::st, ::st].shape
+    assert np.array_equal(Ys, Y1[:, ::st, ::st]) and np.array_equal(Ss, S1[:, ::st, ::st])
+    assert np.array_equal(R.conv2d_nhwc_py(X, W, cfg["ph"], cfg["pw"], st), Ys)
+    Pm = R.patch_matrix(X, cfg["R"], cfg["S"], cfg["ph"], cfg["pw"], st)
+    want = Pm.astype(np.float64) @ W.reshape(4, -1).astype(np.float64).T
+    assert np.max(np.abs(Ys.reshape(-1, 4) - want)) <= 1e-12 * max(1.0, np.max(np.abs(want)))
+    b, ho, wo = 1, Ys.shape[1] - 1, Ys.shape[2] - 1
+    s, mag = R.conv2d_at(X, W[2], b, ho, wo, cfg["ph"], cfg["pw"], st)
+    assert abs(s - Ys[b, ho, wo, 2]) <= 1e-12 * max(mag, 1e-30) and abs(mag - Ss[b, ho, wo, 2]) <= 1e-12 * max(mag, 1e-30)
+    if cfg["R"] == 1 and cfg["S"] == 1:
+        assert np.array_equal(Ys, np.einsum("bhwc,oc->bhwo", X[:, ::st, ::st].astype(np.float64),
+                                            W[:, 0, 0].astype(np.float64)))
+
+
 def test_conv1x1_hand_example(hand):
     c = hand["conv1x1"]
     X = np.array(c["X_nhwc"], dtype=np.float32)

@@ -26,8 +26,9 @@ def fake_problems(specs, misalign=None):
         if s.op == "gemm":
             na, nb, nc = s.M * s.K, s.N * s.K, s.M * s.N
         else:
-            ho = s.H + 2 * s.pad_h - s.R + 1
-            wo = s.W + 2 * s.pad_w - s.S + 1
+            st = getattr(s, "stride", 1)
+            ho = (s.H + 2 * s.pad_h - s.R) // st + 1
+            wo = (s.W + 2 * s.pad_w - s.S) // st + 1
             na, nb, nc = s.Nb * s.H * s.W * s.Cin, s.Cout * s.R * s.S * s.Cin, s.Nb * ho * wo * s.Cout
         ptrs = []
         for cnt in (na, nb, nc):
@@ -46,7 +47,7 @@ def ref_params(**kw):
     return P.Params(**kw)
 
 
-@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5, 6, 7])
 @pytest.mark.parametrize("seed", [0, 1])
 def test_plan_bytes_match_reference_on_configs(idx, seed):
     specs = workloads.config(idx, seed=seed)
@@ -64,15 +65,16 @@ def _g(m, n, k, dtype="bf16", d=math.inf):
     return NS(op="gemm", dtype=dtype, M=m, N=n, K=k, deadline_ms=d)
 
 
-def _c(h, w, cin, cout, r, s, ph, pw, dtype="bf16", nb=1, d=math.inf):
+def _c(h, w, cin, cout, r, s, ph, pw, dtype="bf16", nb=1, d=math.inf, st=1):
     return NS(op="conv", dtype=dtype, Nb=nb, H=h, W=w, Cin=cin, Cout=cout, R=r, S=s, pad_h=ph, pad_w=pw,
-              deadline_ms=d)
+              stride=st, deadline_ms=d)
 
 
 RAGGED = [_g(1, 5, 3, "f32"), _g(17, 33, 129), _g(33, 130, 70, "f16"), _g(65, 129, 8), _g(200, 300, 100, "f32"),
           _g(16, 9000, 64), _g(32, 40, 8192), _g(2, 8192, 8192, d=1.5), _g(7, 100, 2048, "f32", d=0.25),
           _c(5, 5, 3, 7, 3, 3, 1, 1), _c(9, 9, 8, 130, 1, 1, 0, 0, d=0.25), _c(13, 11, 16, 40, 3, 3, 1, 1, nb=2),
-          _c(6, 6, 4, 4, 3, 1, 0, 0, "f32"), _c(4, 4, 8, 8, 1, 1, 1, 1)]
+          _c(6, 6, 4, 4, 3, 1, 0, 0, "f32"), _c(4, 4, 8, 8, 1, 1, 1, 1),
+          _c(56, 56, 64, 128, 1, 1, 0, 0, st=2), _c(15, 14, 8, 24, 3, 3, 1, 1, st=2), _c(9, 9, 8, 8, 3, 3, 0, 0, "f32", st=3)]
 
 
 @pytest.mark.parametrize("prm", [
@@ -118,7 +120,8 @@ def test_plan_bytes_match_reference_on_random_mixes(seed):
             if h + 2 * ph - r + 1 < 1 or w + 2 * pw - sq + 1 < 1:
                 r, sq, ph, pw = 1, 1, 0, 0
             cin, cout = int(rng.choice([1, 3, 8, 64, 200, 512])), int(rng.choice([1, 7, 64, 130, 256]))
-            specs.append(_c(h, w, cin, cout, r, sq, ph, pw, dt, nb=int(rng.integers(1, 3)), d=d))
+            specs.append(_c(h, w, cin, cout, r, sq, ph, pw, dt, nb=int(rng.integers(1, 3)), d=d,
+                            st=int(rng.choice([1, 1, 2, 3]))))
     tmin = int(rng.choice([1024, 4096, 32768, 1 << 18]))
     prm = {"edf": int(rng.integers(0, 2)), "skinny_max_m": int(rng.choice([0, 8, 16, 32, 64])),
            "tile_bytes_min": tmin, "tile_bytes_max": tmin * int(rng.choice([1, 2, 16, 64])),
@@ -188,6 +191,14 @@ def test_validation_errors():
     _expect(-2, bad)
     # filter larger than the image
     _expect(-1, fake_problems([_c(2, 2, 4, 4, 3, 3, 0, 0)]))
+    # negative stride; stride 0 means 1
+    bad = fake_problems([_c(8, 8, 8, 8, 3, 3, 1, 1)])
+    bad[0].stride = -2
+    _expect(-1, bad)
+    zero = fake_problems([_c(8, 8, 8, 8, 3, 3, 1, 1)])
+    zero[0].stride = 0
+    with sk.sk_plan_create(zero, sk.sk_plan_params_default(host_only=1)) as plan:
+        assert sk.sk_plan_get_tiles(plan) == P.plan([_c(8, 8, 8, 8, 3, 3, 1, 1)])[0]
     # overlapping outputs (same C) -> overlap; sharing A and B is fine
     bad = fake_problems([_g(4, 64, 64), _g(4, 64, 64)])
     bad[1].C = bad[0].C + 64

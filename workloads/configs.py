@@ -28,7 +28,8 @@ class Problem:
 
     GEMM:  C[M,N] = A[M,K] . B^T  with B stored K-contiguous as [N,K].
     CONV:  Y[Nb,Ho,Wo,Cout] = X[Nb,H,W,Cin] (*) W[Cout,R,S,Cin], NHWC,
-           stride 1, dilation 1, zero padding (pad_h, pad_w), cross-correlation.
+           stride `stride` in both directions, dilation 1, zero padding (pad_h, pad_w),
+           cross-correlation.
     """
 
     op: str  # "gemm" | "conv"
@@ -45,6 +46,7 @@ class Problem:
     S: int = 0
     pad_h: int = 0
     pad_w: int = 0
+    stride: int = 1
     deadline_ms: float = math.inf
     a_dist: Tuple = ("normal", 1.0)
     b_dist: Tuple = ("normal", 1.0)
@@ -62,8 +64,8 @@ class Problem:
     def c_shape(self):
         if self.op == "gemm":
             return (self.M, self.N)
-        ho = self.H + 2 * self.pad_h - self.R + 1
-        wo = self.W + 2 * self.pad_w - self.S + 1
+        ho = (self.H + 2 * self.pad_h - self.R) // self.stride + 1
+        wo = (self.W + 2 * self.pad_w - self.S) // self.stride + 1
         return (self.Nb, ho, wo, self.Cout)
 
 
@@ -178,6 +180,20 @@ def _cfg6(seed):
     return out
 
 
+def _cfg7(seed):
+    # The down-sampling layers of a 50-layer residual network at batch 1 (the paper's Section 5.3
+    # serves ResNet-50): the stride-2 7x7 stem on a 224x224 RGB image, and at each of the three stage
+    # transitions the stride-2 3x3 convolution of the first block and its stride-2 1x1 projection.
+    def strided(hw, cin, cout, r, pad):
+        he_std = math.sqrt(2.0 / (r * r * cin))
+        return Problem(op="conv", dtype="bf16", Nb=1, H=hw, W=hw, Cin=cin, Cout=cout, R=r, S=r, pad_h=pad, pad_w=pad,
+                       stride=2, a_dist=("uniform", 0.0, 1.0), b_dist=("normal", he_std), tag="resnet50-stride2")
+    return [strided(224, 3, 64, 7, 3),
+            strided(56, 128, 128, 3, 1), strided(56, 256, 512, 1, 0),
+            strided(28, 256, 256, 3, 1), strided(28, 512, 1024, 1, 0),
+            strided(14, 512, 512, 3, 1), strided(14, 1024, 2048, 1, 0)]
+
+
 _RECIPES = {
     "cfg1_fp32_gemm4": _cfg1,
     "cfg2_bf16_gemm16": _cfg2,
@@ -185,6 +201,7 @@ _RECIPES = {
     "cfg4_bert_linear32": _cfg4,
     "cfg5_mixed256_edf": _cfg5,
     "cfg6_lstm_matvec64": _cfg6,
+    "cfg7_resnet_stride2_conv7": _cfg7,
 }
 
 
