@@ -22,6 +22,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "sk_internal.h"
 
 namespace sk {
@@ -994,15 +996,170 @@ __device__ void run_generic(const DevProblem *P_mem, const sk_tile *T_mem) {
   }
 }
 
+// ---------------------------------------------------------------------------
+// MFMA tiles for operands of any alignment (an image with 3 channels, an odd
+// reduction length, unaligned bases): the staging map and the LDS layout of
+// run_tile, but a 16-byte piece is put together from single elements, loaded one
+// by one, and a stage is loaded, stored to LDS and multiplied before the next
+// one is touched (the unpacked elements of one stage fill the registers that
+// the packed pieces of a ring of stages would).  Any output rectangle is
+// walked in blocks of 128 x 128; a split reduction is done whole by the record
+// of its first slice.  Not inlined, like run_generic.
+// ---------------------------------------------------------------------------
 template <int DT>
+__device__ __attribute__((noinline)) void run_tile_any(const DevProblem *P_mem, const sk_tile *T_mem,
+                                                       unsigned char *lds) {
+  constexpr int ES = Elem<DT>::ES;
+  constexpr int CE = 16 / ES;
+  constexpr int KB = 8 * CE;
+  using elem_t = typename std::conditional<ES == 4, uint32_t, uint16_t>::type;
+  const DevProblem P = *P_mem;
+  const sk_tile T = *T_mem;
+  if (T.ks_idx != 0) return;
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6, lane = tid & 63;
+  const int wm = wave & 1, wn = wave >> 1;
+  const int l32 = lane & 31, half = lane >> 5;
+  const int c8 = tid & 7, srow = tid >> 3;
+  const uintptr_t zeros = zero_piece_address();
+  const int m_end = (int)T.m0 + (int)T.m_len, n_end = (int)T.n0 + (int)T.n_len;
+  const bool vec_c = (P.flags & FLAG_VEC_C) != 0;
+  unsigned char *sa = lds + srow * LDS_ROW + c8 * 16;
+  unsigned char *sb = sa + 128 * LDS_ROW;
+
+  for (int mb = (int)T.m0; mb < m_end; mb += 128) {
+    RowA rows[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      int m = mb + srow + 32 * i;
+      if (m >= m_end) m = m_end - 1;  // rows past the edge repeat the last row; never stored
+      rows[i] = row_of(P, m);
+    }
+    for (int nb = (int)T.n0; nb < n_end; nb += 128) {
+      int64_t wrow[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        int n = nb + srow + 32 * i;
+        if (n >= n_end) n = n_end - 1;
+        wrow[i] = (int64_t)n * P.ldb;
+      }
+      f32x16 acc[2][2];
+#pragma unroll
+      for (int fn = 0; fn < 2; ++fn)
+#pragma unroll
+        for (int fm = 0; fm < 2; ++fm)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) acc[fn][fm][i] = 0.f;
+
+      for (int k0 = 0; k0 < P.Kg; k0 += KB) {
+        const int k = k0 + c8 * CE;  // first reduction index of this thread's pieces
+        // filter tap and channel of element k (convolutions); later elements by carrying
+        int g_r = 0, g_s = 0, g_c = 0;
+        if (P.gather) {
+          const int tap = k / P.Cin;
+          g_c = k - tap * P.Cin;
+          g_r = tap / P.S;
+          g_s = tap - g_r * P.S;
+        }
+        elem_t va[4][CE], vb[4][CE];
+#pragma unroll
+        for (int e = 0; e < CE; ++e) {
+          const bool in = k + e < P.Kg;
+          const int64_t rel = P.gather ? ((int64_t)g_r * P.W + g_s) * P.Cin + g_c : (int64_t)(k + e);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const bool ok = in && (!P.gather || ((unsigned)(rows[i].hb + g_r) < (unsigned)P.H &&
+                                                 (unsigned)(rows[i].wb + g_s) < (unsigned)P.W));
+            const uintptr_t pa = (uintptr_t)P.A + (uintptr_t)((rows[i].base + rel) * ES);
+            va[i][e] = *(const elem_t SK_GLOBAL *)(ok ? pa : zeros);
+            const uintptr_t pb = (uintptr_t)P.B + (uintptr_t)((wrow[i] + k + e) * ES);
+            vb[i][e] = *(const elem_t SK_GLOBAL *)(in ? pb : zeros);
+          }
+          if (++g_c == P.Cin) {
+            g_c = 0;
+            if (++g_s == P.S) {
+              g_s = 0;
+              ++g_r;
+            }
+          }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          u32x4 qa, qb;
+          if constexpr (ES == 4) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              qa[e] = va[i][e];
+              qb[e] = vb[i][e];
+            }
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              qa[e] = (uint32_t)va[i][2 * e] | ((uint32_t)va[i][2 * e + 1] << 16);
+              qb[e] = (uint32_t)vb[i][2 * e] | ((uint32_t)vb[i][2 * e + 1] << 16);
+            }
+          }
+          *(u32x4 *)(sa + 32 * i * LDS_ROW) = qa;
+          *(u32x4 *)(sb + 32 * i * LDS_ROW) = qb;
+        }
+        __syncthreads();
+        const unsigned char *la = lds;
+        const unsigned char *lb = lds + 128 * LDS_ROW;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          const int piece = (2 * kk + half) * 16;
+          u32x4 fa[2], fb[2];
+#pragma unroll
+          for (int f = 0; f < 2; ++f) {
+            fa[f] = *(const u32x4 *)(la + ((wm * 2 + f) * 32 + l32) * LDS_ROW + piece);
+            fb[f] = *(const u32x4 *)(lb + ((wn * 2 + f) * 32 + l32) * LDS_ROW + piece);
+          }
+#pragma unroll
+          for (int fn = 0; fn < 2; ++fn)
+#pragma unroll
+            for (int fm = 0; fm < 2; ++fm) mma32<DT>(fb[fn], fa[fm], acc[fn][fm]);
+        }
+        __syncthreads();  // everyone has read the stage before the next one overwrites it
+      }
+
+      // lane holds, per (fn, fm): row l32, columns 8*(i/4) + 4*half + (i%4)
+#pragma unroll
+      for (int fm = 0; fm < 2; ++fm) {
+        const int m = mb + (wm * 2 + fm) * 32 + l32;
+        if (m < m_end) {
+          const int64_t row_off = (int64_t)m * P.ldc;
+#pragma unroll
+          for (int fn = 0; fn < 2; ++fn) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              const int n = nb + (wn * 2 + fn) * 32 + 8 * j + 4 * half;
+              if (n < n_end) {
+                f32x4 v = {acc[fn][fm][4 * j], acc[fn][fm][4 * j + 1], acc[fn][fm][4 * j + 2], acc[fn][fm][4 * j + 3]};
+                store4<DT>(P.C, row_off, n, n_end, v, vec_c);
+              }
+            }
+          }
+        }
+      }
+    }
+  }
+}
+
+template <int DT, bool ANY_ALIGNMENT>
 __device__ __forceinline__ void run_class(const DevProblem &P, const sk_tile &T, const DevProblem *P_mem,
                                           const sk_tile *T_mem, const SplitK &sp, unsigned char *lds,
                                           uint32_t *s_flag, Prefetch &pf) {
   const int cls = T.cls;
-  if ((P.flags & (FLAG_VEC_A | FLAG_VEC_B)) != (FLAG_VEC_A | FLAG_VEC_B)) {
-    pf.claim();
-    pf.issue();
-    run_generic<DT>(P_mem, T_mem);
+  if (ANY_ALIGNMENT && (P.flags & (FLAG_VEC_A | FLAG_VEC_B)) != (FLAG_VEC_A | FLAG_VEC_B)) {
+    if constexpr (ANY_ALIGNMENT) {
+      pf.claim();
+      pf.issue();
+      // small rectangles one output per thread, larger ones through the matrix cores
+      if ((int)T.m_len * (int)T.n_len < 4096)
+        run_generic<DT>(P_mem, T_mem);
+      else
+        run_tile_any<DT>(P_mem, T_mem, lds);
+    }
   } else if (cls == 0) {
     run_skinny<DT, 1>(P, T, sp, lds, s_flag, pf);
   } else if (cls == 3) {
@@ -1016,7 +1173,10 @@ __device__ __forceinline__ void run_class(const DevProblem &P, const sk_tile &T,
 
 // ONLY_DT >= 0: every operator of the plan has that element type (one third of the
 // code, fewer registers); ONLY_DT < 0: operators of mixed types.
-template <int ONLY_DT>
+// ANY_ALIGNMENT false: every operator can be read in aligned 16-byte pieces, and the kernel
+// does not carry the paths for the others (their calls cost the fast paths registers and a
+// stack); true: operators of either kind.
+template <int ONLY_DT, bool ANY_ALIGNMENT>
 __global__ void __launch_bounds__(WG_THREADS, 2) sk_superkernel(const TileWork *__restrict__ work, KernelArgs a) {
   __shared__ __attribute__((aligned(16))) unsigned char lds[LDS_TILE_BYTES];
   __shared__ __attribute__((aligned(16))) uint32_t s_mail[2][WORK_DWORDS + 4];  // next record + its index, by parity
@@ -1042,12 +1202,12 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sk_superkernel(const TileWork *
     const sk_tile &T = W.tile;
     const DevProblem &P = W.prob;
     if constexpr (ONLY_DT >= 0) {
-      run_class<ONLY_DT>(P, T, &work[t].prob, &work[t].tile, sp, lds, &s_flag, pf);
+      run_class<ONLY_DT, ANY_ALIGNMENT>(P, T, &work[t].prob, &work[t].tile, sp, lds, &s_flag, pf);
     } else {
       switch (P.dtype) {
-        case SK_BF16: run_class<SK_BF16>(P, T, &work[t].prob, &work[t].tile, sp, lds, &s_flag, pf); break;
-        case SK_F16: run_class<SK_F16>(P, T, &work[t].prob, &work[t].tile, sp, lds, &s_flag, pf); break;
-        default: run_class<SK_F32>(P, T, &work[t].prob, &work[t].tile, sp, lds, &s_flag, pf); break;
+        case SK_BF16: run_class<SK_BF16, ANY_ALIGNMENT>(P, T, &work[t].prob, &work[t].tile, sp, lds, &s_flag, pf); break;
+        case SK_F16: run_class<SK_F16, ANY_ALIGNMENT>(P, T, &work[t].prob, &work[t].tile, sp, lds, &s_flag, pf); break;
+        default: run_class<SK_F32, ANY_ALIGNMENT>(P, T, &work[t].prob, &work[t].tile, sp, lds, &s_flag, pf); break;
       }
     }
 

@@ -144,6 +144,7 @@ struct sk_plan {
   int grid = 0;      // persistent workgroups of sk_launch
   int64_t grid_cap = 0;  // most workgroups any launch of this plan may use
   int only_dtype = -1;   // the element type all operators share, or -1 if they differ
+  bool any_alignment = false;  // some operator cannot be read in aligned 16-byte pieces
   double ticks_per_ms = 0.0;
   DeviceTables dev;
   // the one-launch-per-operator baseline: every operator tiled as if it were alone;
@@ -236,6 +237,9 @@ sk_status sk_plan_create(const sk_problem *problems, int32_t n, const sk_plan_pa
     plan->only_dtype = plan->host.problems[0].dtype;
     for (const sk_problem &p : plan->host.problems)
       if (p.dtype != plan->only_dtype) plan->only_dtype = -1;
+    const int32_t vec = sk::FLAG_VEC_A | sk::FLAG_VEC_B;
+    for (const sk::DevProblem &d : plan->host.dev)
+      if ((d.flags & vec) != vec) plan->any_alignment = true;
   }
   if (!prm.host_only) {
     hipError_t e = hipGetDevice(&plan->device);
@@ -319,20 +323,23 @@ static sk_status launch_range(sk_plan *plan, const DeviceTables &dt, hipStream_t
   a.ws_off = dt.ws_off;
   a.arrive = dt.arrive;
   const dim3 g((unsigned)grid), b(sk::WG_THREADS);
-  switch (plan->only_dtype) {
-    case SK_F32:
-      hipLaunchKernelGGL(sk::sk_superkernel<SK_F32>, g, b, 0, stream, dt.work, a);
-      break;
-    case SK_BF16:
-      hipLaunchKernelGGL(sk::sk_superkernel<SK_BF16>, g, b, 0, stream, dt.work, a);
-      break;
-    case SK_F16:
-      hipLaunchKernelGGL(sk::sk_superkernel<SK_F16>, g, b, 0, stream, dt.work, a);
-      break;
-    default:
-      hipLaunchKernelGGL(sk::sk_superkernel<-1>, g, b, 0, stream, dt.work, a);
-      break;
+  void (*kernel)(const sk::TileWork *, sk::KernelArgs) = nullptr;
+  if (plan->any_alignment) {
+    switch (plan->only_dtype) {
+      case SK_F32: kernel = sk::sk_superkernel<SK_F32, true>; break;
+      case SK_BF16: kernel = sk::sk_superkernel<SK_BF16, true>; break;
+      case SK_F16: kernel = sk::sk_superkernel<SK_F16, true>; break;
+      default: kernel = sk::sk_superkernel<-1, true>; break;
+    }
+  } else {
+    switch (plan->only_dtype) {
+      case SK_F32: kernel = sk::sk_superkernel<SK_F32, false>; break;
+      case SK_BF16: kernel = sk::sk_superkernel<SK_BF16, false>; break;
+      case SK_F16: kernel = sk::sk_superkernel<SK_F16, false>; break;
+      default: kernel = sk::sk_superkernel<-1, false>; break;
+    }
   }
+  hipLaunchKernelGGL(kernel, g, b, 0, stream, dt.work, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_error("kernel launch", e);
   return SK_OK;

@@ -94,6 +94,10 @@ RAGGED = [
     # strides: skinny and LDS-tile classes, 1x1 and 3x3, extents that do not divide, the generic path
     c(9, 8, 16, 40, 3, 3, 1, 1, st=2), c(8, 8, 32, 24, 1, 1, 0, 0, st=2, nb=2), c(30, 29, 8, 130, 3, 3, 1, 1, st=2),
     c(28, 28, 64, 64, 1, 1, 0, 0, "f16", st=2), c(11, 11, 8, 8, 3, 3, 0, 0, "f32", st=3), c(9, 9, 5, 6, 3, 3, 1, 1, st=2),
+    # operands that cannot be read in 16-byte pieces, large enough for the matrix-core path: odd reduction
+    # lengths in every type, a 3-channel 7x7 stride-2 stem, several 128-blocks per rectangle
+    g(300, 200, 77), g(40, 1000, 1001, "f16"), g(130, 260, 37, "f32"), c(40, 40, 3, 64, 7, 7, 3, 3, st=2),
+    c(30, 30, 5, 130, 3, 3, 1, 1, "f32"), c(23, 17, 6, 96, 3, 3, 1, 1, "f16", nb=2),
 ]
 
 
