@@ -42,6 +42,9 @@ def parse():
     ap.add_argument("--replicate", type=int, default=1,
                     help="put this many independent copies of the workload into ONE plan (steady-state rate of a "
                          "workload too small to outlast a launch)")
+    ap.add_argument("--vendor-baseline", action="store_true",
+                    help="also time the operators one by one through PyTorch's GEMM and convolution calls "
+                         "(rocBLAS/hipBLASLt, MIOpen): context, not part of the metric")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy, so that a rocprofv3 --pmc run of this command "
                          "shows what FETCH_SIZE / WRITE_SIZE read for a kernel of known traffic")
@@ -190,6 +193,47 @@ def main():
         seq_wall, seq_dev = timed(lambda: sk.sk_launch_sequential(next_plan(), stream), seq_steps, 1)
         out["sequential"] = {"ms": round(seq_wall, 5), "tflops": round(flops / (seq_wall * 1e-3) / 1e12, 3),
                              "speedup": round(seq_wall / wall_ms, 3)}
+
+        # the same launches replayed from a HIP graph (no per-launch host cost: the strongest form of
+        # time multiplexing this library can be given)
+        try:
+            side = torch.cuda.Stream(device=dev)
+            side.wait_stream(torch.cuda.current_stream())
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
+                sk.sk_launch_sequential(plan, side.cuda_stream)  # warm the capture stream
+                side.synchronize()
+                with torch.cuda.graph(graph, stream=side):
+                    sk.sk_launch_sequential(plan, side.cuda_stream)
+            torch.cuda.synchronize()
+            g_wall, _ = timed(graph.replay, seq_steps, 2)
+            out["sequential_graph"] = {"ms": round(g_wall, 5), "tflops": round(flops / (g_wall * 1e-3) / 1e12, 3),
+                                       "speedup": round(g_wall / wall_ms, 3)}
+            del graph
+        except Exception as e:  # reported, never fatal: the graph leg is context, not the metric
+            out["sequential_graph"] = {"error": str(e)[:200]}
+
+        if args.vendor_baseline:
+            # the vendor libraries, one call per operator on one stream (time multiplexing as a framework
+            # would do it).  Views only: the calls read the same buffers, outputs go to fresh tensors.
+            import torch.nn.functional as F
+            calls = []
+            for i, sp_ in enumerate(base_specs):
+                a, b = keep[3 * i], keep[3 * i + 1]
+                if sp_.op == "gemm":
+                    calls.append((torch.matmul, (a, b.t()), {}))
+                else:
+                    calls.append((F.conv2d, (a.permute(0, 3, 1, 2), b.permute(0, 3, 1, 2)),
+                                  {"padding": (sp_.pad_h, sp_.pad_w), "stride": sp_.stride}))
+
+            def vendor():
+                for fn, a_, kw in calls:
+                    fn(*a_, **kw)
+
+            v_wall, _ = timed(vendor, seq_steps, 2)
+            out["vendor_sequential"] = {"ms": round(v_wall, 5), "tflops": round(flops / (v_wall * 1e-3) / 1e12, 3),
+                                        "speedup": round(v_wall / wall_ms, 3),
+                                        "what": "torch.matmul / conv2d (channels_last views) per operator, one stream"}
 
         # multi-stream baseline: one single-operator plan per operator, round-robin over <= 32 streams
         nstreams = min(32, len(specs))

@@ -207,6 +207,38 @@ def test_recycled_plan_tables():
     sk.sk_release_cached_memory()  # empty pool
 
 
+def test_launches_replayed_from_a_graph():
+    """Both launch calls captured into HIP graphs and replayed several times, with eager launches and
+    synchronisations between the replays: every replay gives the oracle's result (the kernels re-arm
+    their own counters; nothing in the captured work is a memset)."""
+    specs = workloads.config(2, seed=1)[:8] + workloads.config(3, seed=0)[3:6]
+    b = H.Batch(specs, seed=1)
+    side = torch.cuda.Stream()
+    with b.plan(tile_bytes_min=8192, tile_bytes_max=8192) as plan:   # small tiles: split reductions in the graph
+        graphs = []
+        for launch in (sk.sk_launch, sk.sk_launch_sequential):
+            with torch.cuda.stream(side):
+                launch(plan, side.cuda_stream)
+                side.synchronize()
+                gr = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(gr, stream=side):
+                    launch(plan, side.cuda_stream)
+            graphs.append(gr)
+        _sync()
+        for rep in range(3):
+            for gi, gr in enumerate(graphs):
+                b.reset_outputs()
+                _sync()
+                gr.replay()
+                _sync()
+                H.check_against_oracle(b, f"graph {gi} replay {rep}")
+                b.reset_outputs()
+                sk.sk_launch(plan, H.stream_handle())   # eager work between the replays
+                _sync()
+                H.check_against_oracle(b, f"eager after graph {gi} replay {rep}")
+        del graphs
+
+
 def test_single_and_empty_plans():
     run_all_modes([g(1, 64, 64)], seed=3, label="single")
     with sk.sk_plan_create([], None) as plan:
