@@ -170,6 +170,12 @@ sk_status sk_release_cached_memory(void);
  * from the table in order through a single atomic counter, so operators with
  * earlier deadlines start first.  Asynchronous.  Needs a device-resident plan
  * (SK_ERR_STATE otherwise).
+ * A plan has one tile queue and one set of split-reduction counters, which the
+ * kernel re-arms itself when it ends: launches of ONE plan must not overlap
+ * (order them on one stream or with events); different plans may.
+ * The call makes no allocation, copy, memset or host synchronisation, so it may
+ * be captured into a HIP graph; the plan must then outlive the graph's
+ * replays.
  */
 sk_status sk_launch(sk_plan *plan, void *hip_stream);
 
@@ -181,7 +187,8 @@ sk_status sk_launch(sk_plan *plan, void *hip_stream);
  * would get), not with the tiles of the coalesced table.  Reductions may
  * therefore be sliced differently: outputs agree with sk_launch up to the order
  * of summation.  The first call on a plan builds and uploads these tables
- * (SK_ERR_ALLOC / SK_ERR_HIP as for sk_plan_create); later calls only launch.
+ * (SK_ERR_ALLOC / SK_ERR_HIP as for sk_plan_create); later calls only launch
+ * (and may be captured into a HIP graph like sk_launch).
  */
 sk_status sk_launch_sequential(sk_plan *plan, void *hip_stream);
 
