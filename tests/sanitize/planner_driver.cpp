@@ -1,0 +1,130 @@
+// Host-only driver for the planner under AddressSanitizer / UndefinedBehaviorSanitizer:
+// seeded random operator lists (odd sizes, strides, all element types, every parameter
+// combination the planner accepts, and lists it must reject), planned whole and operator by
+// operator.  Checks only what must hold for any input: status codes, table sizes, that every
+// record stays inside its operator.  Byte-exact comparison with the reference planner is the
+// Python tests' job.
+#include <cstdint>
+#include <cstdio>
+#include <random>
+#include <string>
+#include <vector>
+
+#include "sk_internal.h"
+
+static int fail(const char *what, int seed) {
+  std::fprintf(stderr, "planner_driver: %s (seed %d)\n", what, seed);
+  return 1;
+}
+
+int main() {
+  for (int seed = 0; seed < 300; ++seed) {
+    std::mt19937 g(seed);
+    auto pick = [&](std::initializer_list<int> v) { return *(v.begin() + g() % v.size()); };
+    const int n = (int)(g() % 40);
+    std::vector<sk_problem> ps((size_t)n);
+    uintptr_t addr = 0x10000000;
+    bool expect_ok = true;
+    for (int i = 0; i < n; ++i) {
+      sk_problem &p = ps[(size_t)i];
+      p = sk_problem{};
+      p.dtype = pick({SK_F32, SK_BF16, SK_F16});
+      const int es = p.dtype == SK_F32 ? 4 : 2;
+      int64_t na, nb, nc;
+      if (g() % 5 < 3) {
+        p.op = SK_GEMM;
+        p.M = pick({1, 2, 7, 16, 17, 33, 64, 65, 129, 300, 1000});
+        p.N = pick({1, 5, 31, 32, 33, 127, 128, 129, 500, 4097});
+        p.K = pick({1, 3, 8, 63, 64, 65, 256, 1000, 4096, 9000});
+        p.lda = g() % 3 ? 0 : p.K + (int)(g() % 9);
+        p.ldb = g() % 3 ? 0 : p.K + (int)(g() % 9);
+        p.ldc = g() % 3 ? 0 : p.N + (int)(g() % 9);
+        na = (int64_t)p.M * (p.lda ? p.lda : p.K);
+        nb = (int64_t)p.N * (p.ldb ? p.ldb : p.K);
+        nc = (int64_t)p.M * (p.ldc ? p.ldc : p.N);
+      } else {
+        p.op = SK_CONV2D_NHWC;
+        p.Nb = 1 + (int)(g() % 2);
+        p.H = 1 + (int)(g() % 40);
+        p.Wd = 1 + (int)(g() % 40);
+        p.Cin = pick({1, 3, 8, 64, 200});
+        p.Cout = pick({1, 7, 64, 130});
+        p.R = pick({1, 3, 5, 7});
+        p.S = pick({1, 3});
+        p.pad_h = (int)(g() % 4);
+        p.pad_w = (int)(g() % 2);
+        p.stride = (int)(g() % 4);
+        if (p.H + 2 * p.pad_h < p.R || p.Wd + 2 * p.pad_w < p.S) expect_ok = false;
+        na = (int64_t)p.Nb * p.H * p.Wd * p.Cin;
+        nb = (int64_t)p.Cout * p.R * p.S * p.Cin;
+        nc = (int64_t)p.Nb * (p.H + 2 * p.pad_h + 1) * (p.Wd + 2 * p.pad_w + 1) * p.Cout;
+      }
+      p.A = (const void *)addr;
+      addr += (uintptr_t)(na * es + 511) / 256 * 256;
+      p.B = (const void *)addr;
+      addr += (uintptr_t)(nb * es + 511) / 256 * 256;
+      p.C = (void *)(addr + (g() % 4 == 0 ? 2 : 0));  // sometimes misaligned
+      addr += (uintptr_t)(nc * es + 767) / 256 * 256;
+      const double ds[] = {0.0, -1.0, 0.5, 0.5, 3.0, 1e300, std::numeric_limits<double>::infinity(),
+                           std::numeric_limits<double>::quiet_NaN()};
+      p.deadline_ms = ds[g() % 8];
+    }
+    sk_plan_params prm;
+    sk_plan_params_default(&prm);
+    prm.host_only = 1;
+    prm.edf = (int)(g() % 2);
+    prm.skinny_max_m = pick({0, 8, 16, 32, 64});
+    prm.tile_bytes_min = pick({1024, 4096, 32768, 1 << 18});
+    prm.tile_bytes_max = prm.tile_bytes_min * pick({1, 2, 16, 64});
+    prm.balance_div = pick({1, 7, 64, 512, 2048});
+    prm.max_groups = pick({1, 3, 4, 64, 256});
+    prm.tail_div = pick({0, 1, 16, 384, 5000});
+    sk::HostPlan hp;
+    std::string err;
+    const sk_status st = sk::plan_host(n ? ps.data() : nullptr, n, &prm, hp, err);
+    if (!expect_ok) {
+      if (st == SK_OK) return fail("a filter larger than its padded image was accepted", seed);
+      continue;
+    }
+    if (st != SK_OK) {
+      std::fprintf(stderr, "%s\n", err.c_str());
+      return fail("plan_host failed on a valid list", seed);
+    }
+    if ((int)hp.dev.size() != n || (int)hp.order.size() != n) return fail("table sizes", seed);
+    int64_t sum = 0;
+    for (int i = 0; i < n; ++i) sum += hp.count[(size_t)i];
+    if (sum != (int64_t)hp.tiles.size()) return fail("tile counts do not add up", seed);
+    for (const sk_tile &t : hp.tiles) {
+      if ((int)t.problem >= n) return fail("record names a missing operator", seed);
+      const sk::DevProblem &d = hp.dev[t.problem];
+      if (t.m_len < 1 || t.n_len < 1 || t.k_len < 1 || (int64_t)t.m0 + t.m_len > d.Mg ||
+          (int64_t)t.n0 + t.n_len > d.Ng || (int64_t)t.k0 + t.k_len > d.Kg || t.ks_idx >= t.S ||
+          t.out_tile_id >= hp.ws_off.size())
+        return fail("record leaves its operator", seed);
+    }
+    sk::HostPlan alone;
+    if (sk::plan_host_each_alone(hp, alone, err) != SK_OK) return fail("plan_host_each_alone", seed);
+    if (alone.dev.size() != hp.dev.size()) return fail("baseline tables", seed);
+  }
+  // lists the planner must reject
+  {
+    sk::HostPlan hp;
+    std::string err;
+    sk_problem p{};
+    p.op = SK_GEMM;
+    p.dtype = SK_BF16;
+    p.M = 4;
+    p.N = 64;
+    p.K = 64;
+    p.A = (const void *)0x1000;
+    p.B = (const void *)0x2000;
+    p.C = (void *)0x3000;
+    sk_problem two[2] = {p, p};  // same output twice
+    if (sk::plan_host(two, 2, nullptr, hp, err) != SK_ERR_OVERLAP) return fail("overlap not detected", -1);
+    p.M = 0;
+    if (sk::plan_host(&p, 1, nullptr, hp, err) != SK_ERR_INVALID_ARG) return fail("M = 0 accepted", -1);
+    if (sk::plan_host(nullptr, 3, nullptr, hp, err) != SK_ERR_INVALID_ARG) return fail("null list accepted", -1);
+  }
+  std::puts("planner_driver: ok");
+  return 0;
+}
