@@ -42,6 +42,8 @@ def parse():
     ap.add_argument("--replicate", type=int, default=1,
                     help="put this many independent copies of the workload into ONE plan (steady-state rate of a "
                          "workload too small to outlast a launch)")
+    ap.add_argument("--no-ceilings", action="store_true",
+                    help="skip the measured ceilings (streaming read, bf16 MFMA loop) the rates are also held against")
     ap.add_argument("--vendor-baseline", action="store_true",
                     help="also time the operators one by one through PyTorch's GEMM and convolution calls "
                          "(rocBLAS/hipBLASLt, MIOpen): context, not part of the metric")
@@ -278,12 +280,53 @@ def main():
                 p2.close()
             out["deadlines"] = res
 
+    if not args.no_ceilings:
+        out["ceilings"] = measured_ceilings(torch, out["roofline"]["achieved"], out["value"])
+        tr = out["roofline"]["traffic"]
+        if tr and "achieved_over_stream_read" in out["ceilings"]:
+            best = out["roofline"]["achieved"] / out["ceilings"]["achieved_over_stream_read"]
+            out["ceilings"]["measured_traffic_over_stream_read"] = round(tr / (kern_ms * 1e-3) / 1e9 / best, 4)
+
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(specs, args.seed, args.cpu_seconds)
 
     for pl in plans:
         pl.close()
     print(json.dumps(out))
+
+
+def measured_ceilings(torch, achieved_gbs, achieved_tflops):
+    """What this device attains with kernels that do nothing else (libsk_ceilings.so): a streaming read
+    with the superkernel's load map over 2 GiB, for long and for short rows, and a bf16 MFMA loop."""
+    import ctypes as C
+
+    path = os.path.join(ROOT, "paper_1901_10008_amd", "libsk_ceilings.so")
+    try:
+        lib = C.CDLL(path)
+        lib.sk_ceiling_stream_read.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.c_int, C.c_void_p,
+                                               C.POINTER(C.c_double)]
+        lib.sk_ceiling_mfma_bf16.argtypes = [C.c_int, C.c_void_p, C.POINTER(C.c_double)]
+        buf = torch.ones(2 << 30, dtype=torch.uint8, device="cuda")
+        sink = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
+        torch.cuda.synchronize()
+        res = {}
+        for row_bytes in (16384, 2048):
+            v = C.c_double()
+            st = lib.sk_ceiling_stream_read(buf.data_ptr(), buf.numel(), row_bytes, 5, sink.data_ptr(), C.byref(v))
+            if st != 0:
+                return {"error": f"sk_ceiling_stream_read status {st}"}
+            res[f"stream_read_GBs_rows_of_{row_bytes}B"] = round(v.value, 1)
+        v = C.c_double()
+        st = lib.sk_ceiling_mfma_bf16(20000, sink.data_ptr(), C.byref(v))
+        if st != 0:
+            return {"error": f"sk_ceiling_mfma_bf16 status {st}"}
+        res["mfma_bf16_TFLOPs"] = round(v.value, 1)
+        best = max(res["stream_read_GBs_rows_of_16384B"], res["stream_read_GBs_rows_of_2048B"])
+        res["achieved_over_stream_read"] = round(achieved_gbs / best, 4)
+        del buf, sink
+        return res
+    except OSError as e:
+        return {"error": str(e)[:200]}
 
 
 def measured_traffic(workload):

@@ -8,6 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsuperkernel.so")
+CEILINGS_LIB = os.path.join(HERE, "libsk_ceilings.so")  # measuring aid of bench.py, not part of the ABI
 SOURCES = ["superkernel.hip", "planner.cpp"]
 HEADERS = ["kernels.hip.h", "sk_internal.h", os.path.join(ROOT, "include", "superkernel.h")]
 
@@ -39,6 +40,9 @@ def build(force: bool = True, verbose: bool = False, extra=()) -> str:
         [hipcc, *HIPCC_FLAGS, *extra, *inc, "-c", srcs[0], "-o", o_hip],
         ["g++", "-O2", "-std=c++17", "-fPIC", "-Wall", *inc, "-c", srcs[1], "-o", o_cpp],
         [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", o_hip, o_cpp, "-o", LIB],
+        [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         os.path.join(CSRC, "ceilings.hip"), "-o", CEILINGS_LIB],
     ]
     for cmd in steps:
         if verbose:

@@ -1,0 +1,147 @@
+// What this machine attains on the two resources the roofline is drawn from, measured with
+// kernels that do nothing else: a streaming read with the superkernel's own load map, and a
+// loop of bf16 MFMAs on registers.  bench.py reports the superkernel's rates against these as
+// well as against the datasheet peaks.  Not part of the library's ABI: a measuring aid in a
+// shared object of its own.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+#define SK_GLOBAL __attribute__((address_space(1)))
+
+// Every wave walks along groups of 32 rows, one 128-byte step at a time: four load instructions
+// per step, each covering eight rows with their full 128-byte lines (the weight-streaming map of
+// the skinny tile classes), a ring of NB steps in flight.  Groups are visited in a scattered
+// order so that neighbouring workgroups do not walk neighbouring memory.
+template <int NB>
+__global__ void __launch_bounds__(256, 2) stream_read(const char *p, size_t row_bytes, size_t rows, f32x4 *sink) {
+  const int lane = threadIdx.x & 63;
+  const size_t wave = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6), nwaves = (size_t)gridDim.x * 4;
+  const size_t ngroups = rows / 32;
+  const int nstep = (int)(row_bytes / 128);
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (size_t g0 = wave; g0 < ngroups; g0 += nwaves) {
+    const size_t g = (g0 * 7919u + 104729u) % ngroups;  // 7919 is prime: a permutation when it does not divide ngroups
+    size_t off[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) off[j] = (g * 32 + j * 8 + lane / 8) * row_bytes + (lane % 8) * 16;
+    u32x4 w[NB][4];
+#pragma unroll
+    for (int u = 0; u < NB - 1; ++u)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        w[u][j] = __builtin_nontemporal_load((const u32x4 SK_GLOBAL *)(uintptr_t)(p + off[j] + (size_t)(u < nstep ? u : 0) * 128));
+    for (int i0 = 0; i0 < nstep; i0 += NB) {
+#pragma unroll
+      for (int u = 0; u < NB; ++u) {
+        const int i = i0 + u;
+        int ahead = i + NB - 1;
+        if (ahead >= nstep) ahead = 0;  // loads past the end re-read the first step; never summed
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          w[(u + NB - 1) % NB][j] =
+              __builtin_nontemporal_load((const u32x4 SK_GLOBAL *)(uintptr_t)(p + off[j] + (size_t)ahead * 128));
+        if (i < nstep) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) acc += __builtin_bit_cast(f32x4, w[u][j]);
+        }
+      }
+    }
+  }
+  if (acc.x == 12345.678f) sink[wave] = acc;  // keeps the loads alive; practically never taken
+}
+
+// Four independent 32x32x16 bf16 accumulations per wave, `iters` rounds.
+__global__ void __launch_bounds__(256, 2) mfma_loop(int iters, float seed, f32x4 *sink) {
+  bf16x8 a, b;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    a[i] = (__bf16)(seed + (float)threadIdx.x * 1e-3f);
+    b[i] = (__bf16)(seed - (float)i * 1e-3f);
+  }
+  f32x16 c0, c1, c2, c3;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) c0[i] = c1[i] = c2[i] = c3[i] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+    c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c0, 0, 0, 0);
+    c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c1, 0, 0, 0);
+    c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c2, 0, 0, 0);
+    c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c3, 0, 0, 0);
+  }
+  const float s = c0[0] + c1[1] + c2[2] + c3[3];
+  if (s == 12345.678f) sink[blockIdx.x] = f32x4{s, s, s, s};
+}
+
+int cu_count() {
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+  return cus;
+}
+
+}  // namespace
+
+extern "C" {
+
+// Reads `bytes` of device memory at `buf` as rows of `row_bytes` (a multiple of 128; bytes a
+// multiple of 32 rows) `launches` times after one warm-up; *gb_per_s = bytes / mean launch time.
+// `sink` is device memory of at least 2 * CUs * 4 * 16 bytes.  Returns 0 or a hipError_t.
+int sk_ceiling_stream_read(const void *buf, uint64_t bytes, uint64_t row_bytes, int launches, void *sink,
+                           double *gb_per_s) {
+  const int cus = cu_count();
+  if (!buf || !sink || !gb_per_s || cus <= 0 || row_bytes == 0 || row_bytes % 128 || bytes % (32 * row_bytes) ||
+      launches < 1)
+    return (int)hipErrorInvalidValue;
+  hipEvent_t e0, e1;
+  hipError_t e = hipEventCreate(&e0);
+  if (e != hipSuccess) return (int)e;
+  e = hipEventCreate(&e1);
+  if (e != hipSuccess) return (int)e;
+  const dim3 grid(2 * cus), block(256);
+  const size_t rows = bytes / row_bytes;
+  hipLaunchKernelGGL(stream_read<2>, grid, block, 0, 0, (const char *)buf, (size_t)row_bytes, rows, (f32x4 *)sink);
+  (void)hipEventRecord(e0, 0);
+  for (int i = 0; i < launches; ++i)
+    hipLaunchKernelGGL(stream_read<2>, grid, block, 0, 0, (const char *)buf, (size_t)row_bytes, rows, (f32x4 *)sink);
+  (void)hipEventRecord(e1, 0);
+  e = hipEventSynchronize(e1);
+  float ms = 0.f;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (e != hipSuccess) return (int)e;
+  *gb_per_s = (double)bytes * launches / (ms * 1e-3) / 1e9;
+  return 0;
+}
+
+// *tflops of `iters` rounds of four 32x32x16 bf16 MFMAs in every wave of 2 workgroups per CU.
+int sk_ceiling_mfma_bf16(int iters, void *sink, double *tflops) {
+  const int cus = cu_count();
+  if (!sink || !tflops || cus <= 0 || iters < 1) return (int)hipErrorInvalidValue;
+  hipEvent_t e0, e1;
+  hipError_t e = hipEventCreate(&e0);
+  if (e != hipSuccess) return (int)e;
+  e = hipEventCreate(&e1);
+  if (e != hipSuccess) return (int)e;
+  const dim3 grid(2 * cus), block(256);
+  hipLaunchKernelGGL(mfma_loop, grid, block, 0, 0, iters, 0.5f, (f32x4 *)sink);
+  (void)hipEventRecord(e0, 0);
+  hipLaunchKernelGGL(mfma_loop, grid, block, 0, 0, iters, 0.5f, (f32x4 *)sink);
+  (void)hipEventRecord(e1, 0);
+  e = hipEventSynchronize(e1);
+  float ms = 0.f;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (e != hipSuccess) return (int)e;
+  const double flops = (double)grid.x * 4.0 * iters * 4.0 * (2.0 * 32 * 32 * 16);
+  *tflops = flops / (ms * 1e-3) / 1e12;
+  return 0;
+}
+
+}  // extern "C"

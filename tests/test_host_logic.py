@@ -29,3 +29,12 @@ def test_tuner_candidates_span_the_grid():
     assert len(cands) == 6 and {"tile_bytes_max": 2, "tail_div": 768} in cands
     assert len(tune.candidates()) == math.prod(len(v) for v in tune.DEFAULT_GRID.values())
     assert len({tuple(sorted(c.items())) for c in tune.candidates()}) == len(tune.candidates())
+
+
+def test_ceilings_library_exports_its_two_calls():
+    import ctypes
+    import os
+    import paper_1901_10008_amd
+    path = os.path.join(os.path.dirname(paper_1901_10008_amd.__file__), "libsk_ceilings.so")
+    lib = ctypes.CDLL(path)   # built by paper_1901_10008_amd.build; loading needs no GPU
+    assert lib.sk_ceiling_stream_read and lib.sk_ceiling_mfma_bf16
