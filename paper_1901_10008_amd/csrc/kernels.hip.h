@@ -463,11 +463,67 @@ __device__ __forceinline__ void run_skinny(const DevProblem &P, const sk_tile &T
   const RowA srow = row_of(P, s_ok ? s_row : 0);
   const int s_lds = s_row * LROW + s_piece * 16;
   u32x4 ar[SPT];
+  // For a convolution: filter tap (g_r, g_s) and channel g_c of this thread's first piece in the
+  // chunk that stage_load will fetch next, and g_off = ((g_r*W + g_s)*Cin + g_c), its distance in
+  // elements from the pixel under tap (0,0).  Chunks are fetched in order (0, 1, ..., then 0 again
+  // for the next pass), so the position moves on by additions; the divisions happen once per tile.
+  int g_r = 0, g_s = 0, g_c = 0;
+  int64_t g_off = 0;
+  const int64_t next_filter_row = (int64_t)(P.W - P.S) * P.Cin;
+  if (P.gather) {
+    const int kk = k0 + s_piece * CE;
+    const int tap = kk / P.Cin;
+    g_c = kk - tap * P.Cin;
+    g_r = tap / P.S;
+    g_s = tap - g_r * P.S;
+    g_off = ((int64_t)g_r * P.W + g_s) * P.Cin + g_c;
+  }
+  const int g_r0 = g_r, g_s0 = g_s, g_c0 = g_c;
+  const int64_t g_off0 = g_off;
   auto stage_load = [&](int c) {
     const int k = k0 + ((c << BPC_LOG2) * 8 + s_piece) * CE;
+    if (!P.gather) {
+#pragma unroll
+      for (int i = 0; i < SPT; ++i) ar[i] = fetch_A<ES>(P, srow, k + i * CE, s_ok && k + i * CE < k_stop, zeros);
+      return;
+    }
+    if (c == 0) {
+      g_r = g_r0;
+      g_s = g_s0;
+      g_c = g_c0;
+      g_off = g_off0;
+    }
+    // the thread's pieces follow one another in the patch row (a piece never straddles two taps:
+    // Cin is a multiple of a piece); no branch between the loads
+    int r = g_r, t = g_s, cc = g_c;
+    int64_t off = g_off;
 #pragma unroll
     for (int i = 0; i < SPT; ++i) {
-      ar[i] = fetch_A<ES>(P, srow, k + i * CE, s_ok && k + i * CE < k_stop, zeros);
+      const bool ok = s_ok && k + i * CE < k_stop && (unsigned)(srow.hb + r) < (unsigned)P.H &&
+                      (unsigned)(srow.wb + t) < (unsigned)P.W;
+      const uintptr_t pa = (uintptr_t)P.A + (uintptr_t)((srow.base + off) * ES);
+      ar[i] = *(const u32x4 SK_GLOBAL *)(ok ? pa : zeros);
+      cc += CE;
+      off += CE;
+      const bool next_tap = cc >= P.Cin;
+      cc -= next_tap ? P.Cin : 0;
+      t += next_tap ? 1 : 0;
+      const bool next_row = t == P.S;  // (only ever true right after a step to the next tap)
+      t = next_row ? 0 : t;
+      r += next_row ? 1 : 0;
+      off += next_row ? next_filter_row : 0;
+    }
+    // on to the next chunk
+    constexpr int KC = BPC * 8 * CE;
+    g_c += KC;
+    g_off += KC;
+    while (g_c >= P.Cin) {
+      g_c -= P.Cin;
+      if (++g_s == P.S) {
+        g_s = 0;
+        ++g_r;
+        g_off += next_filter_row;
+      }
     }
   };
   auto stage_store = [&](int c) {
