@@ -122,7 +122,7 @@ typedef struct {
  */
 typedef struct {
   uint32_t problem;     /* index of the operator in the sk_problem array                    */
-  uint16_t cls;         /* tile class: 0, 3, 6 skinny (1, 2, 4 blocks of 16 rows), 9: 128x128 LDS tile */
+  uint16_t cls;         /* tile class: 0, 3, 6 skinny (1, 2, 4 blocks of 16 rows), 9: 128x128 and 10: 128x64 LDS tile */
   uint8_t ks_idx;       /* which reduction slice of the output rectangle this record is     */
   uint8_t S;            /* number of reduction slices of the rectangle (1 = not split)      */
   uint32_t m0, n0;      /* origin of the output rectangle in the operator's [Mg,Ng] GEMM view */

@@ -41,7 +41,9 @@ assert RECORD.size == 32
 #         against a block of 32*G weight rows; long reductions are cut into S slices
 #         that different workgroups take.   id = 3*log2(rm)
 #   9     128 x 128 output tile staged through LDS
+#   10    128 x 64 output tile, for operators with at most 64 output columns
 CLS_TILE_128x128 = 9
+CLS_TILE_128x64 = 10
 
 
 @dataclass
@@ -110,7 +112,8 @@ def tiling(p, T: int, prm: Params):
         return 3 * rm_code, mg, 32 * G, S, slice_len
     # LDS tile: cut the reduction when the operand bytes of one tile are far beyond the target
     S, slice_len = 1, kg
-    tb = (128 + 128) * kg * es
+    bn = 64 if ng <= 64 else 128
+    tb = (128 + bn) * kg * es
     if tb > 2 * T:
         chunk = 256
         nchunks = -(-kg // chunk)
@@ -118,7 +121,7 @@ def tiling(p, T: int, prm: Params):
         per = -(-nchunks // want)
         S = -(-nchunks // per)
         slice_len = per * chunk
-    return CLS_TILE_128x128, 128, 128, S, slice_len
+    return (CLS_TILE_128x64 if bn == 64 else CLS_TILE_128x128), 128, bn, S, slice_len
 
 
 def plan(problems: Sequence, prm: Params | None = None):

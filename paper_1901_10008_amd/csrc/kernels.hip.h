@@ -1222,6 +1222,8 @@ __device__ __forceinline__ void run_class(const DevProblem &P, const sk_tile &T,
     run_skinny<DT, 2>(P, T, sp, lds, s_flag, pf);
   } else if (cls == 6) {
     run_skinny<DT, 4>(P, T, sp, lds, s_flag, pf);
+  } else if (cls == CLS_TILE_128x64) {
+    run_tile<DT, 128, 64, 2, 2>(P, T, sp, lds, s_flag, pf);
   } else {
     run_tile<DT, 128, 128, 2, 2>(P, T, sp, lds, s_flag, pf);
   }

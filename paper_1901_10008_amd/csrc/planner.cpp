@@ -251,9 +251,10 @@ sk_status plan_host(const sk_problem *problems, int32_t n, const sk_plan_params 
       BM = c.Mg;
       BN = 32 * G;
     } else {
-      cls = CLS_TILE_128x128;
+      // 128 output columns per tile, or 64 for an operator that has no more than that
+      cls = c.Ng <= 64 ? CLS_TILE_128x64 : CLS_TILE_128x128;
       BM = 128;
-      BN = 128;
+      BN = c.Ng <= 64 ? 64 : 128;
       // operand bytes of one tile over the whole reduction; far beyond the target: cut the reduction
       const int64_t tb = (BM + BN) * c.Kg * es;
       if (tb > 2 * T) {
@@ -287,9 +288,11 @@ sk_status plan_host(const sk_problem *problems, int32_t n, const sk_plan_params 
         }
         if (S > 1) {
           // partial sums of this rectangle: S slices x 4 waves x (2 * rm) accumulators x 64 lanes, 16 bytes each
-          // (LDS tiles: S slices x 256 threads x 16 accumulator quads)
+          // (LDS tiles: S slices x 256 threads x 16 accumulator quads, 8 for the 64-column tile)
           out.ws_off.push_back((uint32_t)out.ws_f32x4);
-          out.ws_f32x4 += cls == CLS_TILE_128x128 ? S * 4096 : S * 4 * 2 * ((int64_t)1 << (cls / 3)) * 64;
+          out.ws_f32x4 += cls == CLS_TILE_128x128  ? S * 4096
+                          : cls == CLS_TILE_128x64 ? S * 2048
+                                                   : S * 4 * 2 * ((int64_t)1 << (cls / 3)) * 64;
         } else {
           out.ws_off.push_back(0u);
         }

@@ -19,6 +19,7 @@ enum : int32_t {
 enum : uint16_t {
   CLS_SKINNY_FIRST = 0,  // 0..8: 3*log2(rm) + log2(wk), rm = 1, 2, 4 blocks of 16 activation rows
   CLS_TILE_128x128 = 9,
+  CLS_TILE_128x64 = 10,  // operators with at most 64 output columns
 };
 
 // Device-side description of one operator in its canonical GEMM view

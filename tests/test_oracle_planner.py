@@ -120,8 +120,9 @@ def test_hand_enumerated_four_row_block_class():
     assert [(x["cls"], x["n0"], x["n_len"], x["S"]) for x in t] == [(6, 0, 256, 1), (6, 256, 44, 1)]
     # M = 64 is the last skinny size, 65 goes to LDS tiles
     assert P.decode(P.plan([gemm(64, 32, 64)], prm)[0])[0]["cls"] == 6
-    assert P.decode(P.plan([gemm(65, 32, 64)], prm)[0])[0]["cls"] == 9
-    assert P.decode(P.plan([gemm(64, 32, 64)], P.Params(skinny_max_m=32))[0])[0]["cls"] == 9
+    assert P.decode(P.plan([gemm(65, 32, 64)], prm)[0])[0]["cls"] == 10      # at most 64 columns: the narrow tile
+    assert P.decode(P.plan([gemm(64, 32, 64)], P.Params(skinny_max_m=32))[0])[0]["cls"] == 10
+    assert P.decode(P.plan([gemm(65, 65, 64)], prm)[0])[0]["cls"] == 9
 
 
 def test_hand_enumerated_lds_tiles():
@@ -151,6 +152,30 @@ def test_hand_enumerated_lds_tiles():
     assert [(x["m0"], x["ks_idx"], x["S"], x["k0"], x["k_len"]) for x in t] == \
         [(0, 0, 3, 0, 1536), (0, 1, 3, 1536, 1536), (0, 2, 3, 3072, 1536),
          (128, 0, 3, 0, 1536), (128, 1, 3, 1536, 1536), (128, 2, 3, 3072, 1536)]
+
+
+def test_hand_enumerated_narrow_lds_tiles():
+    # at most 64 output columns: 128 x 64 tiles (cls 10).  Mg = 196, Ng = 64, Kg = 576: two row blocks
+    whole = P.Params(tile_bytes_min=1 << 20, tile_bytes_max=1 << 20)
+    t = P.decode(P.plan([conv(14, 64, 64, 3)], whole)[0])
+    assert [(x["cls"], x["m0"], x["n0"], x["m_len"], x["n_len"], x["k_len"], x["S"]) for x in t] == \
+        [(10, 0, 0, 128, 64, 576, 1), (10, 128, 0, 68, 64, 576, 1)]
+    # 40 columns: one ragged column block; 65 columns: back to 128-wide tiles, the second one ragged
+    t = P.decode(P.plan([gemm(130, 40, 64)], whole)[0])
+    assert [(x["cls"], x["m0"], x["n_len"]) for x in t] == [(10, 0, 40), (10, 128, 40)]
+    t = P.decode(P.plan([gemm(130, 65, 64)], whole)[0])
+    assert [(x["cls"], x["m0"], x["n0"], x["n_len"]) for x in t] == [(9, 0, 0, 65), (9, 128, 0, 65)]
+    # the reduction of a narrow tile is cut by the bytes of ITS operands: (128 + 64) * 4608 * 2 = 1728 KiB is
+    # within twice the 1 MiB target, where the 128-wide tile's 2304 KiB are not
+    assert all(x["S"] == 1 for x in P.decode(P.plan([conv(14, 512, 64, 3)], whole)[0]))
+    assert all(x["S"] == 3 for x in P.decode(P.plan([conv(14, 512, 128, 3)], whole)[0]))
+    # ... and is cut below that: target 512 KiB, 18 chunks, wanted min(18, ceil(1728/512) = 4, 4608 // 1024 = 4) = 4,
+    # five chunks per slice -> slices of 1280, 1280, 1280, 768
+    half = P.Params(tile_bytes_min=512 << 10, tile_bytes_max=512 << 10)
+    t = P.decode(P.plan([conv(14, 512, 64, 3)], half)[0])
+    assert [(x["ks_idx"], x["S"], x["k0"], x["k_len"]) for x in t[:4]] == \
+        [(0, 4, 0, 1280), (1, 4, 1280, 1280), (2, 4, 2560, 1280), (3, 4, 3840, 768)]
+    P.check_coverage([conv(14, 512, 64, 3)], P.plan([conv(14, 512, 64, 3)], half)[0])
 
 
 def test_edf_order_is_stable_sort_by_deadline_then_index():
