@@ -61,7 +61,7 @@ def run_all_modes(specs, seed=0, label="", **batch_kw):
     return worst
 
 
-@pytest.mark.parametrize("idx", [1, 2, 3, 4, 6, 7])
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 6, 7, 8])
 def test_config_matches_oracle(idx):
     specs = workloads.config(idx, seed=0)
     worst = run_all_modes(specs, seed=0, label=f"config {idx}")

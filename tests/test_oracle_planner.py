@@ -207,7 +207,7 @@ def test_target_bytes_rule():
     assert P.target_tile_bytes(mid * 4, P.Params(balance_div=2048)) == 65536
 
 
-@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5, 6, 7])
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5, 6, 7, 8])
 def test_coverage_on_every_config(idx):
     probs = workloads.config(idx, seed=0)
     table, order, first, count = P.plan(probs)

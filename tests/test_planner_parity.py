@@ -47,7 +47,7 @@ def ref_params(**kw):
     return P.Params(**kw)
 
 
-@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5, 6, 7])
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5, 6, 7, 8])
 @pytest.mark.parametrize("seed", [0, 1])
 def test_plan_bytes_match_reference_on_configs(idx, seed):
     specs = workloads.config(idx, seed=seed)

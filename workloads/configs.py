@@ -194,6 +194,13 @@ def _cfg7(seed):
             strided(14, 512, 512, 3, 1), strided(14, 1024, 2048, 1, 0)]
 
 
+def _cfg8(seed):
+    # The experiment behind the paper's headline figures (Section 5.3): the second convolution of the
+    # first residual stage of an 18-layer network (3x3, 64 -> 64 channels on a 56x56 image, batch 1),
+    # one instance per tenant, every tenant with weights and activations of its own.
+    return [_conv("bf16", 56, 64, 64, 3, tag=f"resnet18-conv2_2-tenant{i}") for i in range(32)]
+
+
 _RECIPES = {
     "cfg1_fp32_gemm4": _cfg1,
     "cfg2_bf16_gemm16": _cfg2,
@@ -202,6 +209,7 @@ _RECIPES = {
     "cfg5_mixed256_edf": _cfg5,
     "cfg6_lstm_matvec64": _cfg6,
     "cfg7_resnet_stride2_conv7": _cfg7,
+    "cfg8_conv2_2_tenants32": _cfg8,
 }
 
 
