@@ -1012,11 +1012,12 @@ __device__ __forceinline__ void run_tile(const DevProblem &P, const sk_tile &T, 
 // trip, plain fp32 multiply-adds in ascending k.  Correct for everything, fast
 // for nothing.
 // ---------------------------------------------------------------------------
-// (Not inlined, and given the records' addresses in memory rather than references to the
-// caller's copies: a local whose address escapes into a call has to live in scratch memory,
-// and every later use of it in the fast paths would be a load from there.)
+// (Inlined, like every path of the kernel: as real calls the two slow paths gave the kernel a stack,
+// and how well its fast paths then ran changed from build to build.  They exist only in the kernel
+// instantiation for plans with such operands, which takes a few registers more.  They are given the
+// records' addresses in memory rather than references to the caller's copies.)
 template <int DT>
-__device__ void run_generic(const DevProblem *P_mem, const sk_tile *T_mem) {
+__device__ __forceinline__ void run_generic(const DevProblem *P_mem, const sk_tile *T_mem) {
   const DevProblem P = *P_mem;
   const sk_tile T = *T_mem;
   const int m_len = T.m_len, n_len = T.n_len;
@@ -1060,10 +1061,10 @@ __device__ void run_generic(const DevProblem *P_mem, const sk_tile *T_mem) {
 // one is touched (the unpacked elements of one stage fill the registers that
 // the packed pieces of a ring of stages would).  Any output rectangle is
 // walked in blocks of 128 x 128; a split reduction is done whole by the record
-// of its first slice.  Not inlined, like run_generic.
+// of its first slice.
 // ---------------------------------------------------------------------------
 template <int DT>
-__device__ __attribute__((noinline)) void run_tile_any(const DevProblem *P_mem, const sk_tile *T_mem,
+__device__ __forceinline__ void run_tile_any(const DevProblem *P_mem, const sk_tile *T_mem,
                                                        unsigned char *lds) {
   constexpr int ES = Elem<DT>::ES;
   constexpr int CE = 16 / ES;
