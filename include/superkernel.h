@@ -112,7 +112,8 @@ typedef struct {
   int32_t tail_div;       /* tiles shrink towards the end of the table: an operator's target */
                           /* is also capped by (weight bytes of it and of all operators      */
                           /* after it in execution order) / tail_div, so that the launch     */
-                          /* does not end on a few long tiles; 0 = off, default 384          */
+                          /* does not end on a few long tiles, but never below               */
+                          /* 8 * tile_bytes_min; 0 = off, default 384                        */
 } sk_plan_params;
 
 /*

@@ -141,7 +141,8 @@ def plan(problems: Sequence, prm: Params | None = None):
         if prm.tail_div > 0:
             # weight bytes of this operator and of all that execute after it
             remaining = sum(weight_bytes(problems[j]) for j in ordr[pos:])
-            T = max(prm.tile_bytes_min, min(T_all, remaining // prm.tail_div))
+            # never below eight times the lower clamp (unless the whole table's target is)
+            T = min(T_all, max(8 * prm.tile_bytes_min, remaining // prm.tail_div))
         cls, BM, BN, S, slice_len = tiling(p, T, prm)
         first[i] = len(recs)
         for m0 in range(0, mg, BM):

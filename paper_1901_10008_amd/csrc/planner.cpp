@@ -227,7 +227,11 @@ sk_status plan_host(const sk_problem *problems, int32_t n, const sk_plan_params 
     const int es = elem_size(out.problems[i].dtype);
     // towards the end of the table the target shrinks with what is left to do
     T = T_all;
-    if (prm.tail_div > 0) T = std::max<int64_t>(prm.tile_bytes_min, std::min<int64_t>(T_all, remaining[pos] / prm.tail_div));
+    // towards the end of the table the target shrinks with the bytes that remain, but not below eight
+    // times the lower clamp (tiles of a few dozen KB are all fixed cost, and a reduction cut to match
+    // them ends in dozens of slices)
+    if (prm.tail_div > 0)
+      T = std::min<int64_t>(T_all, std::max<int64_t>(8 * prm.tile_bytes_min, remaining[pos] / prm.tail_div));
     uint16_t cls;
     int64_t BM, BN;
     int64_t S = 1, slice_len = c.Kg;  // reduction slices per output rectangle and their length

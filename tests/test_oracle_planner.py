@@ -101,9 +101,18 @@ def test_hand_enumerated_tail_rule():
     # tail_div = 0 switches the rule off
     table, order, first, count = P.plan(ops, P.Params(tile_bytes_min=4096, tile_bytes_max=1 << 20, balance_div=16, tail_div=0))
     assert count == [8, 8, 8]
-    # never below the lower clamp
-    prm3 = P.Params(tile_bytes_min=1 << 19, tile_bytes_max=1 << 20, balance_div=1, tail_div=1 << 20)
+    # never below eight times the lower clamp: T_all = 1 MiB, the tail would ask for ~0, the floor is 8 * 64 KiB
+    prm3 = P.Params(tile_bytes_min=1 << 16, tile_bytes_max=1 << 20, balance_div=1, tail_div=1 << 20)
     assert P.plan(ops, prm3)[3] == [4, 4, 4]   # T = 512 KiB everywhere: G = 4 * (512 // 256) = 8 groups = 256 rows
+    # a table whose own target is below that floor does not shrink at all: T_all = 256 KiB -> 128-row tiles
+    prm4 = P.Params(tile_bytes_min=1 << 16, tile_bytes_max=1 << 18, balance_div=1, tail_div=1 << 20)
+    assert P.plan(ops, prm4)[3] == [8, 8, 8]
+    # with the defaults the floor is 256 KiB: the last operators of a large table are tiled for 256 KiB, not 32
+    many = [gemm(1, 2048, 4096) for _ in range(64)]   # 16 MiB each, 1 GiB in all: T_all = 2 MiB
+    t = P.decode(P.plan(many)[0])
+    last = [x for x in t if x["problem"] == 63]
+    # group = 32 * 4096 * 2 = 256 KiB; four groups exceed 256 KiB: reduction in 1 MiB / 256 KiB = 4 slices of 1024
+    assert len(last) == (2048 // 128) * 4 and {(x["n_len"], x["S"], x["k_len"]) for x in last} == {(128, 4, 1024)}
 
 
 def test_hand_enumerated_four_row_block_class():
