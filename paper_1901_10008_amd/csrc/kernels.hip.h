@@ -7,16 +7,20 @@
 // with both operands K-contiguous, so a 16-byte piece of a row is at the same
 // time one 128-bit load and one MFMA operand (8 halves or 4 floats of K).
 //
-// Two families of tile code:
+// Three families of tile code:
 //   * skinny (Mg <= 64): weights go HBM -> registers -> MFMA directly; the
 //     weight rows are the MFMA's row operand and the few activation rows its
 //     column operand, so a lane ends up with four consecutive output columns.
 //     Activations are staged through LDS.  The four waves of a workgroup take
 //     different 32-row weight groups; long reductions are split over several
 //     workgroups whose partial sums the last one to finish adds in fixed order.
-//   * LDS tiles (128x128): classic staged GEMM, global -> registers -> LDS ->
-//     32x32 MFMA; the activation operand may be gathered on the fly from an
-//     NHWC image (implicit GEMM for convolutions).
+//   * LDS tiles (128x128, or 128x64 for operators with at most 64 output
+//     columns): classic staged GEMM, global -> registers -> LDS -> 32x32 MFMA;
+//     the activation operand may be gathered on the fly from an NHWC image
+//     (implicit GEMM for convolutions, any stride).
+//   * operands that cannot be read in aligned 16-byte pieces: one output per
+//     thread for small rectangles, MFMA tiles assembled element by element for
+//     larger ones; only in the kernel instantiation for plans that need them.
 #pragma once
 
 #include <hip/hip_runtime.h>
