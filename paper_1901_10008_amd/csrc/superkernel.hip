@@ -115,6 +115,42 @@ class TablePool {
   size_t held_ = 0;
 };
 
+// Host staging for the upload of a table: pinned memory, kept per thread and grown on demand
+// (a copy from pageable memory goes through a staging buffer of the runtime's first).  Falls back
+// to pageable memory when pinned memory cannot be had.
+class HostStage {
+ public:
+  // `bytes` of staging memory (contents undefined), valid until the next call on this thread
+  char *acquire(size_t bytes) {
+    if (bytes > cap_) {
+      if (ptr_) (void)hipHostFree(ptr_);
+      ptr_ = nullptr;
+      cap_ = 0;
+      const size_t want = align_up(bytes + bytes / 2, (size_t)1 << 20);
+      void *p = nullptr;
+      if (hipHostMalloc(&p, want, hipHostMallocPortable) == hipSuccess) {
+        ptr_ = (char *)p;
+        cap_ = want;
+      } else {
+        (void)hipGetLastError();
+        try {
+          fallback_.assign(bytes, '\0');
+        } catch (const std::bad_alloc &) {
+          return nullptr;
+        }
+        return &fallback_[0];
+      }
+    }
+    return ptr_;
+  }
+
+ private:
+  char *ptr_ = nullptr;  // never freed at thread exit: the runtime may already be gone
+  size_t cap_ = 0;
+  std::string fallback_;
+};
+thread_local HostStage t_stage;
+
 TablePool &table_pool() {
   static TablePool *pool = new TablePool();  // never destroyed: the runtime may already be gone at exit
   return *pool;
@@ -172,12 +208,10 @@ sk_status upload_tables(const sk::HostPlan &hp, int device, DeviceTables &dt) {
   const size_t off_arrive = align_up(off_wsoff + nrect * sizeof(uint32_t), 256);
   const size_t upload = align_up(off_arrive + nrect * sizeof(uint32_t), 256);  // everything before the workspace
   const size_t total = upload + (size_t)hp.ws_f32x4 * 16;
-  std::string stage;
-  try {
-    stage.assign(upload, '\0');
-  } catch (const std::bad_alloc &) {
-    return set_error(SK_ERR_ALLOC, "host staging allocation failed");
-  }
+  char *stage = t_stage.acquire(upload);
+  if (!stage) return set_error(SK_ERR_ALLOC, "host staging allocation failed");
+  // the work records are written in full below; everything behind them starts at zero
+  std::memset(stage + nt * sizeof(sk::TileWork), 0, upload - nt * sizeof(sk::TileWork));
   if (nrect) std::memcpy(&stage[off_wsoff], hp.ws_off.data(), nrect * sizeof(uint32_t));
   for (size_t i = 0; i < nt; ++i) {
     sk::TileWork w;
@@ -195,7 +229,7 @@ sk_status upload_tables(const sk::HostPlan &hp, int device, DeviceTables &dt) {
     dt.blob = nullptr;
     return set_error(SK_ERR_ALLOC, std::string("hipMalloc: ") + hipGetErrorString(e));
   }
-  e = hipMemcpy(dt.blob, stage.data(), upload, hipMemcpyHostToDevice);
+  e = hipMemcpy(dt.blob, stage, upload, hipMemcpyHostToDevice);
   if (e != hipSuccess) {
     (void)table_pool().release(device, dt.blob, dt.blob_bytes);
     dt.blob = nullptr;
