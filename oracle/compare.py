@@ -18,6 +18,9 @@ TOL = {"f32": 1e-5, "bf16": 2e-2, "f16": 2e-2}
 # unit roundoff of the output format (round to nearest): 2^-p for p significand bits
 # (fp32: 24, fp16: 11, bf16: 8 = 7 stored + 1 implicit)
 _U_OUT = {"f32": 2.0 ** -24, "bf16": 2.0 ** -8, "f16": 2.0 ** -11}
+# half the spacing of the output format's subnormal numbers: the absolute rounding error of an
+# output below the smallest normal number (fp16: 2^-14), which u * |value| does not cover
+_HALF_SUBNORMAL = {"f32": 2.0 ** -150, "bf16": 2.0 ** -134, "f16": 2.0 ** -25}
 
 
 def errors(c, ref, mag=None):
@@ -43,11 +46,12 @@ def errors(c, ref, mag=None):
 
 
 def order_free_bound(ref, mag, K: int, dtype: str):
-    """|c - ref| <= gamma*mag + u_out*(|ref| + gamma*mag) for fp32 accumulation of K
-    exactly representable products in any order, followed by one rounding to the
-    output format.  gamma = (K+2)*2^-24 (first-order, slightly inflated)."""
+    """|c - ref| <= gamma*mag + max(u_out*(|ref| + gamma*mag), half the subnormal spacing) for fp32
+    accumulation of K exactly representable products in any order, followed by one rounding to
+    the output format (relative error u_out in the normal range, absolute error of half a
+    subnormal step below it).  gamma = (K+2)*2^-24 (first-order, slightly inflated)."""
     gamma = (K + 2) * 2.0 ** -24
     ref = np.abs(np.asarray(ref, dtype=np.float64))
     mag = np.asarray(mag, dtype=np.float64)
     acc = gamma * mag
-    return acc + _U_OUT[dtype] * (ref + acc) * 1.0000001 + 1e-300
+    return acc + np.maximum(_U_OUT[dtype] * (ref + acc) * 1.0000001, _HALF_SUBNORMAL[dtype]) + 1e-300

@@ -76,3 +76,28 @@ def test_unit_roundoff_of_each_output_format_is_attained_and_not_exceeded():
         rel = np.abs(v.astype(np.float64) - x) / np.abs(x)
         u = compare._U_OUT[dtype]
         assert rel.max() <= u and rel.max() > 0.9 * u / (1 + u), (dtype, rel.max(), u)
+
+
+def test_order_free_bound_covers_the_correctly_rounded_result_also_below_the_normal_range():
+    """The exact result rounded once to the output format must sit under the bound the parity tests use,
+    whatever its size: in the normal range the rounding error is u |x|, below it (fp16: |x| < 2^-14) it is
+    at most half the spacing of the subnormal numbers, which u |x| does not cover."""
+    from oracle import compare
+    g = np.random.default_rng(6)
+    # exact references over many magnitudes, many of them in fp16's subnormal range
+    ref = (g.standard_normal(200000) * np.exp(g.uniform(-18, 2, 200000))).astype(np.float32).astype(np.float64)
+    mag = np.abs(ref) * g.uniform(1.0, 3.0, ref.size)
+    for dtype in ("f16", "bf16", "f32"):
+        _, v = Q.round_to(dtype, ref.astype(np.float32))
+        err = np.abs(v.astype(np.float64) - ref)
+        assert not (err > compare.order_free_bound(ref, mag, 3, dtype)).any(), dtype
+    sub = np.abs(ref) < 2.0 ** -14
+    _, v = Q.round_to("f16", ref.astype(np.float32))
+    err = np.abs(v.astype(np.float64) - ref)
+    assert sub.sum() > 1000 and err[sub].max() > 0.9 * 2.0 ** -25 and err[sub].max() <= 2.0 ** -25
+    # ... and the relative part alone would not have covered them
+    assert (err[sub] > compare._U_OUT["f16"] * np.abs(ref[sub]) * 1.001).any()
+    # the example that showed it: a 1x1 convolution over 3 channels whose output is 1.32e-5 in fp16
+    r = np.array([1.32070854306221e-05]); m = np.array([4.2e-05])
+    _, v = Q.round_to("f16", r.astype(np.float32))
+    assert abs(float(v[0]) - r[0]) <= compare.order_free_bound(r, m, 3, "f16")[0]
