@@ -240,6 +240,32 @@ def test_launches_replayed_from_a_graph():
         del graphs
 
 
+def test_plans_running_concurrently_on_several_streams():
+    """The spatial-multiplexing baseline (Section 4.2): one plan per operator over several streams at once, and a
+    coalesced plan of other operators beside them.  Plans share nothing but read-only state, so every output is
+    the oracle's; plans are destroyed while later launches still run."""
+    specs = workloads.config(2, seed=7)[:10] + workloads.config(3, seed=0)[1:5] + workloads.config(4, seed=1)[:4]
+    b = H.Batch(specs, seed=12)
+    streams = [torch.cuda.Stream() for _ in range(4)]
+    for rep in range(3):
+        b.reset_outputs()
+        _sync()
+        singles = [sk.sk_plan_create([p], sk.sk_plan_params_default(stamps=rep % 2)) for p in b.problems[:12]]
+        rest = sk.sk_plan_create(b.problems[12:], sk.sk_plan_params_default(tile_bytes_min=8192, tile_bytes_max=8192))
+        for i, pl in enumerate(singles):
+            sk.sk_launch(pl, streams[i % 4].cuda_stream)
+        sk.sk_launch(rest, H.stream_handle())
+        for i, pl in enumerate(singles):
+            if i % 3 == 0:     # a second launch of the same plan: behind the first one, on its stream
+                sk.sk_launch_sequential(pl, streams[i % 4].cuda_stream)
+        for pl in singles[::2]:
+            pl.close()          # waits for that plan's own launches only
+        _sync()
+        for pl in singles[1::2] + [rest]:
+            pl.close()
+        H.check_against_oracle(b, f"concurrent streams round {rep}")
+
+
 def test_single_and_empty_plans():
     run_all_modes([g(1, 64, 64)], seed=3, label="single")
     with sk.sk_plan_create([], None) as plan:
