@@ -68,3 +68,79 @@ def test_config5_full_size_sampled():
         assert not (np.abs(got - ref) > compare.order_free_bound(ref, mag, kg, s.dtype)).any(), (i, s, e)
         worst = max(worst, e["gate"])
     print("config 5 full size: worst sampled gate error", worst)
+
+
+def _rows_around(limit_row, last):
+    """Row indices next to the first row whose byte offset passes 4 GiB, plus both ends."""
+    near = [limit_row - 1, limit_row, limit_row + 1]
+    return [r for r in [0, 1, *near, last - 1, last] if 0 <= r <= last]
+
+
+def test_operands_larger_than_4_gib():
+    """Activations, weights and outputs of more than 4 GiB each: element offsets do not fit 32
+    bits.  One tall GEMM (LDS-tiled), one wide weight-streaming GEMM and one batched 3x3
+    convolution share a plan with two small operators; outputs are sampled on both sides of the
+    4 GiB line of every large buffer and at both ends."""
+    from workloads import Problem
+
+    four_gib = 1 << 32
+    specs = [
+        Problem(op="gemm", dtype="bf16", M=5_000_011, N=512, K=520, a_dist=("normal", 1.0), b_dist=("normal", 0.04)),
+        Problem(op="gemm", dtype="bf16", M=4, N=5_000_008, K=520, a_dist=("normal", 1.0), b_dist=("normal", 0.04)),
+        Problem(op="conv", dtype="bf16", Nb=40, H=1024, W=1024, Cin=64, Cout=64, R=3, S=3, pad_h=1, pad_w=1,
+                a_dist=("uniform", 0.0, 1.0), b_dist=("normal", 0.06)),
+        Problem(op="gemm", dtype="bf16", M=8, N=1000, K=2048, a_dist=("normal", 1.0), b_dist=("normal", 0.02)),
+        Problem(op="gemm", dtype="f32", M=3, N=77, K=129, a_dist=("normal", 1.0), b_dist=("normal", 0.1)),
+    ]
+    b = H.Batch(specs, seed=11, host_draw=False)
+    g = np.random.default_rng(7)
+    with b.plan() as plan:
+        sk.sk_launch(plan, H.stream_handle())
+        torch.cuda.synchronize()
+    dev = lambda idx: torch.as_tensor(np.asarray(idx), device="cuda")
+    views = []
+    for i, s in enumerate(specs):
+        rows, cols, ldc, off = b.c_meta[i]
+        real = torch.float32 if s.dtype == "f32" else torch.bfloat16
+        out = b.c_bufs[i][off: off + rows * ldc].view(real).view(rows, ldc)[:, :cols]
+        assert not torch.isnan(out).any(), f"operator {i}: output not fully written"
+        views.append(out)
+
+    def check(i, got, ref, mag, what):
+        s = specs[i]
+        got = got.float().cpu().numpy().astype(np.float64).reshape(ref.shape)
+        e = compare.errors(got, ref, mag)
+        assert e["gate"] <= compare.TOL[s.dtype], (what, e)
+        assert not (np.abs(got - ref) > compare.order_free_bound(ref, mag, H.kg_of(s), s.dtype)).any(), (what, e)
+
+    # tall GEMM: rows of A pass 4 GiB at 2^32 / (K * 2), rows of C at 2^32 / (N * 2)
+    s = specs[0]
+    ms = np.unique(np.concatenate([_rows_around(four_gib // (s.K * 2), s.M - 1), _rows_around(four_gib // (s.N * 2), s.M - 1),
+                                   g.integers(0, s.M, size=24)]))
+    ref, mag = R.gemm(b.dA[0][dev(ms)].float().cpu().numpy(), b.dB[0].float().cpu().numpy(), want_mag=True)
+    check(0, views[0][dev(ms)], ref, mag, "tall GEMM")
+    # wide GEMM: rows of the weights pass 4 GiB at 2^32 / (K * 2)
+    s = specs[1]
+    ns = np.unique(np.concatenate([_rows_around(four_gib // (s.K * 2), s.N - 1), g.integers(0, s.N, size=120)]))
+    ref, mag = R.gemm(b.dA[1].float().cpu().numpy(), b.dB[1][dev(ns)].float().cpu().numpy(), want_mag=True)
+    check(1, views[1][:, dev(ns)], ref, mag, "wide GEMM")
+    # convolution: bands of four output rows; the image rows they read are copied with a zero row
+    # where the band touches the padding, so the oracle runs with no padding in that direction
+    s = specs[2]
+    Wt = b.dB[2].float().cpu().numpy()
+    X = b.dA[2]
+    image_bytes = s.H * s.W * s.Cin * 2
+    out4 = views[2].view(s.Nb, s.H, s.W, s.Cout)  # same size output: 3x3, padding 1, stride 1
+    for img, h0 in [(0, 0), (four_gib // image_bytes, 0), (four_gib // image_bytes - 1, s.H - 4),
+                    (int(g.integers(0, s.Nb)), int(g.integers(1, s.H - 5))), (s.Nb - 1, s.H - 4)]:
+        lo, hi = h0 - 1, h0 + 5  # input rows [lo, hi) feed output rows h0 .. h0+3
+        band = torch.zeros((1, hi - lo, s.W, s.Cin), dtype=torch.float32, device="cuda")
+        a, z = max(lo, 0), min(hi, s.H)
+        band[0, a - lo: z - lo] = X[img, a:z].float()
+        Y, Sm = R.conv2d_nhwc(band.cpu().numpy(), Wt, 0, s.pad_w, want_mag=True)
+        assert Y.shape == (1, 4, s.W, s.Cout)
+        check(2, out4[img, h0: h0 + 4], Y[0], Sm[0], f"convolution image {img} rows {h0}..{h0 + 3}")
+    # the two small operators, in full
+    for i in (3, 4):
+        ref, mag = R.gemm(b.dA[i].float().cpu().numpy(), b.dB[i].float().cpu().numpy(), want_mag=True)
+        check(i, views[i], ref, mag, f"small operator {i}")
