@@ -91,6 +91,9 @@ def test_operands_larger_than_4_gib():
                 a_dist=("uniform", 0.0, 1.0), b_dist=("normal", 0.06)),
         Problem(op="gemm", dtype="bf16", M=8, N=1000, K=2048, a_dist=("normal", 1.0), b_dist=("normal", 0.02)),
         Problem(op="gemm", dtype="f32", M=3, N=77, K=129, a_dist=("normal", 1.0), b_dist=("normal", 0.1)),
+        # rows of an odd length cannot be read in 16-byte pieces: the element-wise paths
+        Problem(op="gemm", dtype="bf16", M=4_200_003, N=40, K=521, a_dist=("normal", 1.0), b_dist=("normal", 0.04)),
+        Problem(op="gemm", dtype="bf16", M=3, N=4_200_001, K=521, a_dist=("normal", 1.0), b_dist=("normal", 0.04)),
     ]
     b = H.Batch(specs, seed=11, host_draw=False)
     g = np.random.default_rng(7)
@@ -112,6 +115,7 @@ def test_operands_larger_than_4_gib():
         e = compare.errors(got, ref, mag)
         assert e["gate"] <= compare.TOL[s.dtype], (what, e)
         assert not (np.abs(got - ref) > compare.order_free_bound(ref, mag, H.kg_of(s), s.dtype)).any(), (what, e)
+        print(f"{what}: {got.size} outputs sampled, gate error {e['gate']:.2e}")
 
     # tall GEMM: rows of A pass 4 GiB at 2^32 / (K * 2), rows of C at 2^32 / (N * 2)
     s = specs[0]
@@ -140,6 +144,14 @@ def test_operands_larger_than_4_gib():
         Y, Sm = R.conv2d_nhwc(band.cpu().numpy(), Wt, 0, s.pad_w, want_mag=True)
         assert Y.shape == (1, 4, s.W, s.Cout)
         check(2, out4[img, h0: h0 + 4], Y[0], Sm[0], f"convolution image {img} rows {h0}..{h0 + 3}")
+    s = specs[5]
+    ms = np.unique(np.concatenate([_rows_around(four_gib // (s.K * 2), s.M - 1), g.integers(0, s.M, size=24)]))
+    ref, mag = R.gemm(b.dA[5][dev(ms)].float().cpu().numpy(), b.dB[5].float().cpu().numpy(), want_mag=True)
+    check(5, views[5][dev(ms)], ref, mag, "tall GEMM, odd row length")
+    s = specs[6]
+    ns = np.unique(np.concatenate([_rows_around(four_gib // (s.K * 2), s.N - 1), g.integers(0, s.N, size=120)]))
+    ref, mag = R.gemm(b.dA[6].float().cpu().numpy(), b.dB[6][dev(ns)].float().cpu().numpy(), want_mag=True)
+    check(6, views[6][:, dev(ns)], ref, mag, "wide GEMM, odd row length")
     # the two small operators, in full
     for i in (3, 4):
         ref, mag = R.gemm(b.dA[i].float().cpu().numpy(), b.dB[i].float().cpu().numpy(), want_mag=True)
