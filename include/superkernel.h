@@ -30,6 +30,9 @@
  *     caller (NULL = the default stream).  Launches are asynchronous.
  *   - A plan has one work counter: two launches of the SAME plan must not be in
  *     flight at the same time (launching it again on the same stream is fine).
+ *   - Host threads: any number of threads may call into the library at the same
+ *     time, each on plans of its own; calls that name the same plan are
+ *     serialised by the caller.
  */
 #ifndef SUPERKERNEL_H
 #define SUPERKERNEL_H

@@ -266,6 +266,52 @@ def test_plans_running_concurrently_on_several_streams():
         H.check_against_oracle(b, f"concurrent streams round {rep}")
 
 
+def test_host_threads_plan_and_launch_side_by_side():
+    """Serving threads each plan, launch and destroy their own plans (own stream, own operators) at the
+    same time: the table pool is shared, the upload staging and the error string are per thread."""
+    import threading
+
+    nthreads, rounds = 4, 6
+    batches = [H.Batch(workloads.config(2, seed=20 + t)[:6] + workloads.config(3, seed=0)[t: t + 2], seed=30 + t)
+               for t in range(nthreads)]
+    reference_tables = []
+    for b in batches:
+        with b.plan(host_only=1) as plan:
+            reference_tables.append(sk.sk_plan_get_tiles(plan))
+    errors = []
+
+    def serve(t):
+        try:
+            torch.cuda.set_device(0)
+            stream = torch.cuda.Stream()
+            b = batches[t]
+            for r in range(rounds):
+                with sk.sk_plan_create(b.problems, sk.sk_plan_params_default(stamps=r % 2)) as plan:
+                    assert sk.sk_plan_get_tiles(plan) == reference_tables[t]
+                    if r % 3 == 2:
+                        sk.sk_launch_sequential(plan, stream.cuda_stream)
+                    else:
+                        sk.sk_launch(plan, stream.cuda_stream)
+                    if r % 2:
+                        stream.synchronize()
+                with pytest.raises(sk.SkError) as bad:   # an error in one thread: its own detail string
+                    sk.sk_plan_create([sk.make_problem(Problem(op="gemm", dtype="bf16", M=t + 1, N=8, K=8), 0, 0, 0)])
+                assert "null" in bad.value.detail
+            stream.synchronize()
+        except BaseException as e:  # noqa: BLE001 -- reported by the main thread
+            errors.append((t, repr(e)))
+
+    threads = [threading.Thread(target=serve, args=(t,)) for t in range(nthreads)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    assert not errors, errors
+    _sync()
+    for t, b in enumerate(batches):
+        H.check_against_oracle(b, f"thread {t}")
+
+
 def test_single_and_empty_plans():
     run_all_modes([g(1, 64, 64)], seed=3, label="single")
     with sk.sk_plan_create([], None) as plan:
