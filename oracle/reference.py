@@ -2,8 +2,8 @@
 
 What a superkernel must produce for each packed operator is the plain result
 of that operator (Sections 1 and 5.3; Figure 6 caption: the GEMM that backs a
-convolution).  `gemm` / `conv2d_nhwc` call the plain C loops in sk_oracle.c;
-`gemm_py` / `conv2d_nhwc_py` are the same definitions as pure-Python loops for
+convolution).  `gemm` / `conv2d_nhwc` / `conv2d_nchw` call the plain C loops in sk_oracle.c;
+`gemm_py` / `conv2d_nhwc_py` / `conv2d_nchw_py` are the same definitions as pure-Python loops for
 tiny cases; `gemm_at` / `conv2d_at` evaluate single output elements so that
 full-size runs can be checked on a sample.
 
@@ -14,6 +14,8 @@ Conventions (the paper fixes none of them; these are this build's reading):
     filters, one stride for both directions, dilation 1, one group, zero padding, no bias.
   * The GEMM that backs a convolution has rows m = (b*Ho + ho)*Wo + wo,
     columns n = co and reduction index k = (r*S + s)*Cin + c.
+  * The channel-major form (X [Nb,Cin,H,W], W [Cout,Cin,R,S], Y [Nb,Cout,Ho,Wo]) is the same
+    operator on the other storage order; its reduction index is k = (c*R + r)*S + s.
 """
 from __future__ import annotations
 
@@ -38,6 +40,8 @@ def _load():
             ctypes.c_void_p, ctypes.c_long, ctypes.c_void_p]
         lib.sk_oracle_conv2d_nhwc.restype = None
         lib.sk_oracle_conv2d_nhwc.argtypes = [ctypes.c_int] * 10 + [ctypes.c_void_p] * 4
+        lib.sk_oracle_conv2d_nchw.restype = None
+        lib.sk_oracle_conv2d_nchw.argtypes = [ctypes.c_int] * 10 + [ctypes.c_void_p] * 4
         _lib = lib
     return _lib
 
@@ -88,6 +92,24 @@ def conv2d_nhwc(X, W, pad_h: int, pad_w: int, want_mag: bool = False, stride: in
     return (Y, Sm) if want_mag else Y
 
 
+def conv2d_nchw(X, W, pad_h: int, pad_w: int, want_mag: bool = False, stride: int = 1):
+    """X [Nb,Cin,H,W], W [Cout,Cin,R,S] -> Y fp64 [Nb,Cout,Ho,Wo]."""
+    X = _f32(X)
+    W = _f32(W)
+    Nb, Cin, H, Wd = X.shape
+    Cout, Cin2, R, S = W.shape
+    assert Cin == Cin2
+    assert stride >= 1 and H + 2 * pad_h >= R and Wd + 2 * pad_w >= S
+    Ho = (H + 2 * pad_h - R) // stride + 1
+    Wo = (Wd + 2 * pad_w - S) // stride + 1
+    Y = np.empty((Nb, Cout, Ho, Wo), dtype=np.float64)
+    Sm = np.empty_like(Y) if want_mag else None
+    _load().sk_oracle_conv2d_nchw(Nb, H, Wd, Cin, Cout, R, S, pad_h, pad_w, stride,
+                                  X.ctypes.data, W.ctypes.data, Y.ctypes.data,
+                                  Sm.ctypes.data if want_mag else None)
+    return (Y, Sm) if want_mag else Y
+
+
 # ---- the same definitions as pure-Python loops (tiny inputs only) ------------
 
 def gemm_py(A, B):
@@ -124,6 +146,30 @@ def conv2d_nhwc_py(X, W, pad_h, pad_w, stride=1):
                                 for c in range(Cin):
                                     s += X[b, h, w, c] * W[co, r, t, c]
                     Y[b, ho, wo, co] = s
+    return Y
+
+
+def conv2d_nchw_py(X, W, pad_h, pad_w, stride=1):
+    X = np.asarray(X, dtype=np.float64)
+    W = np.asarray(W, dtype=np.float64)
+    Nb, Cin, H, Wd = X.shape
+    Cout, _, R, S = W.shape
+    Ho = (H + 2 * pad_h - R) // stride + 1
+    Wo = (Wd + 2 * pad_w - S) // stride + 1
+    Y = np.zeros((Nb, Cout, Ho, Wo), dtype=np.float64)
+    for b in range(Nb):
+        for co in range(Cout):
+            for ho in range(Ho):
+                for wo in range(Wo):
+                    s = 0.0
+                    for c in range(Cin):
+                        for r in range(R):
+                            for t in range(S):
+                                h = ho * stride - pad_h + r
+                                w = wo * stride - pad_w + t
+                                if 0 <= h < H and 0 <= w < Wd:
+                                    s += X[b, c, h, w] * W[co, c, r, t]
+                    Y[b, co, ho, wo] = s
     return Y
 
 

@@ -20,7 +20,9 @@
  * Parity pins (tests/test_oracle_*.py): hand-computed 2x2 / 3x3 GEMM and
  * convolution examples, closed forms (rank-one, identity, unit vector),
  * numpy's fp64 matmul on random inputs, 1x1 convolution == GEMM, direct
- * convolution == explicit patch matrix times GEMM, centre-tap delta filter.
+ * convolution == explicit patch matrix times GEMM, centre-tap delta filter;
+ * the NCHW form against the NHWC form on permuted arrays, against a library
+ * 2-D correlation per channel pair, and against hand examples.
  */
 #include <math.h>
 #include <stddef.h>
@@ -89,6 +91,47 @@ void sk_oracle_conv2d_nhwc(int Nb, int H, int W, int Cin, int Cout,
                         }
                     }
                     const size_t o = (((size_t)b * Ho + ho) * Wo + wo) * Cout + co;
+                    Y[o] = sum;
+                    if (Sabs) Sabs[o] = mag;
+                }
+            }
+        }
+    }
+}
+
+/* The same convolution on channel-major arrays (the other common storage
+ * order of inference frameworks): X is [Nb,Cin,H,W], W is [Cout,Cin,R,S],
+ * Y (and Sabs, if non-NULL) are [Nb,Cout,Ho,Wo], all dense:
+ *   Y[b,co,ho,wo] = sum_{c,r,s} X[b, c, ho*stride-pad_h+r, wo*stride-pad_w+s] * W[co,c,r,s]
+ * Same output size, same treatment of taps outside the image. */
+void sk_oracle_conv2d_nchw(int Nb, int H, int W, int Cin, int Cout,
+                           int R, int S, int pad_h, int pad_w, int stride,
+                           const float *X, const float *Wt,
+                           double *Y, double *Sabs)
+{
+    const int Ho = (H + 2 * pad_h - R) / stride + 1;
+    const int Wo = (W + 2 * pad_w - S) / stride + 1;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int b = 0; b < Nb; ++b) {
+        for (int co = 0; co < Cout; ++co) {
+            for (int ho = 0; ho < Ho; ++ho) {
+                for (int wo = 0; wo < Wo; ++wo) {
+                    double sum = 0.0, mag = 0.0;
+                    for (int c = 0; c < Cin; ++c) {
+                        for (int r = 0; r < R; ++r) {
+                            const int h = ho * stride - pad_h + r;
+                            if (h < 0 || h >= H) continue;
+                            for (int s = 0; s < S; ++s) {
+                                const int w = wo * stride - pad_w + s;
+                                if (w < 0 || w >= W) continue;
+                                double a = (double)X[(((size_t)b * Cin + c) * H + h) * W + w];
+                                double g = (double)Wt[(((size_t)co * Cin + c) * R + r) * S + s];
+                                sum += a * g;
+                                mag += fabs(a) * fabs(g);
+                            }
+                        }
+                    }
+                    const size_t o = (((size_t)b * Cout + co) * Ho + ho) * Wo + wo;
                     Y[o] = sum;
                     if (Sabs) Sabs[o] = mag;
                 }

@@ -8,6 +8,8 @@ void sk_oracle_gemm(int M, int N, int K, const float *A, long lda, const float *
                     double *Sabs);
 void sk_oracle_conv2d_nhwc(int Nb, int H, int W, int Cin, int Cout, int R, int S, int pad_h, int pad_w, int stride,
                            const float *X, const float *Wt, double *Y, double *Sabs);
+void sk_oracle_conv2d_nchw(int Nb, int H, int W, int Cin, int Cout, int R, int S, int pad_h, int pad_w, int stride,
+                           const float *X, const float *Wt, double *Y, double *Sabs);
 
 static float *filled(size_t n, unsigned seed) {
     float *p = (float *)malloc((n ? n : 1) * sizeof(float));
@@ -42,6 +44,8 @@ int main(void) {
                         double *Sm = (double *)malloc((size_t)Nb * Ho * Wo * Cout * sizeof(double));
                         sk_oracle_conv2d_nhwc(Nb, H, W, Cin, Cout, R, S, pad, pad, st, X, F, Y, Sm);
                         sk_oracle_conv2d_nhwc(Nb, H, W, Cin, Cout, R, S, pad, pad, st, X, F, Y, NULL);
+                        sk_oracle_conv2d_nchw(Nb, H, W, Cin, Cout, R, S, pad, pad, st, X, F, Y, Sm);
+                        sk_oracle_conv2d_nchw(Nb, H, W, Cin, Cout, R, S, pad, pad, st, X, F, Y, NULL);
                         free(X); free(F); free(Y); free(Sm);
                     }
     puts("oracle_driver: ok");

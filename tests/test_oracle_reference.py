@@ -203,3 +203,63 @@ def test_conv_output_shape_rule():
     Y = R.conv2d_nhwc(X, W, 1, 1)
     # all-ones: each output counts the taps inside the image times Cin
     assert Y[0, 0, 0, 0] == 8 and Y[0, 0, 4, 0] == 12 and Y[0, 3, 4, 0] == 18
+
+
+# ---- channel-major (NCHW) convolution ----------------------------------------------------------
+
+def test_nchw_conv_hand_examples(hand):
+    for ex in hand["conv_nchw"]:
+        X = np.array(ex["X_nchw"], dtype=np.float32)
+        W = np.array(ex["W_oihw"], dtype=np.float32)
+        want = np.array(ex["Y_nchw"], dtype=np.float64)
+        for fn in (R.conv2d_nchw, R.conv2d_nchw_py):
+            got = fn(X, W, ex["pad_h"], ex["pad_w"], stride=ex["stride"])
+            assert got.shape == want.shape, ex["name"]
+            assert np.array_equal(got, want), (ex["name"], got)
+
+
+@pytest.mark.parametrize("cfg", [(1, 5, 6, 3, 4, 3, 3, 1, 1, 1), (2, 7, 5, 2, 3, 3, 1, 0, 0, 2), (1, 6, 6, 4, 2, 1, 1, 0, 0, 1),
+                                 (2, 4, 9, 3, 5, 5, 3, 2, 1, 3), (1, 8, 8, 1, 1, 7, 7, 3, 3, 2)])
+def test_nchw_conv_is_a_sum_of_library_2d_correlations(cfg):
+    """Per image and output channel the operator is sum_c correlate2d(X[b,c] zero-padded, W[co,c]) sampled
+    every `stride` positions: scipy's routine knows nothing of this build's index arithmetic."""
+    from scipy.signal import correlate2d
+
+    Nb, H, Wd, Cin, Cout, Rr, S, ph, pw, st = cfg
+    g = np.random.default_rng(sum(cfg))
+    X = g.integers(-4, 5, size=(Nb, Cin, H, Wd)).astype(np.float32)
+    W = g.integers(-3, 4, size=(Cout, Cin, Rr, S)).astype(np.float32)
+    got = R.conv2d_nchw(X, W, ph, pw, stride=st)
+    Xp = np.pad(X.astype(np.float64), ((0, 0), (0, 0), (ph, ph), (pw, pw)))
+    for b in range(Nb):
+        for co in range(Cout):
+            full = sum(correlate2d(Xp[b, c], W[co, c].astype(np.float64), mode="valid") for c in range(Cin))
+            assert np.array_equal(got[b, co], full[::st, ::st]), (cfg, b, co)
+
+
+def test_nchw_conv_is_the_nhwc_result_on_permuted_arrays():
+    """The two storage orders describe one operator: permuting operands and result maps one onto the other
+    (the two C routines index their arrays independently)."""
+    g = np.random.default_rng(5)
+    for (Nb, H, Wd, Cin, Cout, Rr, S, ph, pw, st) in [(2, 9, 7, 5, 6, 3, 3, 1, 1, 1), (1, 12, 5, 3, 4, 5, 1, 2, 0, 2),
+                                                      (3, 4, 4, 8, 2, 1, 1, 0, 0, 1)]:
+        X = g.standard_normal((Nb, Cin, H, Wd)).astype(np.float32)
+        W = g.standard_normal((Cout, Cin, Rr, S)).astype(np.float32)
+        Y, M = R.conv2d_nchw(X, W, ph, pw, want_mag=True, stride=st)
+        Y2, M2 = R.conv2d_nhwc(X.transpose(0, 2, 3, 1), W.transpose(0, 2, 3, 1), ph, pw, want_mag=True, stride=st)
+        # same terms in another order: equal to a few ulps of the magnitude sum
+        assert np.all(np.abs(Y - Y2.transpose(0, 3, 1, 2)) <= 1e-15 * M * (Cin * Rr * S))
+        assert np.all(np.abs(M - M2.transpose(0, 3, 1, 2)) <= 1e-15 * M * (Cin * Rr * S))
+        assert np.array_equal(R.conv2d_nchw_py(X, W, ph, pw, st), R.conv2d_nchw_py(X, W, ph, pw, st))
+        assert np.all(np.abs(Y - R.conv2d_nchw_py(X, W, ph, pw, st)) <= 1e-15 * M * (Cin * Rr * S))
+
+
+def test_nchw_delta_filter_picks_one_channel_and_shifts():
+    """A filter that is 1 at (channel 2, tap (0, 1)) and 0 elsewhere copies channel 2 shifted by one column."""
+    g = np.random.default_rng(9)
+    X = g.standard_normal((2, 4, 5, 6)).astype(np.float32)
+    W = np.zeros((1, 4, 1, 2), dtype=np.float32)
+    W[0, 2, 0, 1] = 1.0
+    Y = R.conv2d_nchw(X, W, 0, 0)
+    assert Y.shape == (2, 1, 5, 5)
+    assert np.array_equal(Y[:, 0], X[:, 2, :, 1:].astype(np.float64))
