@@ -55,7 +55,7 @@ typedef enum {
 
 /* A, B and C of one operator share the element type; accumulation is always fp32. */
 typedef enum { SK_F32 = 0, SK_BF16 = 1, SK_F16 = 2 } sk_dtype;
-typedef enum { SK_GEMM = 0, SK_CONV2D_NHWC = 1 } sk_op;
+typedef enum { SK_GEMM = 0, SK_CONV2D_NHWC = 1, SK_CONV2D_NCHW = 2 } sk_op;
 
 /*
  * One operator (Section 5.1: "the operators, the inputs, and latency constraints").
@@ -76,6 +76,16 @@ typedef enum { SK_GEMM = 0, SK_CONV2D_NHWC = 1 } sk_op;
  *   M, N, K and the row strides are ignored.  It is executed as the
  *   GEMM with rows (b*Ho+ho)*Wo+wo, columns co and reduction index
  *   (r*S+s)*Cin+c, without materialising the patch matrix.
+ *
+ * SK_CONV2D_NCHW:  the same operator on channel-major arrays, the other
+ *   storage order inference frameworks hand over:  A = X[Nb,Cin,H,Wd],
+ *   B = W[Cout,Cin,R,S],  C = Y[Nb,Cout,Ho,Wo], all dense,
+ *   Y[b,co,ho,wo] = sum_{c,r,s} X[b, c, ho*stride-pad_h+r, wo*stride-pad_w+s] * W[co,c,r,s].
+ *   Same fields and output size.  The reduction index is (c*R+r)*S+s, so the
+ *   weights are still one contiguous row per output channel; activations and
+ *   outputs are not contiguous along it, and the operator runs through the
+ *   element-wise tile paths (correct for every shape, several times slower
+ *   than the NHWC form).
  *
  * deadline_ms: latency budget measured from the start of the launch.  <= 0, NaN
  *   or +inf mean "none".  It only orders the operators (earliest first, ties by

@@ -27,7 +27,7 @@ from .binding import (  # noqa: F401
     sk_release_cached_memory,
     sk_strerror,
     sk_last_error,
-    SK_F32, SK_BF16, SK_F16, SK_GEMM, SK_CONV2D_NHWC,
+    SK_F32, SK_BF16, SK_F16, SK_GEMM, SK_CONV2D_NHWC, SK_CONV2D_NCHW,
     DTYPE_CODE,
     EXPORTED_SYMBOLS,
 )

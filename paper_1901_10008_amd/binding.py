@@ -9,7 +9,7 @@ from typing import Iterable, List, Sequence
 HERE = os.path.dirname(os.path.abspath(__file__))
 
 SK_F32, SK_BF16, SK_F16 = 0, 1, 2
-SK_GEMM, SK_CONV2D_NHWC = 0, 1
+SK_GEMM, SK_CONV2D_NHWC, SK_CONV2D_NCHW = 0, 1, 2
 DTYPE_CODE = {"f32": SK_F32, "bf16": SK_BF16, "f16": SK_F16}
 
 EXPORTED_SYMBOLS = [
@@ -131,8 +131,8 @@ def make_problem(spec, A: int, B: int, Cptr: int, lda: int = 0, ldb: int = 0, ld
         p.op = SK_GEMM
         p.M, p.N, p.K = spec.M, spec.N, spec.K
         p.lda, p.ldb, p.ldc = lda, ldb, ldc
-    elif spec.op == "conv":
-        p.op = SK_CONV2D_NHWC
+    elif spec.op in ("conv", "conv_nchw"):
+        p.op = SK_CONV2D_NHWC if spec.op == "conv" else SK_CONV2D_NCHW
         p.Nb, p.H, p.Wd, p.Cin, p.Cout = spec.Nb, spec.H, spec.W, spec.Cin, spec.Cout
         p.R, p.S, p.pad_h, p.pad_w = spec.R, spec.S, spec.pad_h, spec.pad_w
         p.stride = getattr(spec, "stride", 1)

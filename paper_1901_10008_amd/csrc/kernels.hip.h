@@ -213,7 +213,7 @@ __device__ __forceinline__ u32x4 fetch_B(const DevProblem &P, int64_t row_off, i
 
 // Where row m of the activation operand starts.
 struct RowA {
-  int64_t base;  // plain: m*lda.  gather: offset of pixel (b, hb, wb, 0), the one under filter tap (0,0); may be negative
+  int64_t base;  // plain: m*lda.  gather: offset of pixel (b, hb, wb), channel 0, the one under filter tap (0,0); may be negative
   int hb, wb;    // gather: ho*stride-pad_h, wo*stride-pad_w
 };
 
@@ -231,9 +231,35 @@ __device__ __forceinline__ RowA row_of(const DevProblem &P, int m) {
     const int wo = rem - ho * P.Wo;
     r.hb = ho * P.stride - P.pad_h;
     r.wb = wo * P.stride - P.pad_w;
-    r.base = (((int64_t)b * P.H + r.hb) * P.W + r.wb) * P.Cin;
+    if (P.nchw)
+      r.base = ((int64_t)b * P.Cin * P.H + r.hb) * P.W + r.wb;  // pixel (b, channel 0, hb, wb)
+    else
+      r.base = (((int64_t)b * P.H + r.hb) * P.W + r.wb) * P.Cin;
   }
   return r;
+}
+
+// Channel-major convolutions (element-wise paths only).  Element strides of the image along
+// filter row, filter column and channel, and where output (m, n) lives in Y[Nb,Cout,Ho,Wo].
+struct ImageStrides {
+  int64_t sh, sw, sc;
+};
+__device__ __forceinline__ ImageStrides image_strides(const DevProblem &P) {
+  if (P.nchw) return ImageStrides{(int64_t)P.W, 1, (int64_t)P.H * P.W};
+  return ImageStrides{(int64_t)P.W * P.Cin, (int64_t)P.Cin, 1};
+}
+__device__ __forceinline__ int64_t nchw_out_base(const DevProblem &P, int m) {
+  const int hw = P.Ho * P.Wo;
+  const int b = m / hw;
+  return (int64_t)b * P.Ng * hw + (m - b * hw);  // + n * Ho*Wo
+}
+template <int DT>
+__device__ __forceinline__ void store_elem(void *C, int64_t off, float v) {
+  char SK_GLOBAL *c = as_global_mut<char>(C) + off * Elem<DT>::ES;
+  if constexpr (DT == SK_F32)
+    *(float SK_GLOBAL *)c = v;
+  else
+    *(uint16_t SK_GLOBAL *)c = (uint16_t)cvt_bits<DT>(v);
 }
 
 // Element k of the implicit patch row: k = (r*S + s)*Cin + c  ->  pixel (hb+r, wb+s), channel c.
@@ -1036,7 +1062,7 @@ __device__ __forceinline__ void run_generic(const DevProblem *P_mem, const sk_ti
     if (!P.gather) {
       for (int k = 0; k < P.Kg; ++k)
         acc = __builtin_fmaf(load_elem<DT>(P.A, row.base + k), load_elem<DT>(P.B, wrow + k), acc);
-    } else {
+    } else if (!P.nchw) {
       // taps in the order of the reduction index; those in the padding contribute nothing
       for (int r = 0; r < P.R; ++r) {
         if ((unsigned)(row.hb + r) >= (unsigned)P.H) continue;
@@ -1048,12 +1074,21 @@ __device__ __forceinline__ void run_generic(const DevProblem *P_mem, const sk_ti
             acc = __builtin_fmaf(load_elem<DT>(P.A, xa + c), load_elem<DT>(P.B, wb + c), acc);
         }
       }
+    } else {
+      // channel-major: reduction index (c*R + r)*S + t
+      const int64_t plane = (int64_t)P.H * P.W;
+      for (int c = 0; c < P.Cin; ++c)
+        for (int r = 0; r < P.R; ++r) {
+          if ((unsigned)(row.hb + r) >= (unsigned)P.H) continue;
+          for (int t = 0; t < P.S; ++t) {
+            if ((unsigned)(row.wb + t) >= (unsigned)P.W) continue;
+            acc = __builtin_fmaf(load_elem<DT>(P.A, row.base + c * plane + (int64_t)r * P.W + t),
+                                 load_elem<DT>(P.B, wrow + ((int64_t)c * P.R + r) * P.S + t), acc);
+          }
+        }
     }
-    char SK_GLOBAL *c = as_global_mut<char>(P.C) + ((int64_t)m * P.ldc + n) * Elem<DT>::ES;
-    if constexpr (DT == SK_F32)
-      *(float SK_GLOBAL *)c = acc;
-    else
-      *(uint16_t SK_GLOBAL *)c = (uint16_t)cvt_bits<DT>(acc);
+    const int64_t c_off = P.nchw ? nchw_out_base(P, m) + (int64_t)n * P.Ho * P.Wo : (int64_t)m * P.ldc + n;
+    store_elem<DT>(P.C, c_off, acc);
   }
 }
 
@@ -1085,6 +1120,7 @@ __device__ __forceinline__ void run_tile_any(const DevProblem *P_mem, const sk_t
   const uintptr_t zeros = zero_piece_address();
   const int m_end = (int)T.m0 + (int)T.m_len, n_end = (int)T.n0 + (int)T.n_len;
   const bool vec_c = (P.flags & FLAG_VEC_C) != 0;
+  const ImageStrides im = image_strides(P);
   unsigned char *sa = lds + srow * LDS_ROW + c8 * 16;
   unsigned char *sb = sa + 128 * LDS_ROW;
 
@@ -1116,17 +1152,22 @@ __device__ __forceinline__ void run_tile_any(const DevProblem *P_mem, const sk_t
         const int k = k0 + c8 * CE;  // first reduction index of this thread's pieces
         // filter tap and channel of element k (convolutions); later elements by carrying
         int g_r = 0, g_s = 0, g_c = 0;
-        if (P.gather) {
+        if (P.gather && !P.nchw) {
           const int tap = k / P.Cin;
           g_c = k - tap * P.Cin;
           g_r = tap / P.S;
           g_s = tap - g_r * P.S;
+        } else if (P.gather) {  // channel-major: k = (c*R + r)*S + s
+          const int cr = k / P.S;
+          g_s = k - cr * P.S;
+          g_c = cr / P.R;
+          g_r = cr - g_c * P.R;
         }
         elem_t va[4][CE], vb[4][CE];
 #pragma unroll
         for (int e = 0; e < CE; ++e) {
           const bool in = k + e < P.Kg;
-          const int64_t rel = P.gather ? ((int64_t)g_r * P.W + g_s) * P.Cin + g_c : (int64_t)(k + e);
+          const int64_t rel = P.gather ? g_r * im.sh + g_s * im.sw + g_c * im.sc : (int64_t)(k + e);
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             const bool ok = in && (!P.gather || ((unsigned)(rows[i].hb + g_r) < (unsigned)P.H &&
@@ -1136,11 +1177,19 @@ __device__ __forceinline__ void run_tile_any(const DevProblem *P_mem, const sk_t
             const uintptr_t pb = (uintptr_t)P.B + (uintptr_t)((wrow[i] + k + e) * ES);
             vb[i][e] = *(const elem_t SK_GLOBAL *)(in ? pb : zeros);
           }
-          if (++g_c == P.Cin) {
-            g_c = 0;
-            if (++g_s == P.S) {
-              g_s = 0;
-              ++g_r;
+          if (!P.nchw) {
+            if (++g_c == P.Cin) {
+              g_c = 0;
+              if (++g_s == P.S) {
+                g_s = 0;
+                ++g_r;
+              }
+            }
+          } else if (++g_s == P.S) {
+            g_s = 0;
+            if (++g_r == P.R) {
+              g_r = 0;
+              ++g_c;
             }
           }
         }
@@ -1188,7 +1237,8 @@ __device__ __forceinline__ void run_tile_any(const DevProblem *P_mem, const sk_t
       for (int fm = 0; fm < 2; ++fm) {
         const int m = mb + (wm * 2 + fm) * 32 + l32;
         if (m < m_end) {
-          const int64_t row_off = (int64_t)m * P.ldc;
+          const int64_t row_off = P.nchw ? nchw_out_base(P, m) : (int64_t)m * P.ldc;
+          const int64_t plane = (int64_t)P.Ho * P.Wo;
 #pragma unroll
           for (int fn = 0; fn < 2; ++fn) {
 #pragma unroll
@@ -1196,7 +1246,14 @@ __device__ __forceinline__ void run_tile_any(const DevProblem *P_mem, const sk_t
               const int n = nb + (wn * 2 + fn) * 32 + 8 * j + 4 * half;
               if (n < n_end) {
                 f32x4 v = {acc[fn][fm][4 * j], acc[fn][fm][4 * j + 1], acc[fn][fm][4 * j + 2], acc[fn][fm][4 * j + 3]};
-                store4<DT>(P.C, row_off, n, n_end, v, vec_c);
+                if (!P.nchw) {
+                  store4<DT>(P.C, row_off, n, n_end, v, vec_c);
+                } else {
+                  // consecutive output channels lie a plane apart
+#pragma unroll
+                  for (int q = 0; q < 4; ++q)
+                    if (n + q < n_end) store_elem<DT>(P.C, row_off + (int64_t)(n + q) * plane, v[q]);
+                }
               }
             }
           }

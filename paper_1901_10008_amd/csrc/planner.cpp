@@ -50,7 +50,7 @@ sk_status canonicalise(const sk_problem &p, int32_t i, Canon &c, std::string &er
       return SK_ERR_INVALID_ARG;
     }
     c = Canon{p.M, p.N, p.K, 0, 0};
-  } else if (p.op == SK_CONV2D_NHWC) {
+  } else if (p.op == SK_CONV2D_NHWC || p.op == SK_CONV2D_NCHW) {
     if (p.Nb < 1 || p.H < 1 || p.Wd < 1 || p.Cin < 1 || p.Cout < 1 || p.R < 1 || p.S < 1 || p.pad_h < 0 ||
         p.pad_w < 0) {
       err = at(i) + "convolution dimensions must be >= 1 and padding >= 0";
@@ -159,15 +159,21 @@ sk_status plan_host(const sk_problem *problems, int32_t n, const sk_plan_params 
       // a 1x1 filter without padding or stride reads the image as a plain [pixels, Cin] matrix
       d.gather = !(p.R == 1 && p.S == 1 && p.pad_h == 0 && p.pad_w == 0 && d.stride == 1);
       d.lda = p.Cin;
+      if (p.op == SK_CONV2D_NCHW) {
+        d.nchw = 1;
+        d.gather = 1;  // neither a patch row nor an output row is contiguous in this storage order
+      }
     }
     int32_t flags = 0;
-    if (d.gather) {
+    if (d.nchw) {
+      // element-wise paths only: no 16-byte pieces along the reduction or along an output row
+    } else if (d.gather) {
       if (aligned16(p.A) && p.Cin % ce == 0) flags |= FLAG_VEC_A;
     } else {
       if (aligned16(p.A) && d.lda % ce == 0 && c.Kg % ce == 0) flags |= FLAG_VEC_A;
     }
     if (aligned16(p.B) && d.ldb % ce == 0 && c.Kg % ce == 0) flags |= FLAG_VEC_B;
-    if ((reinterpret_cast<uintptr_t>(p.C) % (4 * es)) == 0 && d.ldc % 4 == 0) flags |= FLAG_VEC_C;
+    if (!d.nchw && (reinterpret_cast<uintptr_t>(p.C) % (4 * es)) == 0 && d.ldc % 4 == 0) flags |= FLAG_VEC_C;
     d.flags = flags;
     out.dev[i] = d;
     total_w += c.Ng * c.Kg * es;

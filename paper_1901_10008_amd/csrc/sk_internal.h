@@ -25,8 +25,8 @@ enum : uint16_t {
 // Device-side description of one operator in its canonical GEMM view
 //   C[Mg,Ng] = A'[Mg,Kg] . Bs[Ng,Kg]^T
 // where A' is either a plain row-major matrix (gather == 0) or the implicit
-// patch matrix of an NHWC image (gather == 1; Section 5.3: a convolution is
-// executed through the GEMM that backs it).
+// patch matrix of an image (gather == 1; Section 5.3: a convolution is
+// executed through the GEMM that backs it), NHWC or, with nchw set, NCHW.
 struct DevProblem {
   const void *A;
   const void *B;
@@ -39,6 +39,8 @@ struct DevProblem {
   int32_t flags;
   int32_t tile_first, tile_count;
   int32_t stride;  // of a convolution, both directions (>= 1)
+  int32_t nchw;    // convolution on channel-major arrays: X[Nb,Cin,H,W], W[Cout,Cin,R,S], Y[Nb,Cout,Ho,Wo]
+  int32_t pad0;
 };
 static_assert(sizeof(DevProblem) % 8 == 0, "DevProblem must stay 8-byte sized");
 
@@ -48,7 +50,6 @@ static_assert(sizeof(DevProblem) % 8 == 0, "DevProblem must stay 8-byte sized");
 struct TileWork {
   sk_tile tile;
   DevProblem prob;
-  uint32_t pad[2];
 };
 static_assert(sizeof(TileWork) == 160, "TileWork layout");
 

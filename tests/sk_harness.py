@@ -128,6 +128,9 @@ class Batch:
             s = self.specs[i]
             if s.op == "gemm":
                 self._ref[i] = R.gemm(self.a_val[i], self.b_val[i], want_mag=True)
+            elif s.op == "conv_nchw":
+                Y, S = R.conv2d_nchw(self.a_val[i], self.b_val[i], s.pad_h, s.pad_w, want_mag=True, stride=s.stride)
+                self._ref[i] = (Y.reshape(-1, Y.shape[-1]), S.reshape(-1, Y.shape[-1]))
             else:
                 Y, S = R.conv2d_nhwc(self.a_val[i], self.b_val[i], s.pad_h, s.pad_w, want_mag=True, stride=s.stride)
                 self._ref[i] = (Y.reshape(-1, s.Cout), S.reshape(-1, s.Cout))

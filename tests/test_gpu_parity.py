@@ -106,6 +106,29 @@ def test_ragged_shapes_all_paths():
     run_all_modes(RAGGED, seed=7, label="ragged")
 
 
+def nchw(h, w, cin, cout, r, s, ph, pw, dtype="bf16", nb=1, d=math.inf, st=1):
+    return Problem(op="conv_nchw", dtype=dtype, Nb=nb, H=h, W=w, Cin=cin, Cout=cout, R=r, S=s, pad_h=ph, pad_w=pw,
+                   stride=st, deadline_ms=d, a_dist=("uniform", 0.0, 1.0), b_dist=("normal", 0.1))
+
+
+# channel-major convolutions: outputs of one thread each and matrix-core blocks, every type, 1x1 up to 7x7,
+# strides, padding on one side only, several images, more than one 128-block in both directions
+NCHW = [
+    nchw(5, 5, 3, 7, 3, 3, 1, 1), nchw(9, 9, 8, 130, 1, 1, 0, 0, d=0.25), nchw(13, 11, 16, 40, 3, 3, 1, 1, nb=2),
+    nchw(6, 6, 4, 4, 3, 1, 0, 0, "f32"), nchw(7, 7, 24, 20, 3, 3, 1, 1, "f16"), nchw(3, 3, 16, 8, 3, 3, 2, 2),
+    nchw(10, 10, 5, 6, 3, 3, 1, 1, "f32", nb=3), nchw(30, 29, 8, 130, 3, 3, 1, 1, st=2),
+    nchw(40, 40, 3, 64, 7, 7, 3, 3, st=2), nchw(23, 17, 6, 96, 3, 3, 1, 0, "f16", nb=2),
+    nchw(28, 28, 64, 64, 1, 1, 0, 0, "f16", st=2), nchw(20, 20, 32, 200, 3, 3, 1, 1, "f32"), nchw(1, 1, 64, 10, 1, 1, 0, 0),
+    nchw(14, 14, 256, 256, 3, 3, 1, 1, d=0.5),
+]
+
+
+def test_channel_major_convolutions():
+    # among NHWC convolutions and GEMMs of the fast paths, in one plan
+    run_all_modes(NCHW + [c(13, 11, 16, 40, 3, 3, 1, 1, nb=2), g(16, 1000, 64), g(129, 130, 136)], seed=21, label="nchw")
+    run_all_modes(NCHW[:8], seed=22, label="misaligned nchw", a_off=4, b_off=4, c_off=4)
+
+
 def test_misaligned_and_strided_operands():
     specs = [s for s in RAGGED if s.op == "gemm"]
     # 2/4-byte offsets break 16-byte alignment (element-wise load/store paths); padded row strides
@@ -134,8 +157,9 @@ def test_random_mixes_under_random_plan_parameters(seed):
         else:
             hw = int(rng.choice([4, 7, 9, 14, 20]))
             r = int(rng.choice([1, 3]))
-            specs.append(c(hw, hw, int(rng.choice([3, 8, 16, 64, 128, 256])), int(rng.choice([8, 40, 64, 128, 136])),
-                           r, r, r // 2, r // 2, dt, nb=int(rng.integers(1, 3)), d=d, st=int(rng.choice([1, 1, 2]))))
+            make = nchw if seed >= 2 and rng.random() < 0.3 else c   # (seeds 0 and 1 keep their earlier draws)
+            specs.append(make(hw, hw, int(rng.choice([3, 8, 16, 64, 128, 256])), int(rng.choice([8, 40, 64, 128, 136])),
+                              r, r, r // 2, r // 2, dt, nb=int(rng.integers(1, 3)), d=d, st=int(rng.choice([1, 1, 2]))))
     tmin = int(rng.choice([4096, 32768, 1 << 17]))
     prm = {"skinny_max_m": int(rng.choice([16, 32, 64])), "tile_bytes_min": tmin,
            "tile_bytes_max": tmin * int(rng.choice([1, 4, 16])), "balance_div": int(rng.choice([16, 2048])),

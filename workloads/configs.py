@@ -30,9 +30,10 @@ class Problem:
     CONV:  Y[Nb,Ho,Wo,Cout] = X[Nb,H,W,Cin] (*) W[Cout,R,S,Cin], NHWC,
            stride `stride` in both directions, dilation 1, zero padding (pad_h, pad_w),
            cross-correlation.
+    CONV_NCHW: the same operator on channel-major arrays: Y[Nb,Cout,Ho,Wo] = X[Nb,Cin,H,W] (*) W[Cout,Cin,R,S].
     """
 
-    op: str  # "gemm" | "conv"
+    op: str  # "gemm" | "conv" | "conv_nchw"
     dtype: str  # "f32" | "bf16" | "f16"
     M: int = 0
     N: int = 0
@@ -54,10 +55,14 @@ class Problem:
 
     @property
     def a_shape(self):
+        if self.op == "conv_nchw":
+            return (self.Nb, self.Cin, self.H, self.W)
         return (self.M, self.K) if self.op == "gemm" else (self.Nb, self.H, self.W, self.Cin)
 
     @property
     def b_shape(self):
+        if self.op == "conv_nchw":
+            return (self.Cout, self.Cin, self.R, self.S)
         return (self.N, self.K) if self.op == "gemm" else (self.Cout, self.R, self.S, self.Cin)
 
     @property
@@ -66,14 +71,15 @@ class Problem:
             return (self.M, self.N)
         ho = (self.H + 2 * self.pad_h - self.R) // self.stride + 1
         wo = (self.W + 2 * self.pad_w - self.S) // self.stride + 1
-        return (self.Nb, ho, wo, self.Cout)
+        return (self.Nb, self.Cout, ho, wo) if self.op == "conv_nchw" else (self.Nb, ho, wo, self.Cout)
 
 
 def canonical_dims(p: Problem):
     """(Mg, Ng, Kg) of the GEMM an operator is counted as (for flop/byte accounting)."""
     if p.op == "gemm":
         return p.M, p.N, p.K
-    _, ho, wo, _ = p.c_shape
+    ho = (p.H + 2 * p.pad_h - p.R) // p.stride + 1
+    wo = (p.W + 2 * p.pad_w - p.S) // p.stride + 1
     return p.Nb * ho * wo, p.Cout, p.R * p.S * p.Cin
 
 
