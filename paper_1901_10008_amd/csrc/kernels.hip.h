@@ -18,9 +18,11 @@
 //     columns): classic staged GEMM, global -> registers -> LDS -> 32x32 MFMA;
 //     the activation operand may be gathered on the fly from an NHWC image
 //     (implicit GEMM for convolutions, any stride).
-//   * operands that cannot be read in aligned 16-byte pieces: one output per
-//     thread for small rectangles, MFMA tiles assembled element by element for
-//     larger ones; only in the kernel instantiation for plans that need them.
+//   * operands that cannot be read in aligned 16-byte pieces, and convolutions
+//     on channel-major (NCHW) arrays, whose patch rows and output rows are not
+//     contiguous: one output per thread for small rectangles, MFMA tiles
+//     assembled element by element for larger ones; only in the kernel
+//     instantiation for plans that need them.
 #pragma once
 
 #include <hip/hip_runtime.h>
