@@ -1042,7 +1042,7 @@ __device__ __forceinline__ void run_tile(const DevProblem &P, const sk_tile &T, 
 // generic tiles: operands that cannot be read in aligned 16-byte pieces
 // (odd K, odd Cin, unaligned pointers or strides).  One output per thread and
 // trip, plain fp32 multiply-adds in ascending k.  Correct for everything, fast
-// for nothing.
+// for nothing; used for rectangles with next to no work.
 // ---------------------------------------------------------------------------
 // (Inlined, like every path of the kernel: as real calls the two slow paths gave the kernel a stack,
 // and how well its fast paths then ran changed from build to build.  They exist only in the kernel
@@ -1274,8 +1274,11 @@ __device__ __forceinline__ void run_class(const DevProblem &P, const sk_tile &T,
     if constexpr (ANY_ALIGNMENT) {
       pf.claim();
       pf.issue();
-      // small rectangles one output per thread, larger ones through the matrix cores
-      if ((int)T.m_len * (int)T.n_len < 4096)
+      // One output per thread costs a thread (outputs / 256) * Kg dependent steps of about 0.1 us; a stage
+      // of 64 (fp32: 32) reduction elements through the matrix cores costs a few us whatever the
+      // rectangle.  So only rectangles that are done in a few dozen steps go the first way.
+      const int per_thread = ((int)T.m_len * (int)T.n_len + WG_THREADS - 1) / WG_THREADS;
+      if ((int64_t)per_thread * P.Kg <= 64)
         run_generic<DT>(P_mem, T_mem);
       else
         run_tile_any<DT>(P_mem, T_mem, lds);
