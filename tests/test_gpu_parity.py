@@ -336,6 +336,32 @@ def test_host_threads_plan_and_launch_side_by_side():
         H.check_against_oracle(b, f"thread {t}")
 
 
+def test_thousands_of_tiny_operators():
+    """Far more operators than workgroups: 3000 GEMMs and convolutions of a few hundred outputs each, every
+    fourth with a deadline, in one plan; coalesced, one launch per operator, and with completion stamps."""
+    rng = np.random.default_rng(77)
+    specs = []
+    for i in range(3000):
+        d = float(rng.choice([0.2, 0.5, 1.0])) if i % 4 == 0 else math.inf
+        if i % 5 == 4:
+            specs.append(c(int(rng.integers(2, 6)), int(rng.integers(2, 6)), 8, 8, 3, 3, 1, 1, d=d))
+        else:
+            specs.append(g(int(rng.integers(1, 9)), int(rng.choice([8, 16, 40, 64])), int(rng.choice([8, 24, 64])), d=d))
+    b = H.Batch(specs, seed=31)
+    with b.plan(stamps=1) as plan:
+        table, order, first, count = P.plan(specs)
+        assert sk.sk_plan_get_tiles(plan) == table and sk.sk_plan_get_order(plan) == order
+        sk.sk_launch(plan, H.stream_handle())
+        _sync()
+        H.check_against_oracle(b, "tiny operators")
+        done, start, _ = sk.sk_plan_get_stamps(plan)
+        assert len(done) == len(specs) and all(t >= start for t in done)
+        b.reset_outputs()
+        sk.sk_launch_sequential(plan, H.stream_handle())
+        _sync()
+        H.check_against_oracle(b, "tiny operators, sequential")
+
+
 def test_single_and_empty_plans():
     run_all_modes([g(1, 64, 64)], seed=3, label="single")
     with sk.sk_plan_create([], None) as plan:
