@@ -1101,19 +1101,18 @@ __device__ __forceinline__ void run_generic(const DevProblem *P_mem, const sk_ti
 // by one, and a stage is loaded, stored to LDS and multiplied before the next
 // one is touched (the unpacked elements of one stage fill the registers that
 // the packed pieces of a ring of stages would).  Any output rectangle is
-// walked in blocks of 128 x 128; a split reduction is done whole by the record
-// of its first slice.
+// walked in blocks of 128 x 128; the slices of a split reduction (always a
+// single block) meet in the workspace like those of the other tile classes.
 // ---------------------------------------------------------------------------
 template <int DT>
-__device__ __forceinline__ void run_tile_any(const DevProblem *P_mem, const sk_tile *T_mem,
-                                                       unsigned char *lds) {
+__device__ __forceinline__ void run_tile_any(const DevProblem *P_mem, const sk_tile *T_mem, const SplitK &sp,
+                                             unsigned char *lds, uint32_t *s_flag) {
   constexpr int ES = Elem<DT>::ES;
   constexpr int CE = 16 / ES;
   constexpr int KB = 8 * CE;
   using elem_t = typename std::conditional<ES == 4, uint32_t, uint16_t>::type;
   const DevProblem P = *P_mem;
   const sk_tile T = *T_mem;
-  if (T.ks_idx != 0) return;
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
   const int wm = wave & 1, wn = wave >> 1;
@@ -1150,7 +1149,9 @@ __device__ __forceinline__ void run_tile_any(const DevProblem *P_mem, const sk_t
 #pragma unroll
           for (int i = 0; i < 16; ++i) acc[fn][fm][i] = 0.f;
 
-      for (int k0 = 0; k0 < P.Kg; k0 += KB) {
+      // this record's slice of the reduction (all of it unless the rectangle is split)
+      const int k_stop = (int)T.k0 + (int)T.k_len;
+      for (int k0 = (int)T.k0; k0 < k_stop; k0 += KB) {
         const int k = k0 + c8 * CE;  // first reduction index of this thread's pieces
         // filter tap and channel of element k (convolutions); later elements by carrying
         int g_r = 0, g_s = 0, g_c = 0;
@@ -1168,7 +1169,7 @@ __device__ __forceinline__ void run_tile_any(const DevProblem *P_mem, const sk_t
         elem_t va[4][CE], vb[4][CE];
 #pragma unroll
         for (int e = 0; e < CE; ++e) {
-          const bool in = k + e < P.Kg;
+          const bool in = k + e < k_stop;
           const int64_t rel = P.gather ? g_r * im.sh + g_s * im.sw + g_c * im.sc : (int64_t)(k + e);
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
@@ -1234,6 +1235,84 @@ __device__ __forceinline__ void run_tile_any(const DevProblem *P_mem, const sk_t
         __syncthreads();  // everyone has read the stage before the next one overwrites it
       }
 
+      if (T.S > 1) {
+        // A slice of a split reduction (such a rectangle is a single block here: at most 128 x 128, or
+        // 16, 32 or 64 rows x 128 columns in the skinny classes).  Partial sums go to the rectangle's
+        // workspace, which holds per slice `rows` x 128 (64 for the 64-column class) floats, as 16-byte
+        // pieces indexed by (column group of 32, quad j, half, row); the last slice to arrive adds
+        // all of them in slice order and stores the result.  Same hand-over as in run_tile.
+        // The sixteen accumulator quads of a thread wait in LDS meanwhile (free by now: the last stage
+        // ended with a barrier; a slot per thread and quad), so that the loops below can run rolled up:
+        // unrolled over the accumulators they cost this kernel forty registers it does not have.
+        typedef float f32x2 __attribute__((ext_vector_type(2)));
+        static_assert(16 * WG_THREADS * 16 <= LDS_TILE_BYTES, "the accumulators do not fit the LDS buffer");
+        f32x4 *slot = (f32x4 *)lds + tid;  // quad p of this thread: slot[p * WG_THREADS]
+#pragma unroll
+        for (int fn = 0; fn < 2; ++fn)
+#pragma unroll
+          for (int fm = 0; fm < 2; ++fm)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+              slot[((fn * 2 + fm) * 4 + j) * WG_THREADS] =
+                  f32x4{acc[fn][fm][4 * j], acc[fn][fm][4 * j + 1], acc[fn][fm][4 * j + 2], acc[fn][fm][4 * j + 3]};
+        const int rows = T.cls >= CLS_TILE_128x128 ? 128 : 16 << (T.cls / 3);
+        const int groups = T.cls == CLS_TILE_128x64 ? 2 : 4;
+        const size_t per_slice = (size_t)groups * 4 * 2 * rows;  // f32x4 units
+        unsigned long long *mine = (unsigned long long *)(sp.ws + sp.ws_off[T.out_tile_id]);
+        // where quad p = (fn*2 + fm)*4 + j of this thread lies in slice 0, or null if outside the rectangle's rows / columns
+        auto piece = [&](int p) -> unsigned long long * {
+          const int fn = p >> 3, fm = (p >> 2) & 1, j = p & 3;
+          const int r = (wm * 2 + fm) * 32 + l32, cg = wn * 2 + fn;
+          if (r >= rows || cg >= groups) return nullptr;
+          return mine + 2 * ((size_t)((cg * 4 + j) * 2 + half) * rows + r);
+        };
+#pragma unroll 1
+        for (int p = 0; p < 16; ++p) {
+          unsigned long long *q = piece(p);
+          if (q) {
+            q += 2 * (size_t)T.ks_idx * per_slice;
+            const f32x4 v = slot[p * WG_THREADS];
+            __hip_atomic_store(q, __builtin_bit_cast(unsigned long long, f32x2{v.x, v.y}), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(q + 1, __builtin_bit_cast(unsigned long long, f32x2{v.z, v.w}), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+          }
+        }
+        __builtin_amdgcn_s_waitcnt(0);  // all counters to zero: the stores above have completed
+        __syncthreads();
+        if (tid == 0)
+          *s_flag = __hip_atomic_fetch_add(&sp.arrive[T.out_tile_id], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        if (*s_flag != (uint32_t)T.S - 1) return;
+#pragma unroll 1
+        for (int p = 0; p < 16; ++p) {
+          unsigned long long *q = piece(p);
+          f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+          if (q) {
+            for (int s2 = 0; s2 < T.S; ++s2, q += 2 * per_slice) {
+              const f32x2 lo = __builtin_bit_cast(f32x2, __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+              const f32x2 hi = __builtin_bit_cast(f32x2, __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+              sum += f32x4{lo.x, lo.y, hi.x, hi.y};
+            }
+          }
+          slot[p * WG_THREADS] = sum;
+        }
+        if (tid == 0)  // re-arm for the next launch
+          __hip_atomic_store(&sp.arrive[T.out_tile_id], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (int fn = 0; fn < 2; ++fn)
+#pragma unroll
+          for (int fm = 0; fm < 2; ++fm)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              const f32x4 v = slot[((fn * 2 + fm) * 4 + j) * WG_THREADS];
+              acc[fn][fm][4 * j] = v.x;
+              acc[fn][fm][4 * j + 1] = v.y;
+              acc[fn][fm][4 * j + 2] = v.z;
+              acc[fn][fm][4 * j + 3] = v.w;
+            }
+      }
+
       // lane holds, per (fn, fm): row l32, columns 8*(i/4) + 4*half + (i%4)
 #pragma unroll
       for (int fm = 0; fm < 2; ++fm) {
@@ -1281,7 +1360,7 @@ __device__ __forceinline__ void run_class(const DevProblem &P, const sk_tile &T,
       if ((int64_t)per_thread * P.Kg <= 64)
         run_generic<DT>(P_mem, T_mem);
       else
-        run_tile_any<DT>(P_mem, T_mem, lds);
+        run_tile_any<DT>(P_mem, T_mem, sp, lds, s_flag);
     }
   } else if (cls == 0) {
     run_skinny<DT, 1>(P, T, sp, lds, s_flag, pf);
