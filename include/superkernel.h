@@ -221,9 +221,10 @@ int32_t sk_plan_grid(const sk_plan *plan);
 /*
  * Completion stamps of the LAST completed launch of this plan (the caller must
  * have synchronised the stream).  done_ticks[i] is the device wall clock when
- * operator i's last tile retired, *start_tick the clock when the first
- * workgroup of the launch started; *ticks_per_ms converts.  Any pointer may be
- * NULL.  SK_ERR_STATE unless the plan was created with params->stamps = 1.
+ * operator i's last tile retired, *start_tick the clock when workgroup 0 of
+ * the launch started (another workgroup can begin a fraction of a microsecond
+ * earlier, so the stamp of a very short operator may lie a few ticks before
+ * it); *ticks_per_ms converts.  Any pointer may be NULL.  SK_ERR_STATE unless the plan was created with params->stamps = 1.
  */
 sk_status sk_plan_get_stamps(sk_plan *plan, uint64_t *done_ticks, uint64_t *start_tick,
                              double *ticks_per_ms);

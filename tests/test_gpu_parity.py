@@ -354,8 +354,11 @@ def test_thousands_of_tiny_operators():
         sk.sk_launch(plan, H.stream_handle())
         _sync()
         H.check_against_oracle(b, "tiny operators")
-        done, start, _ = sk.sk_plan_get_stamps(plan)
-        assert len(done) == len(specs) and all(t >= start for t in done)
+        done, start, rate = sk.sk_plan_get_stamps(plan)
+        # the start stamp is workgroup 0's; another workgroup can have begun, and finished a tile, a moment earlier
+        assert len(done) == len(specs) and min(done) >= start - 0.005 * rate and max(done) <= start + 50.0 * rate, \
+            (start, min(done), max(done), rate)
+        print(f"earliest completion {(min(done) - start) / rate * 1e3:.2f} us after workgroup 0 started, latest {(max(done) - start) / rate * 1e3:.1f} us")
         b.reset_outputs()
         sk.sk_launch_sequential(plan, H.stream_handle())
         _sync()
