@@ -8,6 +8,14 @@ here divides by max(|ref_ij|, rms(ref)) per operator; the strict element-wise,
 norm-wise and backward (relative to sum_k |a||b|) figures are returned beside
 it.  `order_free_bound` is the rigorous ceiling any fp32-accumulate summation
 order must sit under.
+
+Pins (tests/test_oracle_compare.py, tests/test_oracle_rounding.py): `errors`
+against hand-worked gate / strict / normwise / backward figures, including a
+cancellation case and the floors a mean or a maximum would give instead of the
+root mean square; `order_free_bound` from both sides: fp32 accumulation of the
+exact products in ascending, descending, pairwise and shuffled order passes, a
+constructed sequential sum comes within 5 % of it, and a dropped product, fp16
+accumulation, products rounded to bf16 and a twice-rounded result are rejected.
 """
 from __future__ import annotations
 
