@@ -29,7 +29,11 @@
  *     counters.  `hip_stream` arguments are hipStream_t handles owned by the
  *     caller (NULL = the default stream).  Launches are asynchronous.
  *   - A plan has one work counter: two launches of the SAME plan must not be in
- *     flight at the same time (launching it again on the same stream is fine).
+ *     flight at the same time.  Launching it again on the same stream is fine
+ *     (the stream orders them); on another stream the launch calls return
+ *     SK_ERR_BUSY while the previous launch has not completed.  The check is best
+ *     effort: launches recorded into a HIP graph are not tracked, and ordering a
+ *     graph's replays against other launches of the plan is the caller's job.
  *   - Host threads: any number of threads may call into the library at the same
  *     time, each on plans of its own; calls that name the same plan are
  *     serialised by the caller.
@@ -50,7 +54,8 @@ typedef enum {
   SK_ERR_OVERLAP = -3,     /* two operators' C ranges overlap                        */
   SK_ERR_ALLOC = -4,       /* host or device allocation failed                       */
   SK_ERR_HIP = -5,         /* a HIP runtime call failed (no device, launch error...) */
-  SK_ERR_STATE = -6        /* plan is host-only / stamps not enabled / ...           */
+  SK_ERR_BUSY = -6,        /* the plan's previous launch still runs on another stream */
+  SK_ERR_STATE = -7        /* plan is host-only / stamps not enabled / ...           */
 } sk_status;
 
 /* A, B and C of one operator share the element type; accumulation is always fp32. */
@@ -58,7 +63,9 @@ typedef enum { SK_F32 = 0, SK_BF16 = 1, SK_F16 = 2 } sk_dtype;
 typedef enum { SK_GEMM = 0, SK_CONV2D_NHWC = 1, SK_CONV2D_NCHW = 2 } sk_op;
 
 /*
- * One operator (Section 5.1: "the operators, the inputs, and latency constraints").
+ * One operator: what it computes, where its operands live and its latency
+ * budget, the three things Section 5.1 has the caller state instead of a launch
+ * geometry.
  *
  * SK_GEMM:  C[M,N] = A[M,K] . B, with the K x N weight operand stored
  *   K-contiguous as Bs[N,K] (the layout of a linear layer's weight), i.e.
@@ -181,15 +188,19 @@ sk_status sk_release_cached_memory(void);
 /*
  * Run every operator of the plan in ONE kernel launch on `hip_stream`
  * (Sections 1 and 5.3: the superkernel).  Persistent workgroups take tiles
- * from the table in order through a single atomic counter, so operators with
- * earlier deadlines start first.  Asynchronous.  Needs a device-resident plan
- * (SK_ERR_STATE otherwise).
+ * from the table in order, so operators with earlier deadlines start first:
+ * workgroup b starts on tile b and takes further tiles through a single atomic
+ * counter; a plan whose tiles are all short (at most 64 KB of operands each)
+ * skips the counter and gives workgroup b the tiles b, b + grid, ...
+ * Asynchronous.  Needs a device-resident plan (SK_ERR_STATE otherwise).
  * A plan has one tile queue and one set of split-reduction counters, which the
  * kernel re-arms itself when it ends: launches of ONE plan must not overlap
- * (order them on one stream or with events); different plans may.
+ * (order them on one stream or with events); different plans may.  SK_ERR_BUSY
+ * if the plan's previous launch went to another stream and still runs.
  * The call makes no allocation, copy, memset or host synchronisation, so it may
  * be captured into a HIP graph; the plan must then outlive the graph's
- * replays.
+ * replays.  (A plan with stamps enabled launches one more, one-thread kernel
+ * that resets the start stamp.)
  */
 sk_status sk_launch(sk_plan *plan, void *hip_stream);
 
@@ -200,13 +211,15 @@ sk_status sk_launch(sk_plan *plan, void *hip_stream);
  * to that operator by itself, what a caller who launches operators one by one
  * would get), not with the tiles of the coalesced table.  Reductions may
  * therefore be sliced differently: outputs agree with sk_launch up to the order
- * of summation.  The first call on a plan builds and uploads these tables
+ * of summation, and bit for bit where the two tables coincide (a plan of one
+ * operator).  SK_ERR_BUSY as for sk_launch.  The first call on a plan builds and uploads these tables
  * (SK_ERR_ALLOC / SK_ERR_HIP as for sk_plan_create); later calls only launch
  * (and may be captured into a HIP graph like sk_launch).
  */
 sk_status sk_launch_sequential(sk_plan *plan, void *hip_stream);
 
-/* Introspection (used to compare the plan with a reference planner). */
+/* Introspection of the packed plan (Section 5.3: what the runtime packing step produced; used to compare
+ * the plan with a reference planner). */
 int64_t sk_plan_num_tiles(const sk_plan *plan);    /* < 0 on error */
 int32_t sk_plan_num_problems(const sk_plan *plan); /* < 0 on error */
 /* Copies the flat table (num_tiles * 32 bytes) to host memory `dst`. */
@@ -219,12 +232,13 @@ sk_status sk_plan_get_ranges(const sk_plan *plan, int64_t *first_tile, int64_t *
 int32_t sk_plan_grid(const sk_plan *plan);
 
 /*
- * Completion stamps of the LAST completed launch of this plan (the caller must
- * have synchronised the stream).  done_ticks[i] is the device wall clock when
- * operator i's last tile retired, *start_tick the clock when workgroup 0 of
- * the launch started (another workgroup can begin a fraction of a microsecond
- * earlier, so the stamp of a very short operator may lie a few ticks before
- * it); *ticks_per_ms converts.  Any pointer may be NULL.  SK_ERR_STATE unless the plan was created with params->stamps = 1.
+ * Per-operator latency of the LAST completed launch of this plan (Section 5.2:
+ * the runtime monitors inference latency per kernel); the caller must have
+ * synchronised the stream.  done_ticks[i] is the device wall clock when
+ * operator i's last tile retired, *start_tick the earliest clock at which any
+ * workgroup of the launch (of the first launch, for sk_launch_sequential)
+ * started; *ticks_per_ms converts.  Any pointer may be NULL.  SK_ERR_STATE
+ * unless the plan was created with params->stamps = 1.
  */
 sk_status sk_plan_get_stamps(sk_plan *plan, uint64_t *done_ticks, uint64_t *start_tick,
                              double *ticks_per_ms);

@@ -1,8 +1,8 @@
 """Reference tile planner and coverage checker -- TEST INFRASTRUCTURE ONLY.
 
-The paper's runtime "repacks multiple small kernels into a large execution
-block" (Section 5.3) and "prioritizes streams with tighter latency budgets"
-(Section 5, item (a)); it gives no packing algorithm, table layout or policy.
+The paper's runtime packs many small kernels into one large launch (Section
+5.3) and serves the streams with the least latency slack first (Section 5,
+item (a)); it gives no packing algorithm, table layout or policy.
 This module fixes this build's reading as a pure integer function of the
 operator list and a few parameters, in plain Python, so that the C++ planner
 behind the C ABI can be compared with it byte for byte:

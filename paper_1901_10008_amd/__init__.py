@@ -29,5 +29,6 @@ from .binding import (  # noqa: F401
     sk_last_error,
     SK_F32, SK_BF16, SK_F16, SK_GEMM, SK_CONV2D_NHWC, SK_CONV2D_NCHW,
     DTYPE_CODE,
+    SK_OK, SK_ERR_INVALID_ARG, SK_ERR_UNSUPPORTED, SK_ERR_OVERLAP, SK_ERR_ALLOC, SK_ERR_HIP, SK_ERR_BUSY, SK_ERR_STATE,
     EXPORTED_SYMBOLS,
 )

@@ -11,6 +11,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 SK_F32, SK_BF16, SK_F16 = 0, 1, 2
 SK_GEMM, SK_CONV2D_NHWC, SK_CONV2D_NCHW = 0, 1, 2
 DTYPE_CODE = {"f32": SK_F32, "bf16": SK_BF16, "f16": SK_F16}
+SK_OK, SK_ERR_INVALID_ARG, SK_ERR_UNSUPPORTED, SK_ERR_OVERLAP = 0, -1, -2, -3
+SK_ERR_ALLOC, SK_ERR_HIP, SK_ERR_BUSY, SK_ERR_STATE = -4, -5, -6, -7
 
 EXPORTED_SYMBOLS = [
     "sk_plan_params_default", "sk_plan_create", "sk_plan_destroy", "sk_launch", "sk_launch_sequential",

@@ -91,7 +91,7 @@ struct KernelArgs {
   uint32_t n_problems;
   uint32_t tile_begin, tile_end;
   uint32_t dynamic;      // 1: tiles come from the atomic counter; 0: static stride over the range
-  uint32_t write_start;  // 1: workgroup 0 records the start tick
+  uint32_t write_start;  // 1: every workgroup lowers the start tick to its own first clock
   f32x4 *ws;             // split-K partial sums
   const uint32_t *ws_off;
   uint32_t *arrive;
@@ -401,6 +401,21 @@ __device__ __forceinline__ f32x4 load_device_scope(const f32x4 *block, int lane)
       __builtin_bit_cast(f32x2, __hip_atomic_load(q + 64 + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
   return f32x4{lo.x, lo.y, hi.x, hi.y};
 }
+
+// Memory order of the arrival count that hands split-reduction partials from one workgroup to another.
+// The partials themselves are written and read with device-scope accesses that go through to memory
+// (see store_device_scope), each wave waits for its own stores to complete (s_waitcnt) and the workgroup
+// meets at a barrier before one thread counts it in, so on this hardware a relaxed count suffices.  The
+// language memory model asks for release/acquire on the count as well; that variant is
+// kept compilable (-DSK_SPLITK_ACQ_REL) and costs a write-back and an invalidate of the XCD's L2 per slice.
+#ifdef SK_SPLITK_ACQ_REL
+#define SK_ARRIVE_ORDER __ATOMIC_ACQ_REL
+#else
+#define SK_ARRIVE_ORDER __ATOMIC_RELAXED
+#endif
+#if defined(__HIP_DEVICE_COMPILE__) && !defined(__gfx950__)
+#error "the split-reduction hand-over relies on gfx950's write-through device-scope stores"
+#endif
 
 struct SplitK {
   f32x4 *ws;                // partial sums of all split output rectangles
@@ -720,7 +735,7 @@ __device__ __forceinline__ void run_skinny(const DevProblem &P, const sk_tile &T
     __builtin_amdgcn_s_waitcnt(0);  // all counters to zero: the stores above have completed
     __syncthreads();
     if (tid == 0)
-      *s_flag = __hip_atomic_fetch_add(&sp.arrive[T.out_tile_id], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      *s_flag = __hip_atomic_fetch_add(&sp.arrive[T.out_tile_id], 1u, SK_ARRIVE_ORDER, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     const uint32_t prev = *s_flag;
     finish = prev == (uint32_t)T.S - 1;
@@ -929,7 +944,7 @@ __device__ __forceinline__ void run_tile(const DevProblem &P, const sk_tile &T, 
     __builtin_amdgcn_s_waitcnt(0);  // all counters to zero: the stores above have completed
     __syncthreads();
     if (tid == 0)
-      *s_flag = __hip_atomic_fetch_add(&sp.arrive[T.out_tile_id], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      *s_flag = __hip_atomic_fetch_add(&sp.arrive[T.out_tile_id], 1u, SK_ARRIVE_ORDER, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     if (*s_flag != (uint32_t)T.S - 1) return;
 #pragma unroll
@@ -1281,7 +1296,7 @@ __device__ __forceinline__ void run_tile_any(const DevProblem *P_mem, const sk_t
         __builtin_amdgcn_s_waitcnt(0);  // all counters to zero: the stores above have completed
         __syncthreads();
         if (tid == 0)
-          *s_flag = __hip_atomic_fetch_add(&sp.arrive[T.out_tile_id], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          *s_flag = __hip_atomic_fetch_add(&sp.arrive[T.out_tile_id], 1u, SK_ARRIVE_ORDER, __HIP_MEMORY_SCOPE_AGENT);
         __syncthreads();
         if (*s_flag != (uint32_t)T.S - 1) return;
 #pragma unroll 1
@@ -1375,6 +1390,10 @@ __device__ __forceinline__ void run_class(const DevProblem &P, const sk_tile &T,
   }
 }
 
+// Sets the start stamp to all ones ahead of a stamped launch (a kernel, not a memset: launches may be
+// captured into graphs).
+__global__ void sk_arm_start_stamp(uint64_t *slot) { *slot = ~0ull; }
+
 // ONLY_DT >= 0: every operator of the plan has that element type (one third of the
 // code, fewer registers); ONLY_DT < 0: operators of mixed types.
 // ANY_ALIGNMENT false: every operator can be read in aligned 16-byte pieces, and the kernel
@@ -1387,7 +1406,10 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sk_superkernel(const TileWork *
   __shared__ uint32_t s_flag;
   const SplitK sp{a.ws, a.ws_off, a.arrive};
 
-  if (a.write_start && a.stamps && blockIdx.x == 0 && threadIdx.x == 0) a.stamps[a.n_problems] = wall_clock64();
+  // Start of the launch = the earliest first clock of any workgroup (the host has set the slot to all ones).
+  if (a.write_start && a.stamps && threadIdx.x == 0)
+    __hip_atomic_fetch_min((unsigned long long *)&a.stamps[a.n_problems], (unsigned long long)wall_clock64(),
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
   // The first tile of every workgroup is fixed (its block index); further tiles come from the
   // queue.  (The host never launches more workgroups than tiles.)

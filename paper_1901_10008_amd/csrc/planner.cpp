@@ -358,6 +358,30 @@ sk_status plan_host_each_alone(const HostPlan &whole, HostPlan &out, std::string
   return SK_OK;
 }
 
+// A launch on the stream of the previous launch is ordered behind it by the stream.  On another stream it
+// may only go ahead when the previous launch has completed (the caller asks the event).  Inside a stream
+// capture nothing can be asked: the launch is recorded, and the graph's replays are the caller's to order.
+LaunchLedger::Ask LaunchLedger::before_launch(uintptr_t stream, bool capturing) const {
+  if (capturing || !has_event || stream == last_stream) return GO;
+  return QUERY_EVENT;
+}
+
+void LaunchLedger::after_launch(uintptr_t stream, bool capturing, bool event_recorded) {
+  if (capturing || !event_recorded) {
+    device_wide = true;  // replays of a graph, or a launch without an event behind it
+    return;
+  }
+  // every earlier eager launch either shares this stream or had completed before this one was admitted:
+  // the event behind this launch covers them all
+  has_event = true;
+  last_stream = stream;
+}
+
+LaunchLedger::Wait LaunchLedger::before_destroy() const {
+  if (device_wide) return DEVICE;
+  return has_event ? EVENT : NOTHING;
+}
+
 }  // namespace sk
 
 extern "C" void sk_plan_params_default(sk_plan_params *p) {

@@ -75,4 +75,21 @@ sk_status plan_host_each_alone(const HostPlan &whole, HostPlan &out, std::string
 
 inline int elem_size(int32_t dtype) { return dtype == SK_F32 ? 4 : 2; }
 
+// Bookkeeping of one plan's launches, free of HIP calls so that it can be exercised on the host.
+// A plan has one tile queue, one set of split-reduction counters and one workspace: a launch may only
+// start when the one before it has finished or precedes it on the same stream.  The ledger says when
+// the caller has to ask the event behind the latest launch, and what sk_plan_destroy must wait for.
+struct LaunchLedger {
+  enum Ask { GO, QUERY_EVENT };            // QUERY_EVENT: launch only if the event has completed, else SK_ERR_BUSY
+  enum Wait { NOTHING, EVENT, DEVICE };
+  bool has_event = false;                  // an event sits behind the latest launch made outside a stream capture
+  uintptr_t last_stream = 0;
+  bool device_wide = false;                // launches the event does not cover (captured into a graph, or the
+                                           // event could not be recorded): only a device-wide wait covers them
+  Ask before_launch(uintptr_t stream, bool capturing) const;
+  // event_recorded: the caller recorded the plan's event behind the launch (never under capture)
+  void after_launch(uintptr_t stream, bool capturing, bool event_recorded);
+  Wait before_destroy() const;
+};
+
 }  // namespace sk

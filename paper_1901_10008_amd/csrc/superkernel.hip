@@ -193,61 +193,82 @@ struct sk_plan {
   bool seq_ready = false;
   sk::HostPlan seq_host;
   DeviceTables seq_dev;
-  // what sk_plan_destroy has to wait for: an event behind the latest launch, as long as all
-  // launches went to one stream outside graph capture; otherwise the whole device
-  hipEvent_t last_use = nullptr;
-  hipStream_t last_stream = nullptr;
-  bool wait_for_device = false;
+  // which launch a new one must not overlap, and what sk_plan_destroy has to wait for
+  hipEvent_t last_use = nullptr;  // recorded behind the latest launch made outside a stream capture
+  sk::LaunchLedger ledger;
 };
 
 namespace {
 
-// Uploads the tables of `hp` to the current device (`device`).
-sk_status upload_tables(const sk::HostPlan &hp, int device, DeviceTables &dt) {
+// Where the parts of a table set lie inside its one block of device memory.
+struct TableLayout {
+  size_t off_work, off_cnt, off_rem, off_stamps, off_wsoff, off_arrive;
+  size_t upload;  // bytes the host fills in (everything before the workspace)
+  size_t total;   // upload + split-K workspace
+};
+
+TableLayout layout_of(const sk::HostPlan &hp) {
   const size_t nt = hp.tiles.size(), np = hp.dev.size(), nrect = hp.ws_off.size();
-  const size_t off_work = 0;
-  const size_t off_cnt = align_up(off_work + nt * sizeof(sk::TileWork), 256);
-  const size_t off_rem = align_up(off_cnt + 2 * sizeof(uint32_t), 256);
-  const size_t off_stamps = align_up(off_rem + np * sizeof(uint32_t), 256);
-  const size_t off_wsoff = align_up(off_stamps + (np + 1) * sizeof(uint64_t), 256);
-  const size_t off_arrive = align_up(off_wsoff + nrect * sizeof(uint32_t), 256);
-  const size_t upload = align_up(off_arrive + nrect * sizeof(uint32_t), 256);  // everything before the workspace
-  const size_t total = upload + (size_t)hp.ws_f32x4 * 16;
-  char *stage = t_stage.acquire(upload);
-  if (!stage) return set_error(SK_ERR_ALLOC, "host staging allocation failed");
+  TableLayout l;
+  l.off_work = 0;
+  l.off_cnt = align_up(l.off_work + nt * sizeof(sk::TileWork), 256);
+  l.off_rem = align_up(l.off_cnt + 2 * sizeof(uint32_t), 256);
+  l.off_stamps = align_up(l.off_rem + np * sizeof(uint32_t), 256);
+  l.off_wsoff = align_up(l.off_stamps + (np + 1) * sizeof(uint64_t), 256);
+  l.off_arrive = align_up(l.off_wsoff + nrect * sizeof(uint32_t), 256);
+  l.upload = align_up(l.off_arrive + nrect * sizeof(uint32_t), 256);
+  l.total = l.upload + (size_t)hp.ws_f32x4 * 16;
+  return l;
+}
+
+// The host image of the uploaded part: work records, zeroed counters and stamps, countdowns, offsets.
+void fill_image(const sk::HostPlan &hp, const TableLayout &l, char *stage) {
+  const size_t nt = hp.tiles.size(), np = hp.dev.size(), nrect = hp.ws_off.size();
   // the work records are written in full below; everything behind them starts at zero
-  std::memset(stage + nt * sizeof(sk::TileWork), 0, upload - nt * sizeof(sk::TileWork));
-  if (nrect) std::memcpy(&stage[off_wsoff], hp.ws_off.data(), nrect * sizeof(uint32_t));
+  std::memset(stage + nt * sizeof(sk::TileWork), 0, l.upload - nt * sizeof(sk::TileWork));
+  if (nrect) std::memcpy(&stage[l.off_wsoff], hp.ws_off.data(), nrect * sizeof(uint32_t));
   for (size_t i = 0; i < nt; ++i) {
     sk::TileWork w;
     std::memset(&w, 0, sizeof(w));
     w.tile = hp.tiles[i];
     w.prob = hp.dev[w.tile.problem];
-    std::memcpy(&stage[off_work + i * sizeof(w)], &w, sizeof(w));
+    std::memcpy(&stage[l.off_work + i * sizeof(w)], &w, sizeof(w));
   }
   for (size_t i = 0; i < np; ++i) {
     const uint32_t c = (uint32_t)hp.count[i];
-    std::memcpy(&stage[off_rem + i * sizeof(uint32_t)], &c, sizeof(c));
+    std::memcpy(&stage[l.off_rem + i * sizeof(uint32_t)], &c, sizeof(c));
   }
-  hipError_t e = table_pool().acquire(device, total, &dt.blob, &dt.blob_bytes);
+}
+
+void bind_tables(DeviceTables &dt, void *base, const TableLayout &l) {
+  char *b = (char *)base;
+  dt.work = (sk::TileWork *)(b + l.off_work);
+  dt.counters = (uint32_t *)(b + l.off_cnt);
+  dt.remaining = (uint32_t *)(b + l.off_rem);
+  dt.stamps = (uint64_t *)(b + l.off_stamps);
+  dt.ws_off = (uint32_t *)(b + l.off_wsoff);
+  dt.arrive = (uint32_t *)(b + l.off_arrive);
+  dt.ws = (sk::f32x4 *)(b + l.upload);
+}
+
+// Uploads the tables of `hp` to the current device (`device`).
+sk_status upload_tables(const sk::HostPlan &hp, int device, DeviceTables &dt) {
+  const TableLayout l = layout_of(hp);
+  char *stage = t_stage.acquire(l.upload);
+  if (!stage) return set_error(SK_ERR_ALLOC, "host staging allocation failed");
+  fill_image(hp, l, stage);
+  hipError_t e = table_pool().acquire(device, l.total, &dt.blob, &dt.blob_bytes);
   if (e != hipSuccess) {
     dt.blob = nullptr;
     return set_error(SK_ERR_ALLOC, std::string("hipMalloc: ") + hipGetErrorString(e));
   }
-  e = hipMemcpy(dt.blob, stage, upload, hipMemcpyHostToDevice);
+  e = hipMemcpy(dt.blob, stage, l.upload, hipMemcpyHostToDevice);
   if (e != hipSuccess) {
     (void)table_pool().release(device, dt.blob, dt.blob_bytes);
     dt.blob = nullptr;
     return hip_error("hipMemcpy", e);
   }
-  char *b = (char *)dt.blob;
-  dt.work = (sk::TileWork *)(b + off_work);
-  dt.counters = (uint32_t *)(b + off_cnt);
-  dt.remaining = (uint32_t *)(b + off_rem);
-  dt.stamps = (uint64_t *)(b + off_stamps);
-  dt.ws_off = (uint32_t *)(b + off_wsoff);
-  dt.arrive = (uint32_t *)(b + off_arrive);
-  dt.ws = (sk::f32x4 *)(b + upload);
+  bind_tables(dt, dt.blob, l);
   return SK_OK;
 }
 
@@ -325,12 +346,13 @@ sk_status sk_plan_destroy(sk_plan *plan) {
     // wait for every launch that may still read them
     hipError_t e = hipSuccess;
     int cur = -1;
-    if (plan->wait_for_device) {
+    const sk::LaunchLedger::Wait wait = plan->ledger.before_destroy();
+    if (wait == sk::LaunchLedger::DEVICE) {
       e = hipGetDevice(&cur);
       if (e == hipSuccess && cur != plan->device) e = hipSetDevice(plan->device);
       if (e == hipSuccess) e = hipDeviceSynchronize();
       if (cur >= 0 && cur != plan->device) (void)hipSetDevice(cur);
-    } else if (plan->last_use) {
+    } else if (wait == sk::LaunchLedger::EVENT) {
       e = hipEventSynchronize(plan->last_use);
     }
     if (e != hipSuccess) st = hip_error("waiting for the plan's launches", e);
@@ -392,22 +414,40 @@ static sk_status launch_range(sk_plan *plan, const DeviceTables &dt, hipStream_t
   return SK_OK;
 }
 
-// Remembers the launch that sk_plan_destroy must wait for.
-static void note_use(sk_plan *plan, hipStream_t stream) {
-  if (plan->wait_for_device) return;
+// Admission of a launch (see sk::LaunchLedger): SK_ERR_BUSY when the plan's previous launch went to another
+// stream and has not completed.  Best effort: launches recorded into graphs are not tracked.
+static sk_status admit_launch(sk_plan *plan, hipStream_t stream, bool *capturing) {
   hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
-  if (hipStreamIsCapturing(stream, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone ||
-      (plan->last_use && stream != plan->last_stream)) {
-    plan->wait_for_device = true;  // replays of a graph or a second stream: not covered by one event
-    return;
+  *capturing = hipStreamIsCapturing(stream, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone;
+  if (plan->ledger.before_launch((uintptr_t)stream, *capturing) == sk::LaunchLedger::QUERY_EVENT) {
+    const hipError_t q = hipEventQuery(plan->last_use);
+    if (q == hipErrorNotReady) {
+      (void)hipGetLastError();
+      return set_error(SK_ERR_BUSY, "the plan's previous launch is still running on another stream");
+    }
+    if (q != hipSuccess) return hip_error("hipEventQuery", q);
   }
-  if (!plan->last_use && hipEventCreateWithFlags(&plan->last_use, hipEventDisableTiming) != hipSuccess) {
-    plan->last_use = nullptr;
-    plan->wait_for_device = true;
-    return;
+  return SK_OK;
+}
+
+// Records the event that the next launch on another stream and sk_plan_destroy look at.
+static void note_launch(sk_plan *plan, hipStream_t stream, bool capturing) {
+  bool recorded = false;
+  if (!capturing) {
+    if (!plan->last_use && hipEventCreateWithFlags(&plan->last_use, hipEventDisableTiming) != hipSuccess)
+      plan->last_use = nullptr;
+    recorded = plan->last_use && hipEventRecord(plan->last_use, stream) == hipSuccess;
   }
-  plan->last_stream = stream;
-  if (hipEventRecord(plan->last_use, stream) != hipSuccess) plan->wait_for_device = true;
+  plan->ledger.after_launch((uintptr_t)stream, capturing, recorded);
+}
+
+// Ahead of a stamped launch: the start stamp is a running minimum over the workgroups' first clocks.
+static sk_status arm_start_stamp(sk_plan *plan, hipStream_t stream) {
+  if (!plan->host.params.stamps) return SK_OK;
+  hipLaunchKernelGGL(sk::sk_arm_start_stamp, dim3(1), dim3(1), 0, stream, plan->dev.stamps + plan->host.dev.size());
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hip_error("kernel launch", e);
+  return SK_OK;
 }
 
 static sk_status check_launchable(sk_plan *plan) {
@@ -423,9 +463,16 @@ static sk_status check_launchable(sk_plan *plan) {
 sk_status sk_launch(sk_plan *plan, void *hip_stream) {
   sk_status st = check_launchable(plan);
   if (st != SK_OK) return st;
-  st = launch_range(plan, plan->dev, (hipStream_t)hip_stream, 0u, (uint32_t)plan->host.tiles.size(), plan->grid,
+  if (plan->host.tiles.empty()) return SK_OK;
+  const hipStream_t stream = (hipStream_t)hip_stream;
+  bool capturing = false;
+  st = admit_launch(plan, stream, &capturing);
+  if (st != SK_OK) return st;
+  st = arm_start_stamp(plan, stream);
+  if (st != SK_OK) return st;
+  st = launch_range(plan, plan->dev, stream, 0u, (uint32_t)plan->host.tiles.size(), plan->grid,
                     !plan->fixed_assignment, true);
-  if (st == SK_OK && !plan->host.tiles.empty()) note_use(plan, (hipStream_t)hip_stream);
+  note_launch(plan, stream, capturing);
   return st;
 }
 
@@ -445,18 +492,20 @@ sk_status sk_launch_sequential(sk_plan *plan, void *hip_stream) {
     plan->seq_ready = true;
   }
   const size_t n = plan->seq_host.dev.size();
-  for (size_t i = 0; i < n; ++i) {
+  if (n == 0) return SK_OK;
+  const hipStream_t stream = (hipStream_t)hip_stream;
+  bool capturing = false;
+  st = admit_launch(plan, stream, &capturing);
+  if (st != SK_OK) return st;
+  st = arm_start_stamp(plan, stream);
+  if (st != SK_OK) return st;
+  for (size_t i = 0; i < n && st == SK_OK; ++i) {
     const int64_t first = plan->seq_host.first[i], count = plan->seq_host.count[i];
     const int grid = (int)(count < plan->grid_cap ? count : plan->grid_cap);
-    st = launch_range(plan, plan->seq_dev, (hipStream_t)hip_stream, (uint32_t)first, (uint32_t)(first + count), grid,
-                      false, i == 0);
-    if (st != SK_OK) {
-      plan->wait_for_device = true;  // some launches are out
-      return st;
-    }
+    st = launch_range(plan, plan->seq_dev, stream, (uint32_t)first, (uint32_t)(first + count), grid, false, i == 0);
   }
-  if (n) note_use(plan, (hipStream_t)hip_stream);
-  return SK_OK;
+  note_launch(plan, stream, capturing);  // also after a failure: some launches may be out
+  return st;
 }
 
 int64_t sk_plan_num_tiles(const sk_plan *plan) { return plan ? (int64_t)plan->host.tiles.size() : -1; }
@@ -520,6 +569,7 @@ const char *sk_strerror(sk_status status) {
     case SK_ERR_OVERLAP: return "output ranges overlap";
     case SK_ERR_ALLOC: return "allocation failed";
     case SK_ERR_HIP: return "HIP runtime error";
+    case SK_ERR_BUSY: return "the plan's previous launch is still running on another stream";
     case SK_ERR_STATE: return "plan is not in a state that allows this call";
   }
   return "unknown status";

@@ -125,6 +125,36 @@ int main() {
     if (sk::plan_host(&p, 1, nullptr, hp, err) != SK_ERR_INVALID_ARG) return fail("M = 0 accepted", -1);
     if (sk::plan_host(nullptr, 3, nullptr, hp, err) != SK_ERR_INVALID_ARG) return fail("null list accepted", -1);
   }
+  // the launch ledger: which launches are admitted at once, which only after the plan's event has
+  // completed, and what destroying the plan waits for
+  {
+    using L = sk::LaunchLedger;
+    L l;
+    const uintptr_t s1 = 0x100, s2 = 0x200;
+    if (l.before_destroy() != L::NOTHING) return fail("a plan never launched waits for something", -2);
+    if (l.before_launch(s1, false) != L::GO) return fail("first launch not admitted", -2);
+    l.after_launch(s1, false, true);
+    if (l.before_launch(s1, false) != L::GO) return fail("same stream must be admitted: the stream orders it", -2);
+    if (l.before_launch(s2, false) != L::QUERY_EVENT) return fail("another stream must ask the event", -2);
+    if (l.before_launch(0, false) != L::QUERY_EVENT) return fail("the default stream is another stream", -2);
+    if (l.before_destroy() != L::EVENT) return fail("destroy must wait for the event", -2);
+    l.after_launch(s2, false, true);  // admitted after the event completed: now the latest launch is on s2
+    if (l.before_launch(s2, false) != L::GO || l.before_launch(s1, false) != L::QUERY_EVENT)
+      return fail("the ledger did not move to the new stream", -2);
+    if (l.before_destroy() != L::EVENT) return fail("one event covers launches admitted one after the other", -2);
+    if (l.before_launch(s1, true) != L::GO) return fail("a captured launch cannot ask anything", -2);
+    l.after_launch(s1, true, false);
+    if (l.before_destroy() != L::DEVICE) return fail("graph replays need the device-wide wait", -2);
+    if (l.before_launch(s1, false) != L::QUERY_EVENT) return fail("eager launches are still checked after a capture", -2);
+    L m;
+    m.after_launch(s1, false, false);  // the event could not be recorded
+    if (m.before_destroy() != L::DEVICE) return fail("a launch without an event needs the device-wide wait", -2);
+    if (m.before_launch(s2, false) != L::GO) return fail("nothing to ask without an event", -2);
+    L d;                               // first launch on the default stream (handle 0)
+    d.after_launch(0, false, true);
+    if (d.before_launch(0, false) != L::GO || d.before_launch(s1, false) != L::QUERY_EVENT)
+      return fail("default stream as the plan's stream", -2);
+  }
   std::puts("planner_driver: ok");
   return 0;
 }

@@ -234,10 +234,10 @@ def test_validation_errors():
     with sk.sk_plan_create(ok, sk.sk_plan_params_default(host_only=1)) as plan:
         with pytest.raises(sk.SkError) as e:
             sk.sk_launch(plan)
-        assert e.value.status == -6
+        assert e.value.status == sk.SK_ERR_STATE
         with pytest.raises(sk.SkError) as e:
             sk.sk_plan_get_stamps(plan)
-        assert e.value.status == -6
+        assert e.value.status == sk.SK_ERR_STATE
 
 
 def test_library_exports_every_declared_symbol():
@@ -250,6 +250,8 @@ def test_library_exports_every_declared_symbol():
     for name in declared:
         assert getattr(L, name) is not None
     assert sk.sk_strerror(0) == "success" and "overlap" in sk.sk_strerror(-3)
+    assert (sk.SK_ERR_BUSY, sk.SK_ERR_STATE) == (-6, -7)
+    assert "another stream" in sk.sk_strerror(sk.SK_ERR_BUSY) and "state" in sk.sk_strerror(sk.SK_ERR_STATE)
 
 
 def test_struct_layout_matches_header():
