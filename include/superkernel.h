@@ -218,6 +218,28 @@ sk_status sk_launch(sk_plan *plan, void *hip_stream);
  */
 sk_status sk_launch_sequential(sk_plan *plan, void *hip_stream);
 
+/*
+ * sk_launch for callers that cannot allocate device memory: code under HIP graph
+ * capture set-ups, tight serving loops, harnesses that forbid hipMalloc.  Takes a
+ * plan created with params->host_only = 1 (such a plan touches no device) and
+ * runs it as sk_launch would, with the plan's device tables (work records, tile
+ * queue, split-reduction counters and workspace) placed in a fixed array inside
+ * the library's code object, SK_STATIC_SCRATCH_BYTES per GPU, instead of an
+ * allocated block.  The call enqueues one copy of the plan's table image from
+ * host memory to that array and one kernel launch on `hip_stream`, and calls no
+ * hipMalloc, hipFree or other allocating routine; the first call on a device
+ * looks up the array's address and the device's size.  Same results as
+ * sk_launch, bit for bit (same table, same kernel).
+ * SK_ERR_UNSUPPORTED if tables plus workspace exceed SK_STATIC_SCRATCH_BYTES,
+ * SK_ERR_STATE for a plan that is not host-only or has stamps enabled.
+ * Every call on a GPU uses that GPU's one array: calls that overlap on one GPU
+ * (different streams, or different host threads without ordering) race and give
+ * wrong results; calls on one stream are ordered by the stream.  The plan must
+ * stay alive until the call has returned; A, B and C as for sk_launch.
+ */
+#define SK_STATIC_SCRATCH_BYTES (32u << 20)
+sk_status sk_launch_static(sk_plan *plan, void *hip_stream);
+
 /* Introspection of the packed plan (Section 5.3: what the runtime packing step produced; used to compare
  * the plan with a reference planner). */
 int64_t sk_plan_num_tiles(const sk_plan *plan);    /* < 0 on error */

@@ -16,6 +16,8 @@ from .binding import (  # noqa: F401
     sk_plan_destroy,
     sk_launch,
     sk_launch_sequential,
+    sk_launch_static,
+    SK_STATIC_SCRATCH_BYTES,
     sk_plan_num_tiles,
     sk_plan_num_problems,
     sk_plan_get_tiles,

@@ -16,6 +16,7 @@ SK_ERR_ALLOC, SK_ERR_HIP, SK_ERR_BUSY, SK_ERR_STATE = -4, -5, -6, -7
 
 EXPORTED_SYMBOLS = [
     "sk_plan_params_default", "sk_plan_create", "sk_plan_destroy", "sk_launch", "sk_launch_sequential",
+    "sk_launch_static",
     "sk_plan_num_tiles", "sk_plan_num_problems", "sk_plan_get_tiles", "sk_plan_get_order",
     "sk_plan_get_ranges", "sk_plan_grid", "sk_plan_get_stamps", "sk_release_cached_memory", "sk_strerror", "sk_last_error",
 ]
@@ -75,7 +76,7 @@ def lib():
     L.sk_plan_create.argtypes = [C.POINTER(sk_problem), C.c_int32, C.POINTER(PlanParams), C.POINTER(vp)]
     L.sk_plan_destroy.restype = C.c_int
     L.sk_plan_destroy.argtypes = [vp]
-    for name in ("sk_launch", "sk_launch_sequential"):
+    for name in ("sk_launch", "sk_launch_sequential", "sk_launch_static"):
         getattr(L, name).restype = C.c_int
         getattr(L, name).argtypes = [vp, vp]
     L.sk_plan_num_tiles.restype = C.c_int64
@@ -194,6 +195,13 @@ def sk_launch(plan: Plan, stream: int = 0) -> None:
 
 def sk_launch_sequential(plan: Plan, stream: int = 0) -> None:
     _check(lib().sk_launch_sequential(plan.handle, stream))
+
+
+def sk_launch_static(plan: Plan, stream: int = 0) -> None:
+    _check(lib().sk_launch_static(plan.handle, stream))
+
+
+SK_STATIC_SCRATCH_BYTES = 32 << 20
 
 
 def sk_plan_num_tiles(plan: Plan) -> int:

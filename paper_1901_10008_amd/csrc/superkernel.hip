@@ -158,6 +158,47 @@ TablePool &table_pool() {
 
 }  // namespace
 
+// Scratch of sk_launch_static: the table block (work records, queue counters, split-K arrival counters and
+// workspace) that sk_plan_create otherwise allocates, as a fixed array in the library's code object.  Each
+// GPU the library runs on holds its own copy, at its own address, until the process ends.
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)SK_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+namespace {
+
+// Device address of `scratch` and the compute-unit count, per device; looked up on the first
+// sk_launch_static of a device, with that device current.  (In host code the array's name is not a
+// device address: everything below uses the looked-up pointer.)
+struct StaticScratch {
+  static constexpr int MAX_DEVICES = 64;
+  std::mutex mu;
+  void *ptr[MAX_DEVICES] = {};
+  int cus[MAX_DEVICES] = {};
+  sk_status get(int device, void **out, int *cu_count) {
+    if (device < 0 || device >= MAX_DEVICES) return set_error(SK_ERR_UNSUPPORTED, "device index beyond 63");
+    std::lock_guard<std::mutex> g(mu);
+    if (!ptr[device]) {
+      void *p = nullptr;
+      hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+      if (e != hipSuccess || !p) return hip_error("hipGetSymbolAddress", e);
+      int n = 0;
+      e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, device);
+      if (e != hipSuccess) return hip_error("hipDeviceGetAttribute", e);
+      cus[device] = n;
+      ptr[device] = p;
+    }
+    *out = ptr[device];
+    *cu_count = cus[device];
+    return SK_OK;
+  }
+};
+StaticScratch &static_scratch() {
+  static StaticScratch *s = new StaticScratch();
+  return *s;
+}
+
+}  // namespace
+
 // The device side of one tile table: one allocation holding
 //   work records (tile + its operator's descriptor) | queue counters | tiles left per operator |
 //   completion stamps | split-K offsets | split-K arrival counters | split-K workspace
@@ -193,6 +234,9 @@ struct sk_plan {
   bool seq_ready = false;
   sk::HostPlan seq_host;
   DeviceTables seq_dev;
+  // sk_launch_static: host image of the uploaded part of the tables (built by sk_plan_create for host-only
+  // plans, pageable memory) and where its parts lie
+  std::vector<char> image;
   // which launch a new one must not overlap, and what sk_plan_destroy has to wait for
   hipEvent_t last_use = nullptr;  // recorded behind the latest launch made outside a stream capture
   sk::LaunchLedger ledger;
@@ -307,6 +351,18 @@ sk_status sk_plan_create(const sk_problem *problems, int32_t n, const sk_plan_pa
     if (((int64_t)t.m_len + t.n_len) * (int64_t)t.k_len * es > 65536) {
       plan->fixed_assignment = false;
       break;
+    }
+  }
+  if (prm.host_only && !plan->host.tiles.empty()) {
+    const TableLayout l = layout_of(plan->host);
+    if (l.total <= STATIC_SCRATCH_BYTES) {  // (larger plans cannot use sk_launch_static anyway)
+      try {
+        plan->image.resize(l.upload);
+      } catch (const std::bad_alloc &) {
+        delete plan;
+        return set_error(SK_ERR_ALLOC, "host allocation failed");
+      }
+      fill_image(plan->host, l, plan->image.data());
     }
   }
   if (!prm.host_only) {
@@ -506,6 +562,38 @@ sk_status sk_launch_sequential(sk_plan *plan, void *hip_stream) {
   }
   note_launch(plan, stream, capturing);  // also after a failure: some launches may be out
   return st;
+}
+
+sk_status sk_launch_static(sk_plan *plan, void *hip_stream) {
+  if (!plan) return set_error(SK_ERR_INVALID_ARG, "plan is null");
+  if (!plan->host.params.host_only)
+    return set_error(SK_ERR_STATE, "sk_launch_static takes a plan created with host_only = 1; use sk_launch for this one");
+  if (plan->host.params.stamps)
+    return set_error(SK_ERR_STATE, "completion stamps are not available through sk_launch_static");
+  if (plan->host.tiles.empty()) return SK_OK;
+  const TableLayout l = layout_of(plan->host);
+  if (l.total > STATIC_SCRATCH_BYTES)
+    return set_error(SK_ERR_UNSUPPORTED, "plan needs " + std::to_string(l.total) + " bytes of tables and workspace, the static scratch holds " +
+                                             std::to_string(STATIC_SCRATCH_BYTES));
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_error("hipGetDevice", e);
+  void *base = nullptr;
+  int cus = 0;
+  sk_status st = static_scratch().get(dev, &base, &cus);
+  if (st != SK_OK) return st;
+  const hipStream_t stream = (hipStream_t)hip_stream;
+  // Records, zeroed queue and arrival counters, workspace offsets: everything the kernel expects to find.
+  // (The split-K workspace behind them is written before it is read and needs no clearing.)
+  e = hipMemcpyAsync(base, plan->image.data(), l.upload, hipMemcpyHostToDevice, stream);
+  if (e != hipSuccess) return hip_error("hipMemcpyAsync", e);
+  DeviceTables dt;
+  bind_tables(dt, base, l);
+  const int64_t limit = plan->host.params.grid_limit > 0 ? plan->host.params.grid_limit : 2 * (int64_t)cus;
+  const int64_t ntiles = (int64_t)plan->host.tiles.size();
+  plan->grid_cap = limit;
+  plan->grid = (int)(ntiles < limit ? ntiles : limit);
+  return launch_range(plan, dt, stream, 0u, (uint32_t)ntiles, plan->grid, !plan->fixed_assignment, false);
 }
 
 int64_t sk_plan_num_tiles(const sk_plan *plan) { return plan ? (int64_t)plan->host.tiles.size() : -1; }
