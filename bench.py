@@ -29,7 +29,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=5, help="1..8 (default 5: 256 mixed operators, EDF)")
+    ap.add_argument("--config", type=int, default=5, help="1..10 (default 5: 256 mixed operators, EDF)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-baselines", action="store_true", help="skip sequential / multi-stream legs")

@@ -207,6 +207,19 @@ def _cfg8(seed):
     return [_conv("bf16", 56, 64, 64, 3, tag=f"resnet18-conv2_2-tenant{i}") for i in range(32)]
 
 
+def _cfg9(seed):
+    # Not a workload of the paper (its regime is small batches): sixteen square GEMMs far above the ridge
+    # of the roofline, the probe for what the LDS-tile class reaches when it is bound by the matrix cores.
+    return [_gemm("bf16", 2048, 2048, 2048, ("normal", 1.0), ("normal", 1.0 / math.sqrt(2048.0)), tag="square-gemm")
+            for _ in range(16)]
+
+
+def _cfg10(seed):
+    # The one layer of the residual-network mix whose arithmetic intensity lies above the ridge
+    # (3x3, 128 -> 128 channels on 28x28), one instance for each of 64 tenants.
+    return [_conv("bf16", 28, 128, 128, 3, tag=f"resnet50-conv3x3-28-tenant{i}") for i in range(64)]
+
+
 _RECIPES = {
     "cfg1_fp32_gemm4": _cfg1,
     "cfg2_bf16_gemm16": _cfg2,
@@ -216,6 +229,8 @@ _RECIPES = {
     "cfg6_lstm_matvec64": _cfg6,
     "cfg7_resnet_stride2_conv7": _cfg7,
     "cfg8_conv2_2_tenants32": _cfg8,
+    "cfg9_square_gemm16": _cfg9,
+    "cfg10_conv3x3_28_tenants64": _cfg10,
 }
 
 
