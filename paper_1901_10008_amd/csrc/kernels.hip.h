@@ -1051,325 +1051,6 @@ __device__ __forceinline__ void run_tile(const DevProblem &P, const sk_tile &T, 
 }
 
 // ---------------------------------------------------------------------------
-// LDS tiles fed by direct global -> LDS loads (gfx950: 16 bytes per lane)
-// ---------------------------------------------------------------------------
-// BM x BN outputs per workgroup (BM = 128 or 256, BN = 64 or 128), four waves as 2 x 2.  The
-// reduction advances in half-stages of 64 bytes of K per operand row.  A half-stage is loaded
-// by (BM + BN) / 16 wave-wide instructions, each of which moves 16 rows x 64 bytes from
-// global memory straight into 1 KB of LDS (lane l lands at byte 16 l of the block): no
-// registers hold operands on the way, no LDS store instructions are issued, and every slot
-// of the LDS ring except the one being multiplied holds loads in flight.
-//
-// LDS image of a half-stage: row r (activation rows first, then weight rows) at byte 64 r,
-// its four 16-byte pieces permuted: logical piece c sits at position c ^ ((r >> 2) & 3).  The
-// MFMA fragment read of 16 consecutive rows at one logical piece then touches 16 different
-// 16-byte bank groups (4 (r & 3) + position), and the load instruction that fills the rows
-// still writes its 1 KB contiguously: lane l loads row 16 j + l / 4, logical piece
-// (l & 3) ^ ((l >> 4) & 3).
-//
-// The loads are counted by hand (s_waitcnt vmcnt) and separated from their readers by bare
-// s_barrier instructions: the fence inside __syncthreads() would wait for every load in
-// flight, including the half-stages just requested.
-#ifndef SK_DMA_PPR64
-#define SK_DMA_PPR64 8
-#endif
-template <int N>
-__device__ __forceinline__ void wait_loads_but() {
-  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
-  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));  // vmcnt(N), nothing else
-}
-__device__ __forceinline__ void load_to_lds(uintptr_t gaddr, unsigned char *lds_block) {
-  __builtin_amdgcn_global_load_lds((const void SK_GLOBAL *)gaddr, (void __attribute__((address_space(3))) *)lds_block, 16,
-                                   0, 0);
-}
-
-template <int DT, int BM, int BN, int PPR>
-__device__ __forceinline__ void run_tile_dma(const DevProblem &P, const sk_tile &T, const SplitK &sp, unsigned char *lds,
-                                             uint32_t *s_flag, Prefetch &pf) {
-  constexpr int ES = Elem<DT>::ES;
-  constexpr int CE = 16 / ES;
-  constexpr int HK = PPR * CE;               // reduction elements per stage
-  constexpr int RB = PPR * 16;               // bytes of K per row and stage
-  constexpr int RPI_LD = 64 / PPR;           // rows per load instruction
-  constexpr int KKS = PPR / 2;               // MFMA steps per stage
-  constexpr int FM = BM / 64, FN = BN / 64;  // 32x32 blocks per wave along m and n
-  constexpr int NA = BM / RPI_LD / 4, NBW = BN / RPI_LD / 4; // load instructions per wave and stage: activations, weights
-  constexpr int NPW = NA + NBW;
-  constexpr int SLOT = (BM + BN) * RB;       // bytes of a stage
-  constexpr int NS = LDS_TILE_BYTES / SLOT;  // ring slots
-  static_assert(BM % 64 == 0 && BN % 64 == 0, "whole 32x32 blocks per wave, whole load instructions per wave");
-  static_assert(NS >= 3, "at least two half-stages in flight");
-  static_assert((NS - 2) * NPW < 64, "load counter");
-
-  const int tid = pf.tid;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int lane = tid & 63;
-  const int wm = wave & 1, wn = wave >> 1;
-  const int l32 = lane & 31, half = lane >> 5;
-
-  const int m0 = (int)T.m0, n0 = (int)T.n0;
-  const int m_end = m0 + (int)T.m_len, n_end = n0 + (int)T.n_len;
-  const int k_begin = (int)T.k0, k_stop = (int)T.k0 + (int)T.k_len;
-
-  // ---- what this lane loads: row 16 (wave + 4 i) + lane / 4 of the activation block (i < NA) or of the
-  // weight block, logical piece c_log of every half-stage
-  const int lrow = lane / PPR;
-  // position p of row r holds logical piece p ^ swizzle(r): (r >> 2) & 3 for 64-byte rows, (r >> 1) & 7 for 128-byte rows
-  // (the rows of a wave's load instructions are 16 (wave + 4 i) + lane / 4, resp. 8 (wave + 4 i) + lane / 8:
-  // the swizzle of a lane's row is the same for all of them)
-  const int c_log = PPR == 4 ? (lane & 3) ^ ((lane >> 4) & 3) : (lane & 7) ^ (((lane >> 4) & 3) | ((wave & 1) << 2));
-  const bool gvec = P.gather != 0;
-  uintptr_t pa[NA];       // row start (convolution: the pixel under filter tap (0,0), may lie outside the image)
-  int hb[NA], wb[NA];     // convolution: ho*stride - pad_h, wo*stride - pad_w
-#pragma unroll
-  for (int i = 0; i < NA; ++i) {
-    int m = m0 + RPI_LD * (wave + 4 * i) + lrow;
-    if (m >= m_end) m = m_end - 1;  // rows past the edge repeat the last row; never stored
-    const RowA r = row_of(P, m);
-    pa[i] = (uintptr_t)P.A + (uintptr_t)(r.base * ES);
-    hb[i] = r.hb;
-    wb[i] = r.wb;
-  }
-  uintptr_t pb[NBW];
-#pragma unroll
-  for (int i = 0; i < NBW; ++i) {
-    int n = n0 + RPI_LD * (wave + 4 * i) + lrow;
-    if (n >= n_end) n = n_end - 1;
-    pb[i] = (uintptr_t)P.B + (uintptr_t)((int64_t)n * P.ldb * ES);
-  }
-  // position of this lane's piece in the patch row: tap (g_r, g_s), channel g_c;
-  // tap_off = ((g_r*W + g_s)*Cin + g_c) elements from the pixel under tap (0,0)
-  int g_r = 0, g_s = 0, g_c = 0;
-  int64_t tap_off = 0;
-  const int64_t next_filter_row = (int64_t)(P.W - P.S) * P.Cin;
-  int k_load = k_begin + c_log * CE;  // reduction index of this lane's piece in the next half-stage to load
-  if (gvec) {
-    const int tap = k_load / P.Cin;
-    g_c = k_load - tap * P.Cin;
-    g_r = tap / P.S;
-    g_s = tap - g_r * P.S;
-    tap_off = ((int64_t)g_r * P.W + g_s) * P.Cin + g_c;
-  }
-  const uintptr_t zeros = zero_piece_address();
-  unsigned char *const my_blocks = lds + wave * 1024;  // + slot*SLOT + 4096*i (activations), + BM*64 + 4096*i (weights)
-  // Loads are unconditional (half-stages past the end of the reduction read the piece of zeros and are never
-  // multiplied), so the number of loads in flight is the same on every path.
-  auto issue = [&](int slot) {
-    const bool in = k_load < k_stop;
-    unsigned char *dst = my_blocks + slot * SLOT;
-    if (gvec) {
-#pragma unroll
-      for (int i = 0; i < NA; ++i) {
-        const bool ok = in && (unsigned)(hb[i] + g_r) < (unsigned)P.H && (unsigned)(wb[i] + g_s) < (unsigned)P.W;
-        load_to_lds(ok ? pa[i] + (uintptr_t)(tap_off * ES) : zeros, dst + 4096 * i);
-      }
-      g_c += HK;
-      tap_off += HK;
-      while (g_c >= P.Cin) {
-        g_c -= P.Cin;
-        if (++g_s == P.S) {
-          g_s = 0;
-          ++g_r;
-          tap_off += next_filter_row;
-        }
-      }
-    } else {
-#pragma unroll
-      for (int i = 0; i < NA; ++i) load_to_lds(in ? pa[i] + (uintptr_t)((int64_t)k_load * ES) : zeros, dst + 4096 * i);
-    }
-#pragma unroll
-    for (int i = 0; i < NBW; ++i)
-      load_to_lds(in ? pb[i] + (uintptr_t)((int64_t)k_load * ES) : zeros, dst + BM * RB + 4096 * i);
-    k_load += HK;
-  };
-
-  f32x16 acc[FN][FM];
-#pragma unroll
-  for (int fn = 0; fn < FN; ++fn)
-#pragma unroll
-    for (int fm = 0; fm < FM; ++fm)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) acc[fn][fm][i] = 0.f;
-
-  // fragment addresses inside a slot: row (w*F + f)*32 + l32, logical piece 2 kk + half at position
-  // (2 kk + half) ^ swizzle(row)
-  const int swz = PPR == 4 ? (l32 >> 2) & 3 : (l32 >> 1) & 7;
-  const int frag_row = l32 * RB;
-  const int frag_pos = half ^ swz;  // position of piece `half`; piece 2 kk + half is at frag_pos ^ 2 kk
-  constexpr int FBLK = 32 * RB;     // bytes of a 32-row block
-  const int a_base = wm * FM * FBLK;
-  const int b_base = BM * RB + wn * FN * FBLK;
-
-  const int nh = (k_stop - k_begin + HK - 1) / HK;
-  // the previous tile's readers of this LDS buffer have passed the barrier at the end of their tile
-#pragma unroll
-  for (int u = 0; u < NS - 1; ++u) issue(u);
-  int slot = 0;
-  for (int h = 0; h < nh; ++h) {
-    pf.at_step(h, nh, CLAIM_LEAD * 8 / PPR, ISSUE_GAP * 8 / PPR);
-    wait_loads_but<(NS - 2) * NPW>();   // this wave's loads of half-stage h have landed
-    __builtin_amdgcn_s_barrier();       // ... and everyone's; everyone is done with half-stage h-1
-    issue(slot == 0 ? NS - 1 : slot - 1);  // half-stage h+NS-1 into the slot half-stage h-1 used
-    const unsigned char *la = lds + slot * SLOT + a_base;
-    const unsigned char *lb = lds + slot * SLOT + b_base;
-    // the fragments of step kk+1 are requested before the MFMAs of step kk
-    u32x4 fa[2][FM], fb[2][FN];
-    auto frag = [&](int kk, u32x4(&xa)[FM], u32x4(&xb)[FN]) {
-      const int off = frag_row + ((frag_pos ^ (2 * kk)) << 4);
-#pragma unroll
-      for (int fm = 0; fm < FM; ++fm) xa[fm] = *(const u32x4 *)(la + fm * FBLK + off);
-#pragma unroll
-      for (int fn = 0; fn < FN; ++fn) xb[fn] = *(const u32x4 *)(lb + fn * FBLK + off);
-    };
-    frag(0, fa[0], fb[0]);
-#pragma unroll
-    for (int kk = 0; kk < KKS; ++kk) {
-      if (kk + 1 < KKS) frag(kk + 1, fa[(kk + 1) & 1], fb[(kk + 1) & 1]);
-#pragma unroll
-      for (int fn = 0; fn < FN; ++fn)
-#pragma unroll
-        for (int fm = 0; fm < FM; ++fm) mma32<DT>(fb[kk & 1][fn], fa[kk & 1][fm], acc[fn][fm]);
-    }
-    slot = slot + 1 == NS ? 0 : slot + 1;
-  }
-  // the loads still in flight (zeros, past the end of the reduction) must land before the buffer is reused
-  wait_loads_but<0>();
-  __syncthreads();
-
-  if (T.S > 1) {
-    // A slice of a split reduction: same hand-over as in the skinny classes.  Partial sums go to
-    // the workspace in register layout with device-scope stores (a slice is FN*FM*4 blocks of
-    // 64 x 16 bytes per wave); the last slice to arrive adds all of them in slice order.
-    constexpr int PER_WAVE = FN * FM * 4;          // 1 KB blocks per wave and slice
-    constexpr int PER_SLICE = 4 * PER_WAVE * 64;   // f32x4 units per slice
-    f32x4 *mine = sp.ws + sp.ws_off[T.out_tile_id] + wave * PER_WAVE * 64;
-#pragma unroll
-    for (int fn = 0; fn < FN; ++fn)
-#pragma unroll
-      for (int fm = 0; fm < FM; ++fm)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const f32x4 v = {acc[fn][fm][4 * j], acc[fn][fm][4 * j + 1], acc[fn][fm][4 * j + 2], acc[fn][fm][4 * j + 3]};
-          store_device_scope(mine + (size_t)T.ks_idx * PER_SLICE + ((fn * FM + fm) * 4 + j) * 64, lane, v);
-        }
-    __builtin_amdgcn_s_waitcnt(0);  // all counters to zero: the stores above have completed
-    __syncthreads();
-    if (tid == 0)
-      *s_flag = __hip_atomic_fetch_add(&sp.arrive[T.out_tile_id], 1u, SK_ARRIVE_ORDER, __HIP_MEMORY_SCOPE_AGENT);
-    __syncthreads();
-    if (*s_flag != (uint32_t)T.S - 1) return;
-#pragma unroll
-    for (int fn = 0; fn < FN; ++fn)
-#pragma unroll
-      for (int fm = 0; fm < FM; ++fm)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) acc[fn][fm][i] = 0.f;
-    for (int s2 = 0; s2 < T.S; ++s2) {
-#pragma unroll
-      for (int fn = 0; fn < FN; ++fn)
-#pragma unroll
-        for (int fm = 0; fm < FM; ++fm)
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const f32x4 v = load_device_scope(mine + (size_t)s2 * PER_SLICE + ((fn * FM + fm) * 4 + j) * 64, lane);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) acc[fn][fm][4 * j + e] += v[e];
-          }
-    }
-    if (tid == 0)  // re-arm for the next launch
-      __hip_atomic_store(&sp.arrive[T.out_tile_id], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  }
-
-  // lane holds, per (fn, fm): row m = l32, columns 8*(i/4) + 4*half + (i%4)
-  //
-  // Written from the accumulators a store instruction would cover 32 rows with 16 bytes each.
-  // Where C allows 16-byte stores the tile goes through LDS instead (free by now) and leaves as
-  // whole rows, 128 rows at a time (the rows of the two waves with the same wm).
-  constexpr int OROW = BN * ES + 16;  // padded row of the output tile in LDS
-  static_assert(128 * OROW <= LDS_TILE_BYTES, "128 output rows do not fit the LDS buffer");
-  const bool wide = ((uintptr_t)P.C % 16 == 0) && ((P.ldc * ES) % 16 == 0);
-  if (wide) {
-    constexpr int PIECES = BN * ES / 16;             // 16-byte pieces per output row
-    constexpr int RPI = WG_THREADS / PIECES;         // rows per store instruction
-    const int pc = tid % PIECES, pr = tid / PIECES;
-    const int n = n0 + pc * CE;
-#pragma unroll
-    for (int part = 0; part < BM / 128; ++part) {
-      if (part) __syncthreads();  // the rows of the part before have been read
-      // rows part*128 .. part*128+127 of the tile: for BM = 256 those of the waves with wm == part
-      // (FM = 4 blocks of 32), for BM = 128 those of both wm (FM = 2 blocks each)
-      if (BM == 128 || wm == part) {
-#pragma unroll
-        for (int fm = 0; fm < FM; ++fm) {
-          const int r = (BM == 128 ? (wm * FM + fm) * 32 : fm * 32) + l32;
-#pragma unroll
-          for (int fn = 0; fn < FN; ++fn) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-              const int c = (wn * FN + fn) * 32 + 8 * j + 4 * half;
-              unsigned char *q = lds + r * OROW + c * ES;
-              if constexpr (ES == 4) {
-                *(f32x4 *)q = f32x4{acc[fn][fm][4 * j], acc[fn][fm][4 * j + 1], acc[fn][fm][4 * j + 2], acc[fn][fm][4 * j + 3]};
-              } else {
-                u32x2 o;
-                o.x = cvt_pack<DT>(acc[fn][fm][4 * j], acc[fn][fm][4 * j + 1]);
-                o.y = cvt_pack<DT>(acc[fn][fm][4 * j + 2], acc[fn][fm][4 * j + 3]);
-                *(u32x2 *)q = o;
-              }
-            }
-          }
-        }
-      }
-      __syncthreads();
-#pragma unroll
-      for (int i = 0; i < 128 / RPI; ++i) {
-        const int r = pr + i * RPI;
-        const int m = m0 + part * 128 + r;
-        if (m < m_end && n < n_end) {
-          const u32x4 v = *(const u32x4 *)(lds + r * OROW + pc * 16);
-          char SK_GLOBAL *dst = as_global_mut<char>(P.C) + ((int64_t)m * P.ldc + n) * ES;
-          if (n + CE <= n_end) {
-            *(u32x4 SK_GLOBAL *)dst = v;
-          } else {
-            // ragged right edge: element by element
-#pragma unroll
-            for (int e = 0; e < CE; ++e) {
-              if (n + e < n_end) {
-                if constexpr (ES == 4)
-                  ((uint32_t SK_GLOBAL *)dst)[e] = v[e];
-                else
-                  ((uint16_t SK_GLOBAL *)dst)[e] = (uint16_t)(v[e / 2] >> (16 * (e & 1)));
-              }
-            }
-          }
-        }
-      }
-    }
-    // (the barrier at the end of every tile keeps the next tile's LDS writes behind these reads)
-    return;
-  }
-  const bool vec_c = (P.flags & FLAG_VEC_C) != 0;
-#pragma unroll
-  for (int fm = 0; fm < FM; ++fm) {
-    const int m = m0 + (wm * FM + fm) * 32 + l32;
-    if (m < m_end) {
-      const int64_t row_off = (int64_t)m * P.ldc;
-#pragma unroll
-      for (int fn = 0; fn < FN; ++fn) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int n = n0 + (wn * FN + fn) * 32 + 8 * j + 4 * half;
-          if (n < n_end) {
-            f32x4 v = {acc[fn][fm][4 * j], acc[fn][fm][4 * j + 1], acc[fn][fm][4 * j + 2], acc[fn][fm][4 * j + 3]};
-            store4<DT>(P.C, row_off, n, n_end, v, vec_c);
-          }
-        }
-      }
-    }
-  }
-}
-
-// ---------------------------------------------------------------------------
 // dispatch and the persistent shell
 // ---------------------------------------------------------------------------
 // ---------------------------------------------------------------------------
@@ -1702,22 +1383,10 @@ __device__ __forceinline__ void run_class(const DevProblem &P, const sk_tile &T,
     run_skinny<DT, 2>(P, T, sp, lds, s_flag, pf);
   } else if (cls == 6) {
     run_skinny<DT, 4>(P, T, sp, lds, s_flag, pf);
-  } else if (cls == 11) {
-    run_tile_dma<DT, 256, 128, 4>(P, T, sp, lds, s_flag, pf);
-  } else if (cls == 12) {
-    run_tile_dma<DT, 256, 64, 4>(P, T, sp, lds, s_flag, pf);
   } else if (cls == CLS_TILE_128x64) {
-#ifndef SK_DMA_TILES
     run_tile<DT, 128, 64, 2, 2>(P, T, sp, lds, s_flag, pf);
-#else
-    run_tile_dma<DT, 128, 64, SK_DMA_PPR64>(P, T, sp, lds, s_flag, pf);
-#endif
   } else {
-#ifndef SK_DMA_TILES
     run_tile<DT, 128, 128, 2, 2>(P, T, sp, lds, s_flag, pf);
-#else
-    run_tile_dma<DT, 128, 128, 4>(P, T, sp, lds, s_flag, pf);
-#endif
   }
 }
 

@@ -12,7 +12,6 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
-#include <cstdlib>
 #include <limits>
 #include <numeric>
 
@@ -266,10 +265,6 @@ sk_status plan_host(const sk_problem *problems, int32_t n, const sk_plan_params 
       cls = c.Ng <= 64 ? CLS_TILE_128x64 : CLS_TILE_128x128;
       BM = 128;
       BN = c.Ng <= 64 ? 64 : 128;
-      if (getenv("SK_EXP_TALL") && c.Mg > 128) {
-        cls = c.Ng <= 64 ? 12 : 11;
-        BM = 256;
-      }
       // operand bytes of one tile over the whole reduction; far beyond the target: cut the reduction
       const int64_t tb = (BM + BN) * c.Kg * es;
       if (tb > 2 * T) {
@@ -305,7 +300,7 @@ sk_status plan_host(const sk_problem *problems, int32_t n, const sk_plan_params 
           // partial sums of this rectangle: S slices x 4 waves x (2 * rm) accumulators x 64 lanes, 16 bytes each
           // (LDS tiles: S slices x 256 threads x 16 accumulator quads, 8 for the 64-column tile)
           out.ws_off.push_back((uint32_t)out.ws_f32x4);
-          out.ws_f32x4 += cls == 11 ? S * 8192 : cls == 12 ? S * 4096 : cls == CLS_TILE_128x128  ? S * 4096
+          out.ws_f32x4 += cls == CLS_TILE_128x128  ? S * 4096
                           : cls == CLS_TILE_128x64 ? S * 2048
                                                    : S * 4 * 2 * ((int64_t)1 << (cls / 3)) * 64;
         } else {
