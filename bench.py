@@ -182,9 +182,7 @@ def main():
         "per_problem_roofline": {"t_roof_ms": round(t_roof * 1e3, 5), "t_overlap_bound_ms": round(t_lb * 1e3, 5),
                                  "roofline_tflops": round(flops / t_roof / 1e12, 2),
                                  "frac": round(t_roof / (kern_ms * 1e-3), 4)},
-        "roofline": {"bound": "hbm", "achieved": round(abytes / (kern_ms * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS,
-                     "unit": "GB/s", "frac": round(abytes / (kern_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
-                     "traffic": measured_traffic(name)},
+        "roofline": roofline(specs, flops, abytes, kern_ms, name, max(1, args.replicate), overrides),
     }
 
     if not args.no_baselines:
@@ -281,10 +279,10 @@ def main():
             out["deadlines"] = res
 
     if not args.no_ceilings:
-        out["ceilings"] = measured_ceilings(torch, out["roofline"]["achieved"], out["value"])
+        out["ceilings"] = measured_ceilings(torch, abytes / (kern_ms * 1e-3) / 1e9, out["value"])
         tr = out["roofline"]["traffic"]
         if tr and "achieved_over_stream_read" in out["ceilings"]:
-            best = out["roofline"]["achieved"] / out["ceilings"]["achieved_over_stream_read"]
+            best = max(out["ceilings"]["stream_read_GBs_rows_of_16384B"], out["ceilings"]["stream_read_GBs_rows_of_2048B"])
             out["ceilings"]["measured_traffic_over_stream_read"] = round(tr / (kern_ms * 1e-3) / 1e9 / best, 4)
 
     if not args.no_cpu_baseline:
@@ -323,20 +321,67 @@ def measured_ceilings(torch, achieved_gbs, achieved_tflops):
         res["mfma_bf16_TFLOPs"] = round(v.value, 1)
         best = max(res["stream_read_GBs_rows_of_16384B"], res["stream_read_GBs_rows_of_2048B"])
         res["achieved_over_stream_read"] = round(achieved_gbs / best, 4)
+        res["achieved_over_mfma_loop"] = round(achieved_tflops / res["mfma_bf16_TFLOPs"], 4)
         del buf, sink
         return res
     except OSError as e:
         return {"error": str(e)[:200]}
 
 
-def measured_traffic(workload):
-    """HBM bytes per superkernel launch from the committed rocprofv3 --pmc summary (FETCH_SIZE and
-    WRITE_SIZE, scaled by what the same counters read for a plain copy of known size), or None."""
-    path = os.path.join(ROOT, "profiles", "superkernel_cfg5_traffic.txt")
+def roofline(specs, flops, abytes, kern_ms, workload, replicate, overrides):
+    """The roofline of the superkernel launch: which resource bounds the whole mix (sum of bytes over the
+    HBM peak against sum of flops over the matrix-core peak of each operator's type), what the launch
+    achieves of it (algorithmic bytes or flops over the HIP-event time of the launch), and the HBM
+    traffic the hardware counters saw for this workload and this kernel source, if a profile is committed."""
+    import workloads
+
+    t_bytes = abytes / (PEAK_HBM_GBS * 1e9)
+    t_flops = sum(workloads.flops(s) / PEAK_FLOPS[s.dtype] for s in specs)
+    tr = measured_traffic(workload, replicate, overrides)
+    if t_bytes >= t_flops:
+        ach = abytes / (kern_ms * 1e-3) / 1e9
+        out = {"bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+               "frac": round(ach / PEAK_HBM_GBS, 4)}
+    else:
+        dts = {s.dtype for s in specs}
+        peak = PEAK_FLOPS[next(iter(dts))] / 1e12 if len(dts) == 1 else flops / t_flops / 1e12
+        ach = flops / (kern_ms * 1e-3) / 1e12
+        out = {"bound": "mfma", "achieved": round(ach, 1), "peak": round(peak, 1), "unit": "TFLOP/s",
+               "frac": round(ach / peak, 4)}
+    out["traffic"] = tr["hbm_bytes_per_launch"] if tr else None
+    out["traffic_source"] = ({k: tr[k] for k in ("workload", "kernel", "kernel_source_sha256", "profile")} if tr else
+                             "no committed counter profile matches this workload, launch configuration and kernel source")
+    return out
+
+
+def kernel_source_hash():
+    """SHA-256 over the sources the superkernel is built from: a counter profile is only quoted for the
+    kernel it was taken from."""
+    import hashlib
+
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_1901_10008_amd", "csrc")
+    for f in ("kernels.hip.h", "superkernel.hip", "planner.cpp", "sk_internal.h"):
+        with open(os.path.join(csrc, f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()
+
+
+def measured_traffic(workload, replicate=1, overrides=None):
+    """HBM bytes per superkernel launch from the committed rocprofv3 --pmc summaries (FETCH_SIZE and
+    WRITE_SIZE, scaled by what the same counters read for a plain copy of known size): the record for
+    this workload, replication and default plan parameters, and only if it was taken from the kernel
+    source that is in the tree now.  None otherwise."""
+    path = os.path.join(ROOT, "profiles", "superkernel_traffic.json")
     try:
         with open(path) as f:
-            rec = json.load(f)
-        return rec[workload]["hbm_bytes_per_launch"]
+            recs = json.load(f)
+        if overrides:
+            return None
+        rec = recs[f"{workload} x{replicate}"]
+        if rec["kernel_source_sha256"] != kernel_source_hash():
+            return None
+        return rec
     except (OSError, KeyError, ValueError):
         return None
 

@@ -197,6 +197,43 @@ def test_tuner_sweeps_plan_parameters():
     assert rep["solo_penalty_with_mix_best"] >= 1.0 and rep["mix_penalty_with_solo_best"] >= 1.0
 
 
+def test_tuned_parameters_are_picked_up_by_a_second_process(tmp_path):
+    """The tuning phase leaves its result in a file (Section 5.3: the runtime applies pre-computed parameters); a
+    second process that only knows the operator shapes finds the record and plans with it; launched with the
+    loaded parameters the outputs are still the oracle's."""
+    import json
+    import subprocess
+    import sys
+    from paper_1901_10008_amd import tune
+    specs = workloads.config(2, seed=0)[:8] + workloads.config(4, seed=0)[:6]
+    b = H.Batch(specs, seed=0)
+    path = str(tmp_path / "tuned.jsonl")
+    grid = {"tile_bytes_max": (256 << 10, 2 << 20), "skinny_max_m": (32, 64)}
+    best, res = tune.tune(b.problems, grid, rounds=2, launches=2, stream=H.stream_handle())
+    tune.save(path, b.problems, best, res[0][1], note="test")
+    # the other process: shapes only (made-up addresses), no GPU work
+    child = (
+        "import json, sys, workloads, paper_1901_10008_amd as sk\n"
+        "from paper_1901_10008_amd import tune\n"
+        "specs = workloads.config(2, seed=0)[:8] + workloads.config(4, seed=0)[:6]\n"
+        "probs = [sk.make_problem(s, 4096 * (3 * i + 1), 4096 * (3 * i + 2), (1 << 40) + (i << 32)) for i, s in enumerate(specs)]\n"
+        "p = tune.tuned_params(probs, sys.argv[1])\n"
+        "p.host_only = 1\n"
+        "plan = sk.sk_plan_create(probs, p)\n"
+        "print(json.dumps({'tile_bytes_max': p.tile_bytes_max, 'skinny_max_m': p.skinny_max_m, 'tiles': sk.sk_plan_num_tiles(plan)}))\n")
+    out = subprocess.run([sys.executable, "-c", child, path], capture_output=True, text=True, cwd=os.path.dirname(H.__file__) + "/..")
+    assert out.returncode == 0, out.stderr
+    seen = json.loads(out.stdout.strip().splitlines()[-1])
+    assert seen["tile_bytes_max"] == best["tile_bytes_max"] and seen["skinny_max_m"] == best["skinny_max_m"]
+    loaded = tune.tuned_params(b.problems, path)
+    with sk.sk_plan_create(b.problems, loaded, keepalive=b) as plan:
+        assert sk.sk_plan_num_tiles(plan) == seen["tiles"]
+        b.reset_outputs()
+        sk.sk_launch(plan, H.stream_handle())
+        _sync()
+        H.check_against_oracle(b, "tuned parameters from the file")
+
+
 def test_arrival_trace_policies():
     """Operators arriving over time under the three batching policies: every arrival is served, and whatever
     the batching, the outputs are the oracle's."""

@@ -38,3 +38,38 @@ def test_ceilings_library_exports_its_two_calls():
     path = os.path.join(os.path.dirname(paper_1901_10008_amd.__file__), "libsk_ceilings.so")
     lib = ctypes.CDLL(path)   # built by paper_1901_10008_amd.build; loading needs no GPU
     assert lib.sk_ceiling_stream_read and lib.sk_ceiling_mfma_bf16
+
+
+def test_tuned_parameters_round_trip_through_a_file(tmp_path):
+    import ctypes
+    import paper_1901_10008_amd as sk
+    from workloads import Problem
+    specs = [Problem(op="gemm", dtype="bf16", M=4, N=512, K=1024), Problem(op="gemm", dtype="f16", M=70, N=256, K=128),
+             Problem(op="conv", dtype="bf16", Nb=1, H=14, W=14, Cin=64, Cout=64, R=3, S=3, pad_h=1, pad_w=1)]
+    probs = [sk.make_problem(s, 0x1000 * (i + 1), 0x100000 * (i + 1), 0x10000000 * (i + 1)) for i, s in enumerate(specs)]
+    path = str(tmp_path / "sub" / "tuned.jsonl")
+    assert tune.load(path) == {} and tune.tuned_params(probs, path) is None
+    sig = tune.save(path, probs, {"tile_bytes_max": 1 << 20, "tail_div": 0, "skinny_max_m": 32}, 12.5, note="first")
+    # the signature ignores order and addresses, not shapes
+    moved = [sk.make_problem(s, 0x77000, 0x88000, 0x99000 + 0x100000 * i) for i, s in enumerate(reversed(specs))]
+    assert tune.signature(moved) == sig == tune.signature(probs)
+    assert tune.signature(probs[:2]) != sig
+    got = tune.tuned_params(moved, path)
+    assert (got.tile_bytes_max, got.tail_div, got.skinny_max_m) == (1 << 20, 0, 32)
+    assert got.balance_div == sk.sk_plan_params_default().balance_div           # untouched fields keep their defaults
+    tune.save(path, probs, {"tile_bytes_max": 2 << 20}, 11.0, note="second")    # a later record of the same mix wins
+    assert tune.tuned_params(probs, path).tile_bytes_max == 2 << 20 and len(tune.load(path)) == 1
+    assert tune.tuned_params(probs[:1], path) is None
+    # a plan made with the loaded parameters is the plan made with the same values given by hand (host-only: no GPU)
+    loaded = tune.tuned_params(probs, path)
+    loaded.host_only = 1
+    with sk.sk_plan_create(probs, loaded) as a, \
+            sk.sk_plan_create(probs, sk.sk_plan_params_default(host_only=1, tile_bytes_max=2 << 20)) as b:
+        assert sk.sk_plan_get_tiles(a) == sk.sk_plan_get_tiles(b)
+
+
+def test_cotenancy_table_marks_both_optima():
+    rep = {"targets": [1024, 2048], "solo_us": [10.0, 12.0], "mix_us": [90.0, 80.0], "solo_best_target": 1024,
+           "mix_best_target": 2048, "solo_penalty_with_mix_best": 1.2, "mix_penalty_with_solo_best": 1.125}
+    txt = tune.cotenancy_table(rep, "operator 0")
+    assert "best alone" in txt.splitlines()[3] and "best for the mix" in txt.splitlines()[4] and "x1.2;" in txt
