@@ -265,6 +265,70 @@ int32_t sk_plan_grid(const sk_plan *plan);
 sk_status sk_plan_get_stamps(sk_plan *plan, uint64_t *done_ticks, uint64_t *start_tick,
                              double *ticks_per_ms);
 
+/*
+ * Operators that arrive over time (Section 5, items (a) and (b); Section 5.2): a queue in front of the
+ * planner that decides which of the operators submitted so far go into the next superkernel.
+ *
+ *   SK_QUEUE_SEQUENTIAL  one launch per operator in arrival order: the time multiplexing of Section 4.1
+ *   SK_QUEUE_COALESCE    whenever the device is about to run dry, everything that has arrived and whose
+ *                        output buffer is free goes into one plan, earliest deadline first
+ *   SK_QUEUE_OOO         as COALESCE, but a launch is closed once its estimated duration reaches cap_ms:
+ *                        operators are taken in deadline order and those with the most slack wait, so
+ *                        that an urgent operator arriving meanwhile never sits behind a long launch
+ *                        (the reordering in time of Section 5.2)
+ *
+ * The queue runs in the caller's thread: sk_queue_submit and sk_queue_poll both retire finished launches
+ * and plan and launch the next one when it is due (shortly before the running launch is expected to end:
+ * operand bytes / bytes_per_ms, corrected by a running ratio of measured to estimated durations), so the
+ * caller keeps calling sk_queue_poll.  A queue belongs to one host thread at a time.  Launches go to
+ * `hip_stream` (NULL = the default stream; a stream of its own keeps reading results from waiting for the
+ * launch queued behind).  Two operators with the same C pointer are never in flight together: the later
+ * one waits for a later launch.  Operand pointers as for sk_problem; they stay valid until the operator's
+ * completion has been returned.
+ *
+ * sk_queue_submit: n operators arriving now, budget_ms[i] their latency budgets from now (NULL = none);
+ *   tickets[i] (may be NULL) identify them in completions.  The problems are copied.
+ * sk_queue_poll: up to `cap` completions into out[], *n_out of them.  wait = 0: never blocks; wait = 1:
+ *   blocks until at least one completion can be returned or the queue is empty.  latency_ms runs from the
+ *   submit call to the retirement of the operator's last tile (completion stamps of the launch, anchored at
+ *   the host time at which the launch was seen complete); met = latency_ms <= budget_ms, or -1 for an
+ *   operator whose batch could not be planned (the planner's status is then returned by the call that
+ *   tried, and sk_last_error() has the detail).
+ * sk_queue_destroy: waits for the launches in flight; operators not launched yet are dropped.
+ */
+typedef enum { SK_QUEUE_SEQUENTIAL = 0, SK_QUEUE_COALESCE = 1, SK_QUEUE_OOO = 2 } sk_queue_policy;
+
+typedef struct {
+  int32_t policy;         /* sk_queue_policy                                                              */
+  int32_t depth;          /* launches queued on the device at once; 0 = 2 (16 for SK_QUEUE_SEQUENTIAL)    */
+  double cap_ms;          /* SK_QUEUE_OOO: estimated duration at which a launch is closed, default 0.5    */
+  double bytes_per_ms;    /* duration estimate of a launch: operand bytes / this, default 5.5e9           */
+  double launch_floor_ms; /* no launch is estimated shorter than this, default 0.02                       */
+} sk_queue_params;
+
+typedef struct {
+  uint64_t ticket;
+  double latency_ms;
+  double budget_ms; /* +inf if none was given */
+  int32_t met;
+  int32_t launch;   /* running number of the launch that served the operator */
+} sk_completion;
+
+typedef struct {
+  int64_t submitted, completed, launches, met;
+  double device_busy_ms; /* sum over coalesced launches of (last completion stamp - start stamp) */
+  double span_ms;        /* first submit to the latest completion seen                           */
+} sk_queue_stats;
+
+typedef struct sk_queue sk_queue; /* opaque, owned by the library */
+
+void sk_queue_params_default(sk_queue_params *params);
+sk_status sk_queue_create(const sk_queue_params *params, void *hip_stream, sk_queue **out);
+sk_status sk_queue_submit(sk_queue *queue, const sk_problem *ops, const double *budget_ms, int32_t n, uint64_t *tickets);
+sk_status sk_queue_poll(sk_queue *queue, int32_t wait, sk_completion *out, int32_t cap, int32_t *n_out);
+sk_status sk_queue_get_stats(const sk_queue *queue, sk_queue_stats *stats);
+sk_status sk_queue_destroy(sk_queue *queue);
+
 const char *sk_strerror(sk_status status);
 const char *sk_last_error(void);
 

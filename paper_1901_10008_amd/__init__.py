@@ -33,4 +33,7 @@ from .binding import (  # noqa: F401
     DTYPE_CODE,
     SK_OK, SK_ERR_INVALID_ARG, SK_ERR_UNSUPPORTED, SK_ERR_OVERLAP, SK_ERR_ALLOC, SK_ERR_HIP, SK_ERR_BUSY, SK_ERR_STATE,
     EXPORTED_SYMBOLS,
+    Queue, QueueParams, QueueStats, sk_completion, sk_problem,
+    sk_queue_params_default, sk_queue_create, sk_queue_submit, sk_queue_poll, sk_queue_get_stats, sk_queue_destroy,
+    SK_QUEUE_SEQUENTIAL, SK_QUEUE_COALESCE, SK_QUEUE_OOO, QUEUE_POLICY,
 )

@@ -19,7 +19,10 @@ EXPORTED_SYMBOLS = [
     "sk_launch_static",
     "sk_plan_num_tiles", "sk_plan_num_problems", "sk_plan_get_tiles", "sk_plan_get_order",
     "sk_plan_get_ranges", "sk_plan_grid", "sk_plan_get_stamps", "sk_release_cached_memory", "sk_strerror", "sk_last_error",
+    "sk_queue_params_default", "sk_queue_create", "sk_queue_submit", "sk_queue_poll", "sk_queue_get_stats", "sk_queue_destroy",
 ]
+SK_QUEUE_SEQUENTIAL, SK_QUEUE_COALESCE, SK_QUEUE_OOO = 0, 1, 2
+QUEUE_POLICY = {"sequential": SK_QUEUE_SEQUENTIAL, "coalesce": SK_QUEUE_COALESCE, "ooo": SK_QUEUE_OOO}
 
 
 class SkError(RuntimeError):
@@ -49,6 +52,21 @@ class PlanParams(C.Structure):
         ("balance_div", C.c_int32), ("max_groups", C.c_int32), ("grid_limit", C.c_int32),
         ("tail_div", C.c_int32),
     ]
+
+
+class QueueParams(C.Structure):
+    _fields_ = [("policy", C.c_int32), ("depth", C.c_int32), ("cap_ms", C.c_double), ("bytes_per_ms", C.c_double),
+                ("launch_floor_ms", C.c_double)]
+
+
+class sk_completion(C.Structure):
+    _fields_ = [("ticket", C.c_uint64), ("latency_ms", C.c_double), ("budget_ms", C.c_double), ("met", C.c_int32),
+                ("launch", C.c_int32)]
+
+
+class QueueStats(C.Structure):
+    _fields_ = [("submitted", C.c_int64), ("completed", C.c_int64), ("launches", C.c_int64), ("met", C.c_int64),
+                ("device_busy_ms", C.c_double), ("span_ms", C.c_double)]
 
 
 def lib_path() -> str:
@@ -95,6 +113,18 @@ def lib():
     L.sk_plan_get_stamps.argtypes = [vp, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_double)]
     L.sk_release_cached_memory.restype = C.c_int
     L.sk_release_cached_memory.argtypes = []
+    L.sk_queue_params_default.restype = None
+    L.sk_queue_params_default.argtypes = [C.POINTER(QueueParams)]
+    L.sk_queue_create.restype = C.c_int
+    L.sk_queue_create.argtypes = [C.POINTER(QueueParams), vp, C.POINTER(vp)]
+    L.sk_queue_submit.restype = C.c_int
+    L.sk_queue_submit.argtypes = [vp, vp, vp, C.c_int32, vp]
+    L.sk_queue_poll.restype = C.c_int
+    L.sk_queue_poll.argtypes = [vp, C.c_int32, vp, C.c_int32, C.POINTER(C.c_int32)]
+    L.sk_queue_get_stats.restype = C.c_int
+    L.sk_queue_get_stats.argtypes = [vp, C.POINTER(QueueStats)]
+    L.sk_queue_destroy.restype = C.c_int
+    L.sk_queue_destroy.argtypes = [vp]
     L.sk_strerror.restype = C.c_char_p
     L.sk_strerror.argtypes = [C.c_int]
     L.sk_last_error.restype = C.c_char_p
@@ -246,3 +276,74 @@ def sk_plan_get_stamps(plan: Plan):
     rate = C.c_double()
     _check(lib().sk_plan_get_stamps(plan.handle, done, C.byref(start), C.byref(rate)))
     return list(done[:n]), int(start.value), float(rate.value)
+
+
+# ---- operators arriving over time ---------------------------------------------------------------------
+
+def sk_queue_params_default(**overrides) -> QueueParams:
+    p = QueueParams()
+    lib().sk_queue_params_default(C.byref(p))
+    for k, v in overrides.items():
+        if not hasattr(p, k):
+            raise AttributeError(k)
+        setattr(p, k, QUEUE_POLICY[v] if k == "policy" and isinstance(v, str) else v)
+    return p
+
+
+class Queue:
+    """Owner of an sk_queue handle."""
+
+    def __init__(self, handle: int, keepalive=None):
+        self.handle = handle
+        self.keepalive = keepalive
+        self._n = C.c_int32()
+
+    def close(self):
+        if self.handle:
+            h, self.handle = self.handle, None
+            _check(lib().sk_queue_destroy(h))
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+
+def sk_queue_create(params: QueueParams | None = None, stream: int = 0, keepalive=None) -> Queue:
+    out = C.c_void_p()
+    _check(lib().sk_queue_create(C.byref(params) if params is not None else None, stream, C.byref(out)))
+    return Queue(out.value, keepalive)
+
+
+def sk_queue_destroy(queue: Queue) -> None:
+    queue.close()
+
+
+def sk_queue_submit(queue: Queue, ops, budgets=None, first: int = 0, n: int | None = None, tickets=None) -> None:
+    """Submits ops[first : first + n] (a ctypes array of sk_problem) with budgets[first : first + n] (a ctypes
+    array of doubles, or None) and stores their tickets into tickets[first : first + n] (uint64 array or None)."""
+    if n is None:
+        n = len(ops) - first
+    po = C.addressof(ops) + first * C.sizeof(sk_problem)
+    pb = C.addressof(budgets) + first * 8 if budgets is not None else None
+    pt = C.addressof(tickets) + first * 8 if tickets is not None else None
+    _check(lib().sk_queue_submit(queue.handle, po, pb, n, pt))
+
+
+def sk_queue_poll(queue: Queue, out, wait: bool = False) -> int:
+    """Completions into `out` (a ctypes array of sk_completion); returns how many."""
+    _check(lib().sk_queue_poll(queue.handle, 1 if wait else 0, C.addressof(out), len(out), C.byref(queue._n)))
+    return queue._n.value
+
+
+def sk_queue_get_stats(queue: Queue) -> QueueStats:
+    st = QueueStats()
+    _check(lib().sk_queue_get_stats(queue.handle, C.byref(st)))
+    return st

@@ -9,7 +9,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsuperkernel.so")
 CEILINGS_LIB = os.path.join(HERE, "libsk_ceilings.so")  # measuring aid of bench.py, not part of the ABI
-SOURCES = ["superkernel.hip", "planner.cpp"]
+SOURCES = ["superkernel.hip", "planner.cpp", "queue.cpp"]
 HEADERS = ["kernels.hip.h", "sk_internal.h", os.path.join(ROOT, "include", "superkernel.h")]
 
 HIPCC_FLAGS = [
@@ -36,10 +36,14 @@ def build(force: bool = True, verbose: bool = False, extra=()) -> str:
     os.makedirs(obj_dir, exist_ok=True)
     o_hip = os.path.join(obj_dir, "superkernel.o")
     o_cpp = os.path.join(obj_dir, "planner.o")
+    o_queue = os.path.join(obj_dir, "queue.o")
     steps = [
         [hipcc, *HIPCC_FLAGS, *extra, *inc, "-c", srcs[0], "-o", o_hip],
         ["g++", "-O2", "-std=c++17", "-fPIC", "-Wall", *inc, "-c", srcs[1], "-o", o_cpp],
-        [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", o_hip, o_cpp, "-o", LIB],
+        # host code that calls the HIP runtime (events): the host compiler with the runtime's headers
+        ["g++", "-O2", "-std=c++17", "-fPIC", "-Wall", "-D__HIP_PLATFORM_AMD__", "-I", "/opt/rocm/include", *inc, "-c", srcs[2],
+         "-o", o_queue],
+        [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", o_hip, o_cpp, o_queue, "-o", LIB],
         [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          os.path.join(CSRC, "ceilings.hip"), "-o", CEILINGS_LIB],

@@ -14,6 +14,7 @@
 #include <cstring>
 #include <limits>
 #include <numeric>
+#include <unordered_set>
 
 #include "sk_internal.h"
 
@@ -380,6 +381,53 @@ void LaunchLedger::after_launch(uintptr_t stream, bool capturing, bool event_rec
 LaunchLedger::Wait LaunchLedger::before_destroy() const {
   if (device_wide) return DEVICE;
   return has_event ? EVENT : NOTHING;
+}
+
+int64_t operand_bytes(const sk_problem &p) {
+  const int64_t es = elem_size(p.dtype);
+  if (p.op == SK_GEMM) {
+    if (p.M < 1 || p.N < 1 || p.K < 1) return 0;
+    return es * ((int64_t)p.M * p.K + (int64_t)p.N * p.K + (int64_t)p.M * p.N);
+  }
+  if (p.op != SK_CONV2D_NHWC && p.op != SK_CONV2D_NCHW) return 0;
+  const int64_t st = p.stride > 0 ? p.stride : 1;
+  const int64_t span_h = (int64_t)p.H + 2 * (int64_t)p.pad_h - p.R, span_w = (int64_t)p.Wd + 2 * (int64_t)p.pad_w - p.S;
+  if (p.Nb < 1 || p.Cin < 1 || p.Cout < 1 || p.R < 1 || p.S < 1 || span_h < 0 || span_w < 0) return 0;
+  const int64_t Ho = span_h / st + 1, Wo = span_w / st + 1;
+  return es * ((int64_t)p.Nb * p.H * p.Wd * p.Cin + (int64_t)p.Cout * p.R * p.S * p.Cin + (int64_t)p.Nb * Ho * Wo * p.Cout);
+}
+
+double estimate_launch_ms(int64_t bytes, double bytes_per_ms, double floor_ms) {
+  const double t = (double)bytes / bytes_per_ms;
+  return t > floor_ms ? t : floor_ms;
+}
+
+std::vector<size_t> select_batch(const std::vector<QueuedOp> &ops, const std::vector<const void *> &busy, int policy,
+                                 double cap_ms, double corr, double bytes_per_ms, double floor_ms) {
+  std::vector<size_t> picked;
+  if (ops.empty()) return picked;
+  if (policy == SK_QUEUE_SEQUENTIAL) {
+    // arrival order; one stream keeps launches into one buffer ordered, so a busy output does not hold it back
+    picked.push_back(0);
+    return picked;
+  }
+  std::vector<size_t> order(ops.size());
+  std::iota(order.begin(), order.end(), (size_t)0);
+  std::stable_sort(order.begin(), order.end(),
+                   [&](size_t a, size_t b) { return ops[a].deadline_ms < ops[b].deadline_ms; });
+  std::unordered_set<const void *> taken;  // outputs of this batch
+  int64_t total = 0;
+  for (size_t i : order) {
+    const void *c = ops[i].C;
+    if (std::binary_search(busy.begin(), busy.end(), c) || taken.count(c)) continue;
+    if (policy == SK_QUEUE_OOO && !picked.empty() &&
+        estimate_launch_ms(total + ops[i].bytes, bytes_per_ms, floor_ms) * corr > cap_ms)
+      break;
+    picked.push_back(i);
+    taken.insert(c);
+    total += ops[i].bytes;
+  }
+  return picked;
 }
 
 }  // namespace sk

@@ -75,6 +75,32 @@ sk_status plan_host_each_alone(const HostPlan &whole, HostPlan &out, std::string
 
 inline int elem_size(int32_t dtype) { return dtype == SK_F32 ? 4 : 2; }
 
+// Sets the calling thread's sk_last_error() text and passes the status through (superkernel.hip).
+sk_status set_last_error(sk_status st, const std::string &msg);
+
+// ---- the arrival queue's decisions, free of HIP calls so that they can be exercised on the host ----
+
+// One submitted operator as the batch selection sees it.
+struct QueuedOp {
+  double deadline_ms;  // absolute: submit time + budget (+inf if none)
+  int64_t bytes;       // operand bytes, for the duration estimate
+  const void *C;       // its output buffer
+};
+
+// Operand bytes of an operator (activations + weights + output, each once), 0 for a malformed one.
+int64_t operand_bytes(const sk_problem &p);
+
+// Estimated duration of a launch over `bytes` of operands.
+double estimate_launch_ms(int64_t bytes, double bytes_per_ms, double floor_ms);
+
+// Which of `ops` (any order) go into the next launch, as indices in the order they are to be planned:
+// earliest deadline first, ties by index; an operator whose output buffer is in `busy` (sorted) or was
+// taken by an earlier pick waits; SK_QUEUE_OOO closes the batch before the operator that would take
+// the estimate (times `corr`) past cap_ms, unless the batch is still empty; SK_QUEUE_SEQUENTIAL takes
+// the first submitted operator only (index 0), whatever its deadline.
+std::vector<size_t> select_batch(const std::vector<QueuedOp> &ops, const std::vector<const void *> &busy, int policy,
+                                 double cap_ms, double corr, double bytes_per_ms, double floor_ms);
+
 // Bookkeeping of one plan's launches, free of HIP calls so that it can be exercised on the host.
 // A plan has one tile queue, one set of split-reduction counters and one workspace: a launch may only
 // start when the one before it has finished or precedes it on the same stream.  The ledger says when

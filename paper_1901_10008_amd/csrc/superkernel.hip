@@ -23,6 +23,12 @@ sk_status set_error(sk_status st, const std::string &msg) {
   return st;
 }
 
+}  // namespace
+
+sk_status sk::set_last_error(sk_status st, const std::string &msg) { return set_error(st, msg); }
+
+namespace {
+
 sk_status hip_error(const char *what, hipError_t e) {
   return set_error(SK_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
 }

@@ -5,7 +5,9 @@
 // record stays inside its operator.  Byte-exact comparison with the reference planner is the
 // Python tests' job.
 #include <cstdint>
+#include <algorithm>
 #include <cstdio>
+#include <limits>
 #include <random>
 #include <string>
 #include <vector>
@@ -154,6 +156,50 @@ int main() {
     d.after_launch(0, false, true);
     if (d.before_launch(0, false) != L::GO || d.before_launch(s1, false) != L::QUERY_EVENT)
       return fail("default stream as the plan's stream", -2);
+  }
+  // the arrival queue's batch selection
+  {
+    const double inf = std::numeric_limits<double>::infinity();
+    char buf[8];
+    const void *c0 = buf, *c1 = buf + 1, *c2 = buf + 2, *c3 = buf + 3;
+    // arrival order: deadlines 5, 1, inf, 1 (tie with index 1), 0.5 on the buffer of index 0
+    std::vector<sk::QueuedOp> ops = {{5.0, 1000, c0}, {1.0, 1000, c1}, {inf, 1000, c2}, {1.0, 4000, c3}, {0.5, 1000, c0}};
+    std::vector<const void *> none, busy = {c1};
+    std::sort(busy.begin(), busy.end());
+    auto same = [](const std::vector<size_t> &a, std::initializer_list<size_t> b) { return a == std::vector<size_t>(b); };
+    // everything that is free, earliest deadline first, ties by arrival; the later operator of a shared buffer waits
+    if (!same(sk::select_batch(ops, none, SK_QUEUE_COALESCE, 0.5, 1.0, 1000.0, 0.0), {4, 1, 3, 2}))
+      return fail("coalesce order", -3);
+    if (!same(sk::select_batch(ops, busy, SK_QUEUE_COALESCE, 0.5, 1.0, 1000.0, 0.0), {4, 3, 2}))
+      return fail("an operator whose output is in flight must wait", -3);
+    // 1000 bytes per ms: the cap of 2.5 ms closes the batch before the 4000-byte operator; the operators behind
+    // it in deadline order wait as well
+    if (!same(sk::select_batch(ops, none, SK_QUEUE_OOO, 2.5, 1.0, 1000.0, 0.0), {4, 1})) return fail("cap", -3);
+    // ... a correction factor of 2 already before the second operator
+    if (!same(sk::select_batch(ops, none, SK_QUEUE_OOO, 2.5, 2.0, 1000.0, 0.0), {4})) return fail("corrected cap", -3);
+    // a first operator is always taken, however long
+    if (!same(sk::select_batch(ops, none, SK_QUEUE_OOO, 0.001, 1.0, 1000.0, 0.0), {4})) return fail("first operator", -3);
+    // the floor counts: three operators of 1 ms each are estimated at the floor of 10 ms
+    if (!same(sk::select_batch(ops, none, SK_QUEUE_OOO, 10.0, 1.0, 1000.0, 10.0), {4, 1, 3, 2})) return fail("floor", -3);
+    if (!same(sk::select_batch(ops, busy, SK_QUEUE_SEQUENTIAL, 0.5, 1.0, 1000.0, 0.0), {0})) return fail("arrival order", -3);
+    if (!sk::select_batch({}, none, SK_QUEUE_OOO, 0.5, 1.0, 1000.0, 0.0).empty()) return fail("empty queue", -3);
+    if (sk::estimate_launch_ms(5000, 1000.0, 0.02) != 5.0 || sk::estimate_launch_ms(10, 1000.0, 0.02) != 0.02)
+      return fail("estimate", -3);
+    sk_problem g{};
+    g.op = SK_GEMM;
+    g.dtype = SK_BF16;
+    g.M = 3;
+    g.N = 5;
+    g.K = 7;
+    if (sk::operand_bytes(g) != 2 * (3 * 7 + 5 * 7 + 3 * 5)) return fail("GEMM bytes", -3);
+    sk_problem cv{};
+    cv.op = SK_CONV2D_NHWC;
+    cv.dtype = SK_F32;
+    cv.Nb = 2; cv.H = 9; cv.Wd = 8; cv.Cin = 3; cv.Cout = 4; cv.R = 3; cv.S = 3; cv.pad_h = 1; cv.pad_w = 1; cv.stride = 2;
+    // Ho = (9 + 2 - 3) / 2 + 1 = 5, Wo = (8 + 2 - 3) / 2 + 1 = 4
+    if (sk::operand_bytes(cv) != 4 * (2 * 9 * 8 * 3 + 4 * 3 * 3 * 3 + 2 * 5 * 4 * 4)) return fail("convolution bytes", -3);
+    cv.R = 20;
+    if (sk::operand_bytes(cv) != 0) return fail("malformed operator", -3);
   }
   std::puts("planner_driver: ok");
   return 0;

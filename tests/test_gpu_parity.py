@@ -242,14 +242,54 @@ def test_arrival_trace_policies():
     b = H.Batch(specs, seed=0)
     trace = serve.poisson_trace([workloads.algorithmic_bytes(s) for s in specs], 60, rate_per_ms=40.0, seed=1)
     assert len(trace) == 60 and all(x.t_ms < y.t_ms for x, y in zip(trace, trace[1:]))
-    for policy, pipeline in (("sequential", True), ("coalesce", True), ("ooo", True), ("coalesce", False)):
+    for policy, depth, cap in (("sequential", 0, 0.5), ("coalesce", 0, 0.5), ("ooo", 0, 0.5), ("coalesce", 1, 0.5),
+                               ("ooo", 3, 0.03)):
         b.reset_outputs()
-        rep = serve.run_trace(b.problems, trace, policy, pipeline=pipeline)
+        rep = serve.run_trace(b.problems, trace, policy, cap_ms=cap, depth=depth)
         _sync()
         assert rep["operators"] == 60 and 0.0 <= rep["met_fraction"] <= 1.0
         assert rep["launches"] == 60 if policy == "sequential" else rep["launches"] <= 60
         served = {a.index for a in trace}
         H.check_against_oracle(b, "trace " + policy, only=served)
+
+
+def test_arrival_queue_calls():
+    """The queue through its C calls: tickets, completions in full, operators that share an output buffer go
+    into different launches, a batch the planner rejects completes as failed, an empty queue polls empty."""
+    import ctypes as C
+    specs = workloads.config(2, seed=3)[:6]
+    b = H.Batch(specs, seed=3)
+    n = len(specs)
+    ops = (sk.sk_problem * (2 * n))(*b.problems, *b.problems)     # every operator twice: same output buffers
+    budgets = (C.c_double * (2 * n))(*([1.0] * n + [0.0] * n))      # the second half without a budget
+    tickets = (C.c_uint64 * (2 * n))()
+    done = (sk.sk_completion * 64)()
+    side = torch.cuda.Stream()
+    with sk.sk_queue_create(sk.sk_queue_params_default(policy="coalesce"), side.cuda_stream) as q:
+        assert sk.sk_queue_poll(q, done, wait=True) == 0             # nothing submitted: returns at once
+        sk.sk_queue_submit(q, ops, budgets, 0, 2 * n, tickets)
+        assert list(tickets) == list(range(1, 2 * n + 1))
+        seen = {}
+        while len(seen) < 2 * n:
+            for i in range(sk.sk_queue_poll(q, done, wait=True)):
+                seen[done[i].ticket] = (done[i].launch, done[i].met, done[i].latency_ms, done[i].budget_ms)
+        st = sk.sk_queue_get_stats(q)
+        assert (st.submitted, st.completed, st.launches) == (2 * n, 2 * n, 2) and st.device_busy_ms > 0
+        for i in range(n):
+            first, second = seen[tickets[i]], seen[tickets[n + i]]
+            assert first[0] != second[0], "two operators with one output buffer shared a launch"
+            assert first[1] in (0, 1) and second[1] == 1 and second[3] == math.inf and 0 < first[2] < 1000
+        side.synchronize()
+        H.check_against_oracle(b, "queue")
+        # a batch the planner rejects (a dimension of zero): its operator completes as failed, the call says why
+        bad = (sk.sk_problem * 1)(b.problems[0])
+        bad[0].M = 0
+        with pytest.raises(sk.SkError) as e:
+            sk.sk_queue_submit(q, bad, None, 0, 1, None)
+        assert e.value.status == sk.SK_ERR_INVALID_ARG
+        assert sk.sk_queue_poll(q, done, wait=True) == 1 and done[0].met == -1
+    with pytest.raises(sk.SkError):
+        sk.sk_queue_create(sk.sk_queue_params_default(cap_ms=0.0))
 
 
 def test_recycled_plan_tables():
