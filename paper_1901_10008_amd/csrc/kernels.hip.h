@@ -758,6 +758,147 @@ __device__ __forceinline__ void run_skinny(const DevProblem &P, const sk_tile &T
   if (finish) store_pass();
 }
 
+// What follows the main loop of an LDS tile: the hand-over of a split reduction and the stores.
+// lane holds, per (fn, fm): row l32 of the 32x32 block, columns 8*(i/4) + 4*half + (i%4).
+template <int DT, int BM, int BN, int WAVES_M, int WAVES_N>
+__device__ __forceinline__ void finish_tile(const DevProblem &P, const sk_tile &T, const SplitK &sp, unsigned char *lds,
+                                            uint32_t *s_flag, int tid,
+                                            f32x16 (&acc)[BN / (32 * WAVES_N)][BM / (32 * WAVES_M)]) {
+  constexpr int ES = Elem<DT>::ES;
+  constexpr int CE = 16 / ES;
+  constexpr int FM = BM / (32 * WAVES_M);
+  constexpr int FN = BN / (32 * WAVES_N);
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lane = tid & 63;
+  const int wm = wave % WAVES_M, wn = wave / WAVES_M;
+  const int l32 = lane & 31, half = lane >> 5;
+  const int m0 = (int)T.m0, n0 = (int)T.n0;
+  const int m_end = m0 + (int)T.m_len, n_end = n0 + (int)T.n_len;
+  if (T.S > 1) {
+    // A slice of a split reduction: same hand-over as in the skinny classes.  Partial sums go to
+    // the workspace in register layout with device-scope stores (a slice is FN*FM*4 blocks of
+    // 64 x 16 bytes per wave); the last slice to arrive adds all of them in slice order.
+    constexpr int PER_WAVE = FN * FM * 4;          // 1 KB blocks per wave and slice
+    constexpr int PER_SLICE = 4 * PER_WAVE * 64;   // f32x4 units per slice
+    f32x4 *mine = sp.ws + sp.ws_off[T.out_tile_id] + wave * PER_WAVE * 64;
+#pragma unroll
+    for (int fn = 0; fn < FN; ++fn)
+#pragma unroll
+      for (int fm = 0; fm < FM; ++fm)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const f32x4 v = {acc[fn][fm][4 * j], acc[fn][fm][4 * j + 1], acc[fn][fm][4 * j + 2], acc[fn][fm][4 * j + 3]};
+          store_device_scope(mine + (size_t)T.ks_idx * PER_SLICE + ((fn * FM + fm) * 4 + j) * 64, lane, v);
+        }
+    __builtin_amdgcn_s_waitcnt(0);  // all counters to zero: the stores above have completed
+    __syncthreads();
+    if (tid == 0)
+      *s_flag = __hip_atomic_fetch_add(&sp.arrive[T.out_tile_id], 1u, SK_ARRIVE_ORDER, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (*s_flag != (uint32_t)T.S - 1) return;
+#pragma unroll
+    for (int fn = 0; fn < FN; ++fn)
+#pragma unroll
+      for (int fm = 0; fm < FM; ++fm)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[fn][fm][i] = 0.f;
+    for (int s2 = 0; s2 < T.S; ++s2) {
+#pragma unroll
+      for (int fn = 0; fn < FN; ++fn)
+#pragma unroll
+        for (int fm = 0; fm < FM; ++fm)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const f32x4 v = load_device_scope(mine + (size_t)s2 * PER_SLICE + ((fn * FM + fm) * 4 + j) * 64, lane);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[fn][fm][4 * j + e] += v[e];
+          }
+    }
+    if (tid == 0)  // re-arm for the next launch
+      __hip_atomic_store(&sp.arrive[T.out_tile_id], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+
+  // lane holds, per (fn, fm): row m = l32, columns 8*(i/4) + 4*half + (i%4)
+  //
+  // Written from the accumulators a store instruction would cover 32 rows with 16 bytes each.
+  // Where C allows 16-byte stores the tile goes through LDS instead (free by now: every wave has
+  // passed the last stage's barrier) and leaves as whole rows: 16 lanes x 16 bytes side by side.
+  constexpr int OROW = BN * ES + 16;  // padded row of the output tile in LDS
+  static_assert(BM * OROW <= LDS_TILE_BYTES, "output tile does not fit the LDS buffer");
+  const bool wide = ((uintptr_t)P.C % 16 == 0) && ((P.ldc * ES) % 16 == 0);
+  if (wide) {
+#pragma unroll
+    for (int fm = 0; fm < FM; ++fm) {
+      const int r = (wm * FM + fm) * 32 + l32;
+#pragma unroll
+      for (int fn = 0; fn < FN; ++fn) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int c = (wn * FN + fn) * 32 + 8 * j + 4 * half;
+          unsigned char *q = lds + r * OROW + c * ES;
+          if constexpr (ES == 4) {
+            *(f32x4 *)q = f32x4{acc[fn][fm][4 * j], acc[fn][fm][4 * j + 1], acc[fn][fm][4 * j + 2], acc[fn][fm][4 * j + 3]};
+          } else {
+            u32x2 o;
+            o.x = cvt_pack<DT>(acc[fn][fm][4 * j], acc[fn][fm][4 * j + 1]);
+            o.y = cvt_pack<DT>(acc[fn][fm][4 * j + 2], acc[fn][fm][4 * j + 3]);
+            *(u32x2 *)q = o;
+          }
+        }
+      }
+    }
+    __syncthreads();
+    constexpr int PIECES = BN * ES / 16;             // 16-byte pieces per output row
+    constexpr int RPI = WG_THREADS / PIECES;         // rows per store instruction
+    const int pc = tid % PIECES, pr = tid / PIECES;
+    const int n = n0 + pc * CE;
+#pragma unroll
+    for (int i = 0; i < BM / RPI; ++i) {
+      const int r = pr + i * RPI;
+      const int m = m0 + r;
+      if (m < m_end && n < n_end) {
+        const u32x4 v = *(const u32x4 *)(lds + r * OROW + pc * 16);
+        char SK_GLOBAL *dst = as_global_mut<char>(P.C) + ((int64_t)m * P.ldc + n) * ES;
+        if (n + CE <= n_end) {
+          *(u32x4 SK_GLOBAL *)dst = v;
+        } else {
+          // ragged right edge: element by element
+#pragma unroll
+          for (int e = 0; e < CE; ++e) {
+            if (n + e < n_end) {
+              if constexpr (ES == 4)
+                ((uint32_t SK_GLOBAL *)dst)[e] = v[e];
+              else
+                ((uint16_t SK_GLOBAL *)dst)[e] = (uint16_t)(v[e / 2] >> (16 * (e & 1)));
+            }
+          }
+        }
+      }
+    }
+    // (the barrier at the end of every tile keeps the next tile's LDS writes behind these reads)
+    return;
+  }
+  const bool vec_c = (P.flags & FLAG_VEC_C) != 0;
+#pragma unroll
+  for (int fm = 0; fm < FM; ++fm) {
+    const int m = m0 + (wm * FM + fm) * 32 + l32;
+    if (m < m_end) {
+      const int64_t row_off = (int64_t)m * P.ldc;
+#pragma unroll
+      for (int fn = 0; fn < FN; ++fn) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int n = n0 + (wn * FN + fn) * 32 + 8 * j + 4 * half;
+          if (n < n_end) {
+            f32x4 v = {acc[fn][fm][4 * j], acc[fn][fm][4 * j + 1], acc[fn][fm][4 * j + 2], acc[fn][fm][4 * j + 3]};
+            store4<DT>(P.C, row_off, n, n_end, v, vec_c);
+          }
+        }
+      }
+    }
+  }
+}
+
 // ---------------------------------------------------------------------------
 // LDS-staged tiles: BM x BN outputs per workgroup, 128 bytes of K per stage
 // ---------------------------------------------------------------------------
@@ -925,129 +1066,243 @@ __device__ __forceinline__ void run_tile(const DevProblem &P, const sk_tile &T, 
     }
   }
 
-  if (T.S > 1) {
-    // A slice of a split reduction: same hand-over as in the skinny classes.  Partial sums go to
-    // the workspace in register layout with device-scope stores (a slice is FN*FM*4 blocks of
-    // 64 x 16 bytes per wave); the last slice to arrive adds all of them in slice order.
-    constexpr int PER_WAVE = FN * FM * 4;          // 1 KB blocks per wave and slice
-    constexpr int PER_SLICE = 4 * PER_WAVE * 64;   // f32x4 units per slice
-    f32x4 *mine = sp.ws + sp.ws_off[T.out_tile_id] + wave * PER_WAVE * 64;
+  finish_tile<DT, BM, BN, WAVES_M, WAVES_N>(P, T, sp, lds, s_flag, tid, acc);
+}
+
+// ---------------------------------------------------------------------------
+// LDS tiles with lean operand addressing
+// ---------------------------------------------------------------------------
+// The stage of run_tile above spends more instructions on forming addresses than on anything
+// else: per 16-byte piece a 64-bit add, two selects against the piece of zeros and, for a
+// convolution, the bounds of the tap in both directions.  With two waves per SIMD those
+// instructions, not the memory system, set the pace of a stage.  This variant keeps the same
+// pipeline (ring of register stages, two LDS stages, the same LDS image, fragments and MFMAs)
+// and reads its operands through buffer descriptors instead:
+//   * one descriptor per operand and tile, based at the tile's first row, its size the extent of
+//     the tile's rows: a piece's address is a 32-bit row offset kept in a register for the whole
+//     tile plus a scalar offset that advances with the stage, and a piece that lies outside the
+//     descriptor reads as zero, so a piece that must not be read gets the offset 2^31;
+//   * for a convolution whose channel count is a multiple of a stage (64 elements of 2 bytes),
+//     all pieces of a stage lie under one filter tap: the tap and its offset are scalar, and
+//     whether a row's pixel under that tap lies in the image is one bit of a mask that is
+//     worked out once per tile and row.
+// It serves operators whose tile extents fit 31 bits of byte offset and, for convolutions,
+// those with such channel counts and at most 32 filter taps; the others keep run_tile.
+struct LeanOperands {
+  uintptr_t baseA, baseB;  // first byte the descriptors cover
+  uint32_t extA, extB;     // bytes they cover
+  int64_t originA;         // element offset of baseA from P.A
+};
+
+// Whether the tile can take the lean path, and its descriptors.  All scalar (P and T are uniform).
+template <int ES>
+__device__ __forceinline__ bool lean_operands(const DevProblem &P, const sk_tile &T, LeanOperands &L) {
+  constexpr int CE = 16 / ES;
+  constexpr int KB = 8 * CE;
+  constexpr int64_t LIMIT = (int64_t)1 << 31;
+  const int64_t extB = ((int64_t)((int)T.n_len - 1) * P.ldb + P.Kg) * ES;
+  L.baseB = (uintptr_t)P.B + (uintptr_t)((int64_t)T.n0 * P.ldb * ES);
+  L.extB = (uint32_t)extB;
+  int64_t extA;
+  if (!P.gather) {
+    extA = ((int64_t)((int)T.m_len - 1) * P.lda + P.Kg) * ES;
+    L.originA = (int64_t)T.m0 * P.lda;
+  } else {
+    if (P.nchw || P.Cin % KB != 0 || P.R * P.S > 32) return false;
+    // from the corner of the padded first image of the tile to the end of the array
+    const int hw = P.Ho * P.Wo;
+    const int b0 = (int)T.m0 / hw;
+    const int nb = (P.Mg + hw - 1) / hw;
+    L.originA = (((int64_t)b0 * P.H - P.pad_h) * P.W - P.pad_w) * P.Cin;
+    const int b1 = ((int)T.m0 + (int)T.m_len - 1) / hw;
+    // (the last image the tile touches must lie inside 2^31 bytes; the descriptor itself ends with the array)
+    if ((((int64_t)(b1 + 1) * P.H * P.W) * P.Cin - L.originA) * ES >= LIMIT) return false;
+    extA = (((int64_t)nb * P.H * P.W) * P.Cin - L.originA) * ES;
+    if (extA >= LIMIT) extA = LIMIT - 1;
+  }
+  L.baseA = (uintptr_t)P.A + (uintptr_t)(L.originA * ES);
+  L.extA = (uint32_t)extA;
+  return extA < LIMIT && extB < LIMIT;
+}
+
+template <int DT, int BM, int BN, int WAVES_M, int WAVES_N, bool GATHER>
+__device__ __forceinline__ void run_tile_lean(const DevProblem &P, const sk_tile &T, const SplitK &sp, unsigned char *lds,
+                                              uint32_t *s_flag, Prefetch &pf, const LeanOperands &L) {
+  constexpr int ES = Elem<DT>::ES;
+  constexpr int CE = 16 / ES;
+  constexpr int KB = 8 * CE;                  // reduction elements per stage
+  constexpr int FM = BM / (32 * WAVES_M);     // 32x32 blocks per wave along m
+  constexpr int FN = BN / (32 * WAVES_N);     // ... along n
+  constexpr int A_ITERS = BM / 32;            // 16-byte pieces per thread per stage, activations
+  constexpr int B_ITERS = BN / 32;            // ... weights
+  constexpr int STAGE = (BM + BN) * LDS_ROW;  // bytes of one stage in LDS
+  constexpr int NS = 3;
+  constexpr uint32_t NOWHERE = 0x80000000u;   // an offset outside every descriptor: the piece reads as zero
+  static_assert(WAVES_M * WAVES_N == 4, "four waves per workgroup");
+  static_assert(2 * STAGE <= LDS_TILE_BYTES, "two stages do not fit the LDS buffer");
+
+  const int tid = pf.tid;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lane = tid & 63;
+  const int wm = wave % WAVES_M, wn = wave / WAVES_M;
+  const int l32 = lane & 31, half = lane >> 5;
+
+  const int m0 = (int)T.m0, n0 = (int)T.n0;
+  const int m_end = m0 + (int)T.m_len, n_end = n0 + (int)T.n_len;
+  const int k_begin = (int)T.k0, k_stop = (int)T.k0 + (int)T.k_len;
+
+  const __amdgpu_buffer_rsrc_t descA = __builtin_amdgcn_make_buffer_rsrc((void *)L.baseA, 0, (int)L.extA, 0x00020000);
+  const __amdgpu_buffer_rsrc_t descB = __builtin_amdgcn_make_buffer_rsrc((void *)L.baseB, 0, (int)L.extB, 0x00020000);
+
+  // staging map: thread -> piece c8 of rows (tid/8) + 32*i
+  const int c8 = tid & 7;
+  const int srow = tid >> 3;
+  uint32_t offA[A_ITERS];   // byte offset of this thread's piece of row i at reduction index 0 (tap (0,0), channel 0)
+  uint32_t tapsA[A_ITERS];  // convolution: bit (r*S + s) set if the row's pixel under tap (r, s) lies in the image
 #pragma unroll
-    for (int fn = 0; fn < FN; ++fn)
-#pragma unroll
-      for (int fm = 0; fm < FM; ++fm)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const f32x4 v = {acc[fn][fm][4 * j], acc[fn][fm][4 * j + 1], acc[fn][fm][4 * j + 2], acc[fn][fm][4 * j + 3]};
-          store_device_scope(mine + (size_t)T.ks_idx * PER_SLICE + ((fn * FM + fm) * 4 + j) * 64, lane, v);
-        }
-    __builtin_amdgcn_s_waitcnt(0);  // all counters to zero: the stores above have completed
-    __syncthreads();
-    if (tid == 0)
-      *s_flag = __hip_atomic_fetch_add(&sp.arrive[T.out_tile_id], 1u, SK_ARRIVE_ORDER, __HIP_MEMORY_SCOPE_AGENT);
-    __syncthreads();
-    if (*s_flag != (uint32_t)T.S - 1) return;
-#pragma unroll
-    for (int fn = 0; fn < FN; ++fn)
-#pragma unroll
-      for (int fm = 0; fm < FM; ++fm)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) acc[fn][fm][i] = 0.f;
-    for (int s2 = 0; s2 < T.S; ++s2) {
-#pragma unroll
-      for (int fn = 0; fn < FN; ++fn)
-#pragma unroll
-        for (int fm = 0; fm < FM; ++fm)
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const f32x4 v = load_device_scope(mine + (size_t)s2 * PER_SLICE + ((fn * FM + fm) * 4 + j) * 64, lane);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) acc[fn][fm][4 * j + e] += v[e];
-          }
+  for (int i = 0; i < A_ITERS; ++i) {
+    int m = m0 + srow + 32 * i;
+    if (m >= m_end) m = m_end - 1;  // rows past the edge repeat the last row; never stored
+    if constexpr (!GATHER) {
+      offA[i] = (uint32_t)((m - m0) * (int)P.lda * ES) + (uint32_t)c8 * 16u;
+      tapsA[i] = 0;
+    } else {
+      const RowA r = row_of(P, m);
+      offA[i] = (uint32_t)((r.base - L.originA) * ES) + (uint32_t)c8 * 16u;
+      uint32_t hm = 0, wmk = 0, taps = 0;
+      for (int rr = 0; rr < P.R; ++rr) hm |= ((unsigned)(r.hb + rr) < (unsigned)P.H ? 1u : 0u) << rr;
+      for (int ss = 0; ss < P.S; ++ss) wmk |= ((unsigned)(r.wb + ss) < (unsigned)P.W ? 1u : 0u) << ss;
+      for (int rr = 0; rr < P.R; ++rr) taps |= ((hm >> rr) & 1u) ? wmk << (rr * P.S) : 0u;
+      tapsA[i] = taps;
     }
-    if (tid == 0)  // re-arm for the next launch
-      __hip_atomic_store(&sp.arrive[T.out_tile_id], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  uint32_t offB[B_ITERS];
+#pragma unroll
+  for (int i = 0; i < B_ITERS; ++i) {
+    int n = n0 + srow + 32 * i;
+    if (n >= n_end) n = n_end - 1;
+    offB[i] = (uint32_t)((n - n0) * (int)P.ldb * ES) + (uint32_t)c8 * 16u;
   }
 
-  // lane holds, per (fn, fm): row m = l32, columns 8*(i/4) + 4*half + (i%4)
-  //
-  // Written from the accumulators a store instruction would cover 32 rows with 16 bytes each.
-  // Where C allows 16-byte stores the tile goes through LDS instead (free by now: every wave has
-  // passed the last stage's barrier) and leaves as whole rows: 16 lanes x 16 bytes side by side.
-  constexpr int OROW = BN * ES + 16;  // padded row of the output tile in LDS
-  static_assert(BM * OROW <= LDS_TILE_BYTES, "output tile does not fit the LDS buffer");
-  const bool wide = ((uintptr_t)P.C % 16 == 0) && ((P.ldc * ES) % 16 == 0);
-  if (wide) {
+  f32x16 acc[FN][FM];
 #pragma unroll
-    for (int fm = 0; fm < FM; ++fm) {
-      const int r = (wm * FM + fm) * 32 + l32;
+  for (int fn = 0; fn < FN; ++fn)
 #pragma unroll
-      for (int fn = 0; fn < FN; ++fn) {
+    for (int fm = 0; fm < FM; ++fm)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int c = (wn * FN + fn) * 32 + 8 * j + 4 * half;
-          unsigned char *q = lds + r * OROW + c * ES;
-          if constexpr (ES == 4) {
-            *(f32x4 *)q = f32x4{acc[fn][fm][4 * j], acc[fn][fm][4 * j + 1], acc[fn][fm][4 * j + 2], acc[fn][fm][4 * j + 3]};
-          } else {
-            u32x2 o;
-            o.x = cvt_pack<DT>(acc[fn][fm][4 * j], acc[fn][fm][4 * j + 1]);
-            o.y = cvt_pack<DT>(acc[fn][fm][4 * j + 2], acc[fn][fm][4 * j + 3]);
-            *(u32x2 *)q = o;
-          }
+      for (int i = 0; i < 16; ++i) acc[fn][fm][i] = 0.f;
+
+  // scalar position of the next stage to load: reduction index k_next; for a convolution the tap
+  // (t_r, t_s) and the first channel t_c of the stage
+  int k_next = k_begin;
+  int t_r = 0, t_s = 0, t_c = 0;
+  if constexpr (GATHER) {
+    const int tap = k_begin / P.Cin;
+    t_c = k_begin - tap * P.Cin;
+    t_r = tap / P.S;
+    t_s = tap - t_r * P.S;
+  }
+  u32x4 ra[NS][A_ITERS], rb[NS][B_ITERS];
+  // Loads are unconditional (stages past the end of the reduction read whatever lies there, or zeros
+  // past the descriptor, and are never multiplied), so the number of loads in flight is the same on
+  // every path.
+  auto gload = [&](u32x4(&xa)[A_ITERS], u32x4(&xb)[B_ITERS]) {
+    const uint32_t kbytes = (uint32_t)k_next * ES;
+    if constexpr (GATHER) {
+      // (no reduction tail: the reduction length is a multiple of the channel count, that of a stage)
+      const uint32_t tapbit = 1u << ((t_r * P.S + t_s) & 31);
+      const uint32_t tapoff = (uint32_t)(((t_r * P.W + t_s) * P.Cin + t_c) * ES);
+#pragma unroll
+      for (int i = 0; i < A_ITERS; ++i)
+        xa[i] = __builtin_amdgcn_raw_buffer_load_b128(descA, (tapsA[i] & tapbit) ? offA[i] : NOWHERE, tapoff, 0);
+#pragma unroll
+      for (int i = 0; i < B_ITERS; ++i) xb[i] = __builtin_amdgcn_raw_buffer_load_b128(descB, offB[i], kbytes, 0);
+      t_c += KB;
+      if (t_c >= P.Cin) {
+        t_c = 0;
+        if (++t_s == P.S) {
+          t_s = 0;
+          ++t_r;
         }
       }
+    } else {
+      // this thread's piece lies beyond the end of the reduction (last stage of a length that is not a
+      // multiple of a stage): nowhere
+      const uint32_t tail = k_next + c8 * CE < k_stop ? 0u : NOWHERE;
+#pragma unroll
+      for (int i = 0; i < A_ITERS; ++i) xa[i] = __builtin_amdgcn_raw_buffer_load_b128(descA, offA[i] | tail, kbytes, 0);
+#pragma unroll
+      for (int i = 0; i < B_ITERS; ++i) xb[i] = __builtin_amdgcn_raw_buffer_load_b128(descB, offB[i] | tail, kbytes, 0);
     }
-    __syncthreads();
-    constexpr int PIECES = BN * ES / 16;             // 16-byte pieces per output row
-    constexpr int RPI = WG_THREADS / PIECES;         // rows per store instruction
-    const int pc = tid % PIECES, pr = tid / PIECES;
-    const int n = n0 + pc * CE;
+    k_next += KB;
+  };
+  auto lstore = [&](int buf, const u32x4(&xa)[A_ITERS], const u32x4(&xb)[B_ITERS]) {
+    unsigned char *a = lds + buf * STAGE + srow * LDS_ROW + c8 * 16;
+    unsigned char *bb = a + BM * LDS_ROW;
 #pragma unroll
-    for (int i = 0; i < BM / RPI; ++i) {
-      const int r = pr + i * RPI;
-      const int m = m0 + r;
-      if (m < m_end && n < n_end) {
-        const u32x4 v = *(const u32x4 *)(lds + r * OROW + pc * 16);
-        char SK_GLOBAL *dst = as_global_mut<char>(P.C) + ((int64_t)m * P.ldc + n) * ES;
-        if (n + CE <= n_end) {
-          *(u32x4 SK_GLOBAL *)dst = v;
-        } else {
-          // ragged right edge: element by element
+    for (int i = 0; i < A_ITERS; ++i) *(u32x4 *)(a + 32 * i * LDS_ROW) = xa[i];
 #pragma unroll
-          for (int e = 0; e < CE; ++e) {
-            if (n + e < n_end) {
-              if constexpr (ES == 4)
-                ((uint32_t SK_GLOBAL *)dst)[e] = v[e];
-              else
-                ((uint16_t SK_GLOBAL *)dst)[e] = (uint16_t)(v[e / 2] >> (16 * (e & 1)));
-            }
-          }
+    for (int i = 0; i < B_ITERS; ++i) *(u32x4 *)(bb + 32 * i * LDS_ROW) = xb[i];
+  };
+
+  const int nstages = (k_stop - k_begin + KB - 1) / KB;
+#pragma unroll
+  for (int u = 0; u < NS - 1; ++u) gload(ra[u], rb[u]);
+  lstore(0, ra[0], rb[0]);
+  __syncthreads();
+  int buf = 0;
+  for (int s0 = 0; s0 < nstages; s0 += NS) {
+#pragma unroll
+    for (int u = 0; u < NS; ++u) {
+      pf.at_step(s0 + u, nstages, CLAIM_LEAD, ISSUE_GAP);
+      gload(ra[(u + NS - 1) % NS], rb[(u + NS - 1) % NS]);
+      if (s0 + u < nstages) {
+        // stage s0+u is in LDS buffer `buf`; put stage s0+u+1 into the other one while this one is used
+        const unsigned char *la = lds + buf * STAGE;
+        const unsigned char *lb = la + BM * LDS_ROW;
+        u32x4 fa[2][FM], fb[2][FN];
+        auto frag = [&](int kk, u32x4(&xa)[FM], u32x4(&xb)[FN]) {
+          const int piece = (2 * kk + half) * 16;
+#pragma unroll
+          for (int fm = 0; fm < FM; ++fm)
+            xa[fm] = *(const u32x4 *)(la + ((wm * FM + fm) * 32 + l32) * LDS_ROW + piece);
+#pragma unroll
+          for (int fn = 0; fn < FN; ++fn)
+            xb[fn] = *(const u32x4 *)(lb + ((wn * FN + fn) * 32 + l32) * LDS_ROW + piece);
+        };
+        frag(0, fa[0], fb[0]);
+        lstore(buf ^ 1, ra[(u + 1) % NS], rb[(u + 1) % NS]);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          if (kk + 1 < 4) frag(kk + 1, fa[(kk + 1) & 1], fb[(kk + 1) & 1]);
+#pragma unroll
+          for (int fn = 0; fn < FN; ++fn)
+#pragma unroll
+            for (int fm = 0; fm < FM; ++fm) mma32<DT>(fb[kk & 1][fn], fa[kk & 1][fm], acc[fn][fm]);
         }
+        __syncthreads();
+        buf ^= 1;
       }
     }
-    // (the barrier at the end of every tile keeps the next tile's LDS writes behind these reads)
+  }
+  finish_tile<DT, BM, BN, WAVES_M, WAVES_N>(P, T, sp, lds, s_flag, tid, acc);
+}
+
+// One LDS tile: the lean path where the operator allows it.
+template <int DT, int BM, int BN>
+__device__ __forceinline__ void run_lds_tile(const DevProblem &P, const sk_tile &T, const SplitK &sp, unsigned char *lds,
+                                             uint32_t *s_flag, Prefetch &pf) {
+#ifndef SK_NO_LEAN_TILES
+  LeanOperands L;
+  if (lean_operands<Elem<DT>::ES>(P, T, L)) {
+    if (P.gather)
+      run_tile_lean<DT, BM, BN, 2, 2, true>(P, T, sp, lds, s_flag, pf, L);
+    else
+      run_tile_lean<DT, BM, BN, 2, 2, false>(P, T, sp, lds, s_flag, pf, L);
     return;
   }
-  const bool vec_c = (P.flags & FLAG_VEC_C) != 0;
-#pragma unroll
-  for (int fm = 0; fm < FM; ++fm) {
-    const int m = m0 + (wm * FM + fm) * 32 + l32;
-    if (m < m_end) {
-      const int64_t row_off = (int64_t)m * P.ldc;
-#pragma unroll
-      for (int fn = 0; fn < FN; ++fn) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int n = n0 + (wn * FN + fn) * 32 + 8 * j + 4 * half;
-          if (n < n_end) {
-            f32x4 v = {acc[fn][fm][4 * j], acc[fn][fm][4 * j + 1], acc[fn][fm][4 * j + 2], acc[fn][fm][4 * j + 3]};
-            store4<DT>(P.C, row_off, n, n_end, v, vec_c);
-          }
-        }
-      }
-    }
-  }
+#endif
+  run_tile<DT, BM, BN, 2, 2>(P, T, sp, lds, s_flag, pf);
 }
 
 // ---------------------------------------------------------------------------
@@ -1384,9 +1639,9 @@ __device__ __forceinline__ void run_class(const DevProblem &P, const sk_tile &T,
   } else if (cls == 6) {
     run_skinny<DT, 4>(P, T, sp, lds, s_flag, pf);
   } else if (cls == CLS_TILE_128x64) {
-    run_tile<DT, 128, 64, 2, 2>(P, T, sp, lds, s_flag, pf);
+    run_lds_tile<DT, 128, 64>(P, T, sp, lds, s_flag, pf);
   } else {
-    run_tile<DT, 128, 128, 2, 2>(P, T, sp, lds, s_flag, pf);
+    run_lds_tile<DT, 128, 128>(P, T, sp, lds, s_flag, pf);
   }
 }
 
