@@ -319,6 +319,13 @@ def measured_ceilings(torch, achieved_gbs, achieved_tflops):
         if st != 0:
             return {"error": f"sk_ceiling_mfma_bf16 status {st}"}
         res["mfma_bf16_TFLOPs"] = round(v.value, 1)
+        lib.sk_ceiling_lds_read.argtypes = [C.c_int, C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+        g, bpc = C.c_double(), C.c_double()
+        st = lib.sk_ceiling_lds_read(20000, sink.data_ptr(), C.byref(g), C.byref(bpc))
+        if st != 0:
+            return {"error": f"sk_ceiling_lds_read status {st}"}
+        res["lds_fragment_read_GBs"] = round(g.value, 1)
+        res["lds_fragment_read_bytes_per_clk_per_cu"] = round(bpc.value, 1)
         best = max(res["stream_read_GBs_rows_of_16384B"], res["stream_read_GBs_rows_of_2048B"])
         res["achieved_over_stream_read"] = round(achieved_gbs / best, 4)
         res["achieved_over_mfma_loop"] = round(achieved_tflops / res["mfma_bf16_TFLOPs"], 4)

@@ -77,6 +77,27 @@ __global__ void __launch_bounds__(256, 2) mfma_loop(int iters, float seed, f32x4
   if (s == 12345.678f) sink[blockIdx.x] = f32x4{s, s, s, s};
 }
 
+// What the LDS delivers to the fragment reads of the LDS-tile class: every wave of two workgroups per CU
+// reads 16 bytes per lane from the padded 144-byte rows the tiles use (lane l: row l % 32, piece l / 32 + 2 kk),
+// `iters` rounds of eight reads, nothing else.
+__global__ void __launch_bounds__(256, 2) lds_read_loop(int iters, f32x4 *sink) {
+  __shared__ __attribute__((aligned(16))) unsigned char lds[256 * 144];
+  for (int i = threadIdx.x; i < 256 * 144 / 16; i += 256) ((f32x4 *)lds)[i] = f32x4{1.f, 2.f, 3.f, 4.f};
+  __syncthreads();
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const unsigned char *base = lds + ((wave * 64) + (lane & 31)) * 144 + (lane >> 5) * 16;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      acc += *(const f32x4 *)(base + kk * 32);
+      acc += *(const f32x4 *)(base + 32 * 144 + kk * 32);
+    }
+    asm volatile("" : "+v"(acc));
+  }
+  if (acc[0] == 12345.678f) sink[blockIdx.x] = acc;
+}
+
 int cu_count() {
   int dev = 0, cus = 0;
   if (hipGetDevice(&dev) != hipSuccess) return 0;
@@ -141,6 +162,37 @@ int sk_ceiling_mfma_bf16(int iters, void *sink, double *tflops) {
   if (e != hipSuccess) return (int)e;
   const double flops = (double)grid.x * 4.0 * iters * 4.0 * (2.0 * 32 * 32 * 16);
   *tflops = flops / (ms * 1e-3) / 1e12;
+  return 0;
+}
+
+// *bytes_per_clk_per_cu and *gb_per_s of `iters` rounds of eight 16-byte-per-lane LDS reads in every wave of 2 workgroups
+// per CU (the clock is the device's current shader clock as HIP reports it, in kHz).
+int sk_ceiling_lds_read(int iters, void *sink, double *gb_per_s, double *bytes_per_clk_per_cu) {
+  const int cus = cu_count();
+  if (!sink || !gb_per_s || !bytes_per_clk_per_cu || cus <= 0 || iters < 1) return (int)hipErrorInvalidValue;
+  int dev = 0, khz = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e == hipSuccess) e = hipDeviceGetAttribute(&khz, hipDeviceAttributeClockRate, dev);
+  if (e != hipSuccess) return (int)e;
+  hipEvent_t e0, e1;
+  e = hipEventCreate(&e0);
+  if (e != hipSuccess) return (int)e;
+  e = hipEventCreate(&e1);
+  if (e != hipSuccess) return (int)e;
+  const dim3 grid(2 * cus), block(256);
+  hipLaunchKernelGGL(lds_read_loop, grid, block, 0, 0, iters, (f32x4 *)sink);
+  (void)hipEventRecord(e0, 0);
+  hipLaunchKernelGGL(lds_read_loop, grid, block, 0, 0, iters, (f32x4 *)sink);
+  (void)hipEventRecord(e1, 0);
+  e = hipEventSynchronize(e1);
+  float ms = 0.f;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (e != hipSuccess) return (int)e;
+  const double bytes = (double)grid.x * 256.0 * iters * 8.0 * 16.0;
+  *gb_per_s = bytes / (ms * 1e-3) / 1e9;
+  *bytes_per_clk_per_cu = bytes / cus / (ms * 1e-3) / ((double)khz * 1e3);
   return 0;
 }
 

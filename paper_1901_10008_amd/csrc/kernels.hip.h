@@ -213,6 +213,11 @@ __device__ __forceinline__ u32x4 fetch_B(const DevProblem &P, int64_t row_off, i
     return *q;
 }
 
+// n / d with d given as multiplier and shift (FastDiv), 0 <= n < 2^31.
+__device__ __forceinline__ int fast_div(int n, const uint32_t (&d)[2]) {
+  return (int)(uint32_t)(((uint64_t)(uint32_t)n * d[0]) >> d[1]);
+}
+
 // Where row m of the activation operand starts.
 struct RowA {
   int64_t base;  // plain: m*lda.  gather: offset of pixel (b, hb, wb), channel 0, the one under filter tap (0,0); may be negative
@@ -227,9 +232,9 @@ __device__ __forceinline__ RowA row_of(const DevProblem &P, int m) {
     r.wb = 0;
   } else {
     const int hw = P.Ho * P.Wo;
-    const int b = m / hw;
+    const int b = fast_div(m, P.div_hw);
     const int rem = m - b * hw;
-    const int ho = rem / P.Wo;
+    const int ho = fast_div(rem, P.div_wo);
     const int wo = rem - ho * P.Wo;
     r.hb = ho * P.stride - P.pad_h;
     r.wb = wo * P.stride - P.pad_w;
@@ -252,7 +257,7 @@ __device__ __forceinline__ ImageStrides image_strides(const DevProblem &P) {
 }
 __device__ __forceinline__ int64_t nchw_out_base(const DevProblem &P, int m) {
   const int hw = P.Ho * P.Wo;
-  const int b = m / hw;
+  const int b = fast_div(m, P.div_hw);
   return (int64_t)b * P.Ng * hw + (m - b * hw);  // + n * Ho*Wo
 }
 template <int DT>
@@ -266,9 +271,9 @@ __device__ __forceinline__ void store_elem(void *C, int64_t off, float v) {
 
 // Element k of the implicit patch row: k = (r*S + s)*Cin + c  ->  pixel (hb+r, wb+s), channel c.
 __device__ __forceinline__ bool patch_offset(const DevProblem &P, const RowA &row, int k, int64_t &off) {
-  const int tap = k / P.Cin;
+  const int tap = fast_div(k, P.div_cin);
   const int c = k - tap * P.Cin;
-  const int r = tap / P.S;
+  const int r = fast_div(tap, P.div_s);
   const int s = tap - r * P.S;
   const int h = row.hb + r, w = row.wb + s;
   off = row.base + ((int64_t)r * P.W + s) * P.Cin + c;
@@ -519,9 +524,9 @@ __device__ __forceinline__ void run_skinny(const DevProblem &P, const sk_tile &T
   const int64_t next_filter_row = (int64_t)(P.W - P.S) * P.Cin;
   if (P.gather) {
     const int kk = k0 + s_piece * CE;
-    const int tap = kk / P.Cin;
+    const int tap = fast_div(kk, P.div_cin);
     g_c = kk - tap * P.Cin;
-    g_r = tap / P.S;
+    g_r = fast_div(tap, P.div_s);
     g_s = tap - g_r * P.S;
     g_off = ((int64_t)g_r * P.W + g_s) * P.Cin + g_c;
   }
@@ -974,9 +979,9 @@ __device__ __forceinline__ void run_tile(const DevProblem &P, const sk_tile &T, 
   const int64_t next_filter_row = (int64_t)(P.W - P.S) * P.Cin;
   if (gvec) {
     const int k = k_begin + c8 * CE;
-    const int tap = k / P.Cin;
+    const int tap = fast_div(k, P.div_cin);
     g_c = k - tap * P.Cin;
-    g_r = tap / P.S;
+    g_r = fast_div(tap, P.div_s);
     g_s = tap - g_r * P.S;
     tap_off = ((int64_t)g_r * P.W + g_s) * P.Cin + g_c;
   }
@@ -1087,7 +1092,7 @@ __device__ __forceinline__ void run_tile(const DevProblem &P, const sk_tile &T, 
 //     whether a row's pixel under that tap lies in the image is one bit of a mask that is
 //     worked out once per tile and row.
 // It serves operators whose tile extents fit 31 bits of byte offset and, for convolutions,
-// those with such channel counts and at most 32 filter taps; the others keep run_tile.
+// those with such channel counts and at most 31 filter taps; the others keep run_tile.
 struct LeanOperands {
   uintptr_t baseA, baseB;  // first byte the descriptors cover
   uint32_t extA, extB;     // bytes they cover
@@ -1108,13 +1113,13 @@ __device__ __forceinline__ bool lean_operands(const DevProblem &P, const sk_tile
     extA = ((int64_t)((int)T.m_len - 1) * P.lda + P.Kg) * ES;
     L.originA = (int64_t)T.m0 * P.lda;
   } else {
-    if (P.nchw || P.Cin % KB != 0 || P.R * P.S > 32) return false;
+    if (P.nchw || P.Cin % KB != 0 || P.R * P.S > 31) return false;
     // from the corner of the padded first image of the tile to the end of the array
     const int hw = P.Ho * P.Wo;
-    const int b0 = (int)T.m0 / hw;
-    const int nb = (P.Mg + hw - 1) / hw;
+    const int b0 = fast_div((int)T.m0, P.div_hw);
+    const int nb = fast_div(P.Mg + hw - 1, P.div_hw);
     L.originA = (((int64_t)b0 * P.H - P.pad_h) * P.W - P.pad_w) * P.Cin;
-    const int b1 = ((int)T.m0 + (int)T.m_len - 1) / hw;
+    const int b1 = fast_div((int)T.m0 + (int)T.m_len - 1, P.div_hw);
     // (the last image the tile touches must lie inside 2^31 bytes; the descriptor itself ends with the array)
     if ((((int64_t)(b1 + 1) * P.H * P.W) * P.Cin - L.originA) * ES >= LIMIT) return false;
     extA = (((int64_t)nb * P.H * P.W) * P.Cin - L.originA) * ES;
@@ -1169,10 +1174,12 @@ __device__ __forceinline__ void run_tile_lean(const DevProblem &P, const sk_tile
     } else {
       const RowA r = row_of(P, m);
       offA[i] = (uint32_t)((r.base - L.originA) * ES) + (uint32_t)c8 * 16u;
-      uint32_t hm = 0, wmk = 0, taps = 0;
-      for (int rr = 0; rr < P.R; ++rr) hm |= ((unsigned)(r.hb + rr) < (unsigned)P.H ? 1u : 0u) << rr;
-      for (int ss = 0; ss < P.S; ++ss) wmk |= ((unsigned)(r.wb + ss) < (unsigned)P.W ? 1u : 0u) << ss;
-      for (int rr = 0; rr < P.R; ++rr) taps |= ((hm >> rr) & 1u) ? wmk << (rr * P.S) : 0u;
+      // filter rows rr with 0 <= hb + rr < H form a range [lo, hi), and so do the filter columns
+      const int hlo = max(0, -r.hb), hhi = min(P.R, P.H - r.hb);
+      const int wlo = max(0, -r.wb), whi = min(P.S, P.W - r.wb);
+      const uint32_t wmk = whi > wlo ? ((1u << whi) - 1u) & ~((1u << wlo) - 1u) : 0u;  // (at most 31 taps)
+      uint32_t taps = 0;
+      for (int rr = 0; rr < P.R; ++rr) taps |= (rr >= hlo && rr < hhi) ? wmk << (rr * P.S) : 0u;
       tapsA[i] = taps;
     }
   }
@@ -1197,9 +1204,9 @@ __device__ __forceinline__ void run_tile_lean(const DevProblem &P, const sk_tile
   int k_next = k_begin;
   int t_r = 0, t_s = 0, t_c = 0;
   if constexpr (GATHER) {
-    const int tap = k_begin / P.Cin;
+    const int tap = fast_div(k_begin, P.div_cin);
     t_c = k_begin - tap * P.Cin;
-    t_r = tap / P.S;
+    t_r = fast_div(tap, P.div_s);
     t_s = tap - t_r * P.S;
   }
   u32x4 ra[NS][A_ITERS], rb[NS][B_ITERS];
@@ -1426,9 +1433,9 @@ __device__ __forceinline__ void run_tile_any(const DevProblem *P_mem, const sk_t
         // filter tap and channel of element k (convolutions); later elements by carrying
         int g_r = 0, g_s = 0, g_c = 0;
         if (P.gather && !P.nchw) {
-          const int tap = k / P.Cin;
+          const int tap = fast_div(k, P.div_cin);
           g_c = k - tap * P.Cin;
-          g_r = tap / P.S;
+          g_r = fast_div(tap, P.div_s);
           g_s = tap - g_r * P.S;
         } else if (P.gather) {  // channel-major: k = (c*R + r)*S + s
           const int cr = k / P.S;

@@ -160,6 +160,12 @@ sk_status plan_host(const sk_problem *problems, int32_t n, const sk_plan_params 
       // a 1x1 filter without padding or stride reads the image as a plain [pixels, Cin] matrix
       d.gather = !(p.R == 1 && p.S == 1 && p.pad_h == 0 && p.pad_w == 0 && d.stride == 1);
       d.lda = p.Cin;
+      const FastDiv f_hw = fast_div_of((uint32_t)(c.Ho * c.Wo)), f_wo = fast_div_of((uint32_t)c.Wo);
+      const FastDiv f_cin = fast_div_of((uint32_t)p.Cin), f_s = fast_div_of((uint32_t)p.S);
+      d.div_hw[0] = f_hw.mul, d.div_hw[1] = f_hw.shift;
+      d.div_wo[0] = f_wo.mul, d.div_wo[1] = f_wo.shift;
+      d.div_cin[0] = f_cin.mul, d.div_cin[1] = f_cin.shift;
+      d.div_s[0] = f_s.mul, d.div_s[1] = f_s.shift;
       if (p.op == SK_CONV2D_NCHW) {
         d.nchw = 1;
         d.gather = 1;  // neither a patch row nor an output row is contiguous in this storage order

@@ -41,8 +41,25 @@ struct DevProblem {
   int32_t stride;  // of a convolution, both directions (>= 1)
   int32_t nchw;    // convolution on channel-major arrays: X[Nb,Cin,H,W], W[Cout,Cin,R,S], Y[Nb,Cout,Ho,Wo]
   int32_t pad0;
+  // Division by a convolution's Ho*Wo, Wo, Cin and S as multiply and shift (see FastDiv): the tile set-up
+  // divides row and reduction indices by them for every row a thread stages.
+  uint32_t div_hw[2], div_wo[2], div_cin[2], div_s[2];
 };
 static_assert(sizeof(DevProblem) % 8 == 0, "DevProblem must stay 8-byte sized");
+
+// n / d for 0 <= n < 2^31 as (n * mul) >> shift with mul = floor(2^(31+l) / d) + 1, l = ceil(log2 d), shift = 31 + l:
+// mul * d = 2^(31+l) + e with 0 < e <= d <= 2^l, so the quotient is off by less than n / (d * 2^31) < 1 / d.
+struct FastDiv {
+  uint32_t mul, shift;
+};
+inline FastDiv fast_div_of(uint32_t d) {
+  if (d == 0) return FastDiv{0u, 0u};
+  uint32_t l = 0;
+  while (((uint64_t)1 << l) < d) ++l;
+  const uint64_t mul = (((uint64_t)1 << (31 + l)) / d) + 1;  // < 2^32 + 1; equals 2^32 only for d = 1 ... see below
+  // d = 1: l = 0, mul = 2^31 + 1, shift 31: (n * (2^31 + 1)) >> 31 = n for n < 2^31
+  return FastDiv{(uint32_t)mul, 31u + l};
+}
 
 // What the device reads per tile: the record of the tile table with a copy of its operator's
 // descriptor beside it, so that one fetch (and one prefetch) brings everything a workgroup
@@ -51,7 +68,7 @@ struct TileWork {
   sk_tile tile;
   DevProblem prob;
 };
-static_assert(sizeof(TileWork) == 160, "TileWork layout");
+static_assert(sizeof(TileWork) == 192, "TileWork layout");
 
 struct HostPlan {
   std::vector<sk_problem> problems;

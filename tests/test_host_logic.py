@@ -37,7 +37,7 @@ def test_ceilings_library_exports_its_two_calls():
     import paper_1901_10008_amd
     path = os.path.join(os.path.dirname(paper_1901_10008_amd.__file__), "libsk_ceilings.so")
     lib = ctypes.CDLL(path)   # built by paper_1901_10008_amd.build; loading needs no GPU
-    assert lib.sk_ceiling_stream_read and lib.sk_ceiling_mfma_bf16
+    assert lib.sk_ceiling_stream_read and lib.sk_ceiling_mfma_bf16 and lib.sk_ceiling_lds_read
 
 
 def test_tuned_parameters_round_trip_through_a_file(tmp_path):
