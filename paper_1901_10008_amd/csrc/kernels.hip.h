@@ -763,23 +763,14 @@ __device__ __forceinline__ void run_skinny(const DevProblem &P, const sk_tile &T
   if (finish) store_pass();
 }
 
-// What follows the main loop of an LDS tile: the hand-over of a split reduction and the stores.
-// lane holds, per (fn, fm): row l32 of the 32x32 block, columns 8*(i/4) + 4*half + (i%4).
-template <int DT, int BM, int BN, int WAVES_M, int WAVES_N>
-__device__ __forceinline__ void finish_tile(const DevProblem &P, const sk_tile &T, const SplitK &sp, unsigned char *lds,
-                                            uint32_t *s_flag, int tid,
-                                            f32x16 (&acc)[BN / (32 * WAVES_N)][BM / (32 * WAVES_M)]) {
-  constexpr int ES = Elem<DT>::ES;
-  constexpr int CE = 16 / ES;
-  constexpr int FM = BM / (32 * WAVES_M);
-  constexpr int FN = BN / (32 * WAVES_N);
+// A slice of a split reduction hands its partial sums over; true in the workgroup that arrived last, with the
+// sum of all slices (in slice order) in `acc`; false in the others, which have nothing left to do.
+template <int FM, int FN>
+__device__ __forceinline__ bool split_handover(const sk_tile &T, const SplitK &sp, uint32_t *s_flag, int tid,
+                                               f32x16 (&acc)[FN][FM]) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63;
-  const int wm = wave % WAVES_M, wn = wave / WAVES_M;
-  const int l32 = lane & 31, half = lane >> 5;
-  const int m0 = (int)T.m0, n0 = (int)T.n0;
-  const int m_end = m0 + (int)T.m_len, n_end = n0 + (int)T.n_len;
-  if (T.S > 1) {
+
     // A slice of a split reduction: same hand-over as in the skinny classes.  Partial sums go to
     // the workspace in register layout with device-scope stores (a slice is FN*FM*4 blocks of
     // 64 x 16 bytes per wave); the last slice to arrive adds all of them in slice order.
@@ -800,7 +791,7 @@ __device__ __forceinline__ void finish_tile(const DevProblem &P, const sk_tile &
     if (tid == 0)
       *s_flag = __hip_atomic_fetch_add(&sp.arrive[T.out_tile_id], 1u, SK_ARRIVE_ORDER, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
-    if (*s_flag != (uint32_t)T.S - 1) return;
+    if (*s_flag != (uint32_t)T.S - 1) return false;
 #pragma unroll
     for (int fn = 0; fn < FN; ++fn)
 #pragma unroll
@@ -821,7 +812,26 @@ __device__ __forceinline__ void finish_tile(const DevProblem &P, const sk_tile &
     }
     if (tid == 0)  // re-arm for the next launch
       __hip_atomic_store(&sp.arrive[T.out_tile_id], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  }
+    return true;
+}
+
+// What follows the main loop of an LDS tile: the hand-over of a split reduction and the stores.
+// lane holds, per (fn, fm): row l32 of the 32x32 block, columns 8*(i/4) + 4*half + (i%4).
+template <int DT, int BM, int BN, int WAVES_M, int WAVES_N>
+__device__ __forceinline__ void finish_tile(const DevProblem &P, const sk_tile &T, const SplitK &sp, unsigned char *lds,
+                                            uint32_t *s_flag, int tid,
+                                            f32x16 (&acc)[BN / (32 * WAVES_N)][BM / (32 * WAVES_M)]) {
+  constexpr int ES = Elem<DT>::ES;
+  constexpr int CE = 16 / ES;
+  constexpr int FM = BM / (32 * WAVES_M);
+  constexpr int FN = BN / (32 * WAVES_N);
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lane = tid & 63;
+  const int wm = wave % WAVES_M, wn = wave / WAVES_M;
+  const int l32 = lane & 31, half = lane >> 5;
+  const int m0 = (int)T.m0, n0 = (int)T.n0;
+  const int m_end = m0 + (int)T.m_len, n_end = n0 + (int)T.n_len;
+  if (T.S > 1 && !split_handover<FM, FN>(T, sp, s_flag, tid, acc)) return;
 
   // lane holds, per (fn, fm): row m = l32, columns 8*(i/4) + 4*half + (i%4)
   //
@@ -1398,6 +1408,7 @@ __device__ __forceinline__ void run_tile_any(const DevProblem *P_mem, const sk_t
   const uintptr_t zeros = zero_piece_address();
   const int m_end = (int)T.m0 + (int)T.m_len, n_end = (int)T.n0 + (int)T.n_len;
   const bool vec_c = (P.flags & FLAG_VEC_C) != 0;
+  const bool vec_b = (P.flags & FLAG_VEC_B) != 0;
   const ImageStrides im = image_strides(P);
   unsigned char *sa = lds + srow * LDS_ROW + c8 * 16;
   unsigned char *sb = sa + 128 * LDS_ROW;
@@ -1444,6 +1455,16 @@ __device__ __forceinline__ void run_tile_any(const DevProblem *P_mem, const sk_t
           g_r = cr - g_c * P.R;
         }
         elem_t va[4][CE], vb[4][CE];
+        // weight rows that can be read in 16-byte pieces (always so for channel-major convolutions with aligned
+        // weights: a weight row is contiguous in either storage order) are: half the loads of the stage
+        u32x4 wb16[4];
+        if (vec_b) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const uintptr_t pb = (uintptr_t)P.B + (uintptr_t)((wrow[i] + k) * ES);
+            wb16[i] = *(const u32x4 SK_GLOBAL *)(k < k_stop ? pb : zeros);
+          }
+        }
 #pragma unroll
         for (int e = 0; e < CE; ++e) {
           const bool in = k + e < k_stop;
@@ -1454,8 +1475,12 @@ __device__ __forceinline__ void run_tile_any(const DevProblem *P_mem, const sk_t
                                                  (unsigned)(rows[i].wb + g_s) < (unsigned)P.W));
             const uintptr_t pa = (uintptr_t)P.A + (uintptr_t)((rows[i].base + rel) * ES);
             va[i][e] = *(const elem_t SK_GLOBAL *)(ok ? pa : zeros);
-            const uintptr_t pb = (uintptr_t)P.B + (uintptr_t)((wrow[i] + k + e) * ES);
-            vb[i][e] = *(const elem_t SK_GLOBAL *)(in ? pb : zeros);
+            if (!vec_b) {
+              const uintptr_t pb = (uintptr_t)P.B + (uintptr_t)((wrow[i] + k + e) * ES);
+              vb[i][e] = *(const elem_t SK_GLOBAL *)(in ? pb : zeros);
+            } else {
+              vb[i][e] = 0;
+            }
           }
           if (!P.nchw) {
             if (++g_c == P.Cin) {
@@ -1490,7 +1515,7 @@ __device__ __forceinline__ void run_tile_any(const DevProblem *P_mem, const sk_t
             }
           }
           *(u32x4 *)(sa + 32 * i * LDS_ROW) = qa;
-          *(u32x4 *)(sb + 32 * i * LDS_ROW) = qb;
+          *(u32x4 *)(sb + 32 * i * LDS_ROW) = vec_b ? wb16[i] : qb;
         }
         __syncthreads();
         const unsigned char *la = lds;

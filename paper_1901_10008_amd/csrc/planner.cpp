@@ -173,7 +173,8 @@ sk_status plan_host(const sk_problem *problems, int32_t n, const sk_plan_params 
     }
     int32_t flags = 0;
     if (d.nchw) {
-      // element-wise paths only: no 16-byte pieces along the reduction or along an output row
+      // element-wise paths: no 16-byte pieces of the image along the reduction or along an output row
+      // (the weights, one contiguous row per output channel in either order, may still be read in pieces)
     } else if (d.gather) {
       if (aligned16(p.A) && p.Cin % ce == 0) flags |= FLAG_VEC_A;
     } else {
