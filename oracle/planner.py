@@ -85,8 +85,19 @@ def weight_bytes(p) -> int:
     return ng * kg * ELEM_SIZE[p.dtype]
 
 
+def stream_bytes(p, prm: Params) -> int:
+    """Operand bytes the operator's tiles load, the unit of the tile targets: the weights, once, for a skinny
+    operator; for an LDS-tile operator the 128 + BN operand rows of every 128 x BN output tile over the whole
+    reduction."""
+    mg, ng, kg = canonical(p)
+    if mg <= prm.skinny_max_m:
+        return weight_bytes(p)
+    bn = 64 if ng <= 64 else 128
+    return -(-mg // 128) * -(-ng // bn) * (128 + bn) * kg * ELEM_SIZE[p.dtype]
+
+
 def target_tile_bytes(problems: Sequence, prm: Params) -> int:
-    total = sum(weight_bytes(p) for p in problems)
+    total = sum(stream_bytes(p, prm) for p in problems)
     return max(prm.tile_bytes_min, min(prm.tile_bytes_max, total // prm.balance_div))
 
 
@@ -139,8 +150,8 @@ def plan(problems: Sequence, prm: Params | None = None):
         mg, ng, kg = canonical(p)
         T = T_all
         if prm.tail_div > 0:
-            # weight bytes of this operator and of all that execute after it
-            remaining = sum(weight_bytes(problems[j]) for j in ordr[pos:])
+            # stream bytes of this operator and of all that execute after it
+            remaining = sum(stream_bytes(problems[j], prm) for j in ordr[pos:])
             # never below eight times the lower clamp (unless the whole table's target is)
             T = min(T_all, max(8 * prm.tile_bytes_min, remaining // prm.tail_div))
         cls, BM, BN, S, slice_len = tiling(p, T, prm)

@@ -96,6 +96,16 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 
 
 }  // namespace
 
+// Operand bytes the tiles of an operator load ("stream bytes"): what the tile targets are measured in.
+// A skinny operator reads its weights once.  An operator in the LDS-tile classes reads, per 128 x BN output
+// tile, the 128 + BN operand rows of that tile over the whole reduction: its weight array alone would
+// understate its share of a launch by the number of row blocks.
+static int64_t stream_bytes(int64_t Mg, int64_t Ng, int64_t Kg, int64_t es, const sk_plan_params &prm) {
+  if (Mg <= prm.skinny_max_m) return Ng * Kg * es;
+  const int64_t bn = Ng <= 64 ? 64 : 128;
+  return ((Mg + 127) / 128) * ((Ng + bn - 1) / bn) * (128 + bn) * Kg * es;
+}
+
 sk_status plan_host(const sk_problem *problems, int32_t n, const sk_plan_params *params, HostPlan &out,
                     std::string &err) {
   if (n < 0 || (n > 0 && !problems)) {
@@ -184,7 +194,7 @@ sk_status plan_host(const sk_problem *problems, int32_t n, const sk_plan_params 
     if (!d.nchw && (reinterpret_cast<uintptr_t>(p.C) % (4 * es)) == 0 && d.ldc % 4 == 0) flags |= FLAG_VEC_C;
     d.flags = flags;
     out.dev[i] = d;
-    total_w += c.Ng * c.Kg * es;
+    total_w += stream_bytes(c.Mg, c.Ng, c.Kg, es, prm);
   }
 
   // ---- output ranges must be pairwise disjoint ----
@@ -210,7 +220,7 @@ sk_status plan_host(const sk_problem *problems, int32_t n, const sk_plan_params 
     }
   }
 
-  // ---- target weight bytes per skinny tile ----
+  // ---- target operand bytes per tile ----
   int64_t T = total_w / prm.balance_div;
   T = std::max<int64_t>(prm.tile_bytes_min, std::min<int64_t>(prm.tile_bytes_max, T));
   if (n == 0) T = prm.tile_bytes_min;
@@ -225,11 +235,11 @@ sk_status plan_host(const sk_problem *problems, int32_t n, const sk_plan_params 
     });
   }
 
-  // ---- weight bytes from each position of the order to its end ----
+  // ---- stream bytes from each position of the order to its end ----
   std::vector<int64_t> remaining(n + 1, 0);
   for (int32_t pos = n - 1; pos >= 0; --pos) {
     const int32_t i = out.order[pos];
-    remaining[pos] = remaining[pos + 1] + canon[i].Ng * canon[i].Kg * elem_size(out.problems[i].dtype);
+    remaining[pos] = remaining[pos + 1] + stream_bytes(canon[i].Mg, canon[i].Ng, canon[i].Kg, elem_size(out.problems[i].dtype), prm);
   }
 
   // ---- flat table ----

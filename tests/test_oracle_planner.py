@@ -265,3 +265,35 @@ def test_coverage_checker_catches_planted_mistakes():
         P.check_coverage(probs, _mutate(table, 0, n_len=129))      # rectangle too wide
     with pytest.raises(AssertionError):
         P.check_coverage(probs, _mutate(table, 2, out_tile_id=0))  # id collision
+
+
+def test_targets_count_the_bytes_the_tiles_load():
+    # Hand-worked.  Defaults: balance_div 512, clamps 32 KiB .. 2 MiB, tail_div 384, floor of the tail rule 256 KiB.
+    prm = P.Params()
+    # a skinny operator loads its weights once; an LDS-tile operator loads 128 + BN operand rows per output tile
+    assert P.stream_bytes(gemm(8, 4096, 1024), prm) == 4096 * 1024 * 2
+    assert P.stream_bytes(gemm(2048, 2048, 2048), prm) == 16 * 16 * 256 * 2048 * 2          # 256 MiB, weights: 8 MiB
+    assert P.stream_bytes(gemm(65, 64, 1024), prm) == 1 * 1 * 192 * 1024 * 2                # one 128x64 tile
+    assert P.stream_bytes(conv(56, 64, 64, 3), prm) == 25 * 1 * 192 * 576 * 2               # 3136 rows: 25 row blocks
+    assert P.stream_bytes(gemm(200, 300, 512, "f32"), prm) == 2 * 3 * 256 * 512 * 4
+    # Two 2048-cubed GEMMs.  A tile's operands over the whole reduction are 256 * 2048 * 2 = 1 MiB.
+    # Whole-table target: 2 * 256 MiB / 512 = 1 MiB; tail rule: first operator 512 MiB / 384 > 1 MiB, second
+    # 256 MiB / 384 = 699050 B, so 1 MiB <= 2 T for both: no reduction slices, 2 * 256 tiles.
+    # (Measured in weight bytes the target would be the 32 KiB floor resp. 256 KiB under the tail rule, and every
+    # tile would be cut in two.)
+    t = P.decode(P.plan([gemm(2048, 2048, 2048), gemm(2048, 2048, 2048)], prm)[0])
+    assert len(t) == 512 and all(x["S"] == 1 and x["k_len"] == 2048 and x["cls"] == 9 for x in t)
+    # One 256 x 256 x 4096 GEMM alone: 4 tiles of 256 * 4096 * 2 = 2 MiB each; stream bytes 8 MiB -> 16 KiB, clamped
+    # to 32 KiB; tail rule: max(256 KiB, 8 MiB / 384) = 256 KiB, capped by the 32 KiB table target.  2 MiB > 64 KiB:
+    # wanted min(16 chunks, 64, 255, 4096 / 1024) = 4 slices of 1024.
+    t = P.decode(P.plan([gemm(256, 256, 4096)], prm)[0])
+    assert len(t) == 16 and [(x["ks_idx"], x["S"], x["k0"], x["k_len"]) for x in t[:4]] == \
+        [(0, 4, 0, 1024), (1, 4, 1024, 1024), (2, 4, 2048, 1024), (3, 4, 3072, 1024)]
+    # A skinny operator behind a large LDS-tile operator: the table target is the upper clamp (2 MiB) because of the
+    # large one, and the skinny operator, last in order, falls under the tail rule with its own weights only:
+    # 4096 * 4096 * 2 = 32 MiB / 384 = 87381 -> floor 256 KiB; one group is 32 * 4096 * 2 = 256 KiB, four exceed it:
+    # 4 groups per tile, reduction cut: chunk 512, 8 chunks, wanted min(8, 4, 255) = 4 slices of 1024.
+    t = P.decode(P.plan([gemm(4096, 4096, 4096, deadline=1.0), gemm(4, 4096, 4096, deadline=2.0)], prm)[0])
+    sk = [x for x in t if x["problem"] == 1]
+    assert len(sk) == 32 * 4 and {(x["n_len"], x["S"], x["k_len"]) for x in sk} == {(128, 4, 1024)}
+    assert all(x["S"] == 1 for x in t if x["problem"] == 0)   # 256 * 4096 * 2 = 2 MiB <= 2 * 2 MiB
