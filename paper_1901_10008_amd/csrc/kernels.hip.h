@@ -97,6 +97,15 @@ struct KernelArgs {
   uint32_t *arrive;
 };
 
+#ifdef SK_DIAG_CLOCKS
+// diagnostic build only: per workgroup (first 16) and tile (first 64) eight clock stamps
+__device__ uint64_t g_diag[16 * 64 * 8];
+__device__ int g_diag_tile;  // unused
+#define SK_DIAG(slot_) do { if (blockIdx.x < 16 && diag_tile < 64 && threadIdx.x == 0) g_diag[(blockIdx.x * 64 + diag_tile) * 8 + (slot_)] = wall_clock64(); } while (0)
+#else
+#define SK_DIAG(slot_) do { } while (0)
+#endif
+
 // ---------------------------------------------------------------------------
 // element helpers
 // ---------------------------------------------------------------------------
@@ -450,6 +459,9 @@ struct Prefetch {
   uint32_t last;      // last valid index of the launch
   int tid;            // this tile's copy of the thread index (see the tile loop)
   uint32_t word = 0;
+#ifdef SK_DIAG_CLOCKS
+  int diag_tile = 0;
+#endif
   __device__ __forceinline__ void claim() {
     // (lanes other than thread 0 keep whatever `next` held: it is never used, and any
     // instruction that touched the register here would have to wait for an earlier answer)
@@ -1305,6 +1317,210 @@ __device__ __forceinline__ void run_tile_lean(const DevProblem &P, const sk_tile
   finish_tile<DT, BM, BN, WAVES_M, WAVES_N>(P, T, sp, lds, s_flag, tid, acc);
 }
 
+// ---------------------------------------------------------------------------
+// LDS tiles fed by direct global-to-LDS loads
+// ---------------------------------------------------------------------------
+// The same tile, fragments and MFMAs, but the operand pieces never pass through registers:
+// a buffer load with the LDS modifier writes the 16 bytes of lane i at (M0 + 16 i) of the LDS,
+// 1 KB per wave and instruction, and a piece whose offset lies outside the descriptor arrives
+// as zeros.  What this removes from a stage: the register ring (96 registers), the LDS stores
+// with their counted waits, and all but one or two instructions per piece.
+//   * LDS image of a stage: (BM + BN) rows of 128 bytes, no padding (a load instruction fills
+//     eight consecutive rows); position p of row r holds the row's piece p ^ ((r >> 1) & 7), so
+//     the 16 lanes that a fragment read serves together (rows r .. r+15, one piece) fall into
+//     16 different groups of four banks.  The swizzle is applied on the global side: lane i of
+//     a load asks for piece (i & 7) ^ swizzle(row of the lane).
+//   * a ring of NS such images (as many as fit LDS_TILE_BYTES): stages h+1 .. h+NS-2 are in
+//     flight while stage h is multiplied; one barrier per stage says both "everyone's part of
+//     stage h has landed" and "everyone is done with the image that stage h+NS-1 will overwrite".
+//   * the compiler does not see these loads (inline assembly; told about them it would wait for
+//     all of them before every LDS read), so the waits are written out: loads complete in order,
+//     hence "at most n outstanding" with n the loads of the stages issued later.  Loads and
+//     stores of the surrounding code that are also in flight only make these waits, and the
+//     compiler's own, wait for more than they need.
+__device__ __forceinline__ void dma_piece(__amdgpu_buffer_rsrc_t desc, uint32_t voff, uint32_t soff, uint32_t lds_addr) {
+  asm volatile("buffer_load_dwordx4 %0, %1, %2 offen lds" ::"v"(voff), "s"(desc), "s"(soff), "{m0}"(lds_addr) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_loads_but() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <int DT, int BM, int BN, bool GATHER>
+__device__ __forceinline__ void run_tile_dma(const DevProblem &P, const sk_tile &T, const SplitK &sp, unsigned char *lds,
+                                             uint32_t *s_flag, Prefetch &pf, const LeanOperands &L) {
+  constexpr int ES = Elem<DT>::ES;
+  constexpr int CE = 16 / ES;
+  constexpr int KB = 8 * CE;                  // reduction elements per stage (128 bytes per row)
+  constexpr int FM = BM / 64, FN = BN / 64;   // 32x32 blocks per wave along m and n (2 x 2 waves)
+  constexpr int NA = BM / 32, NBW = BN / 32;  // load instructions per wave and stage: activations, weights
+  constexpr int NPW = NA + NBW;
+  constexpr int SLOT = (BM + BN) * 128;       // bytes of a stage in LDS
+  constexpr int NS = LDS_TILE_BYTES / SLOT;   // ring slots
+  constexpr uint32_t NOWHERE = 0x80000000u;   // an offset outside every descriptor: the piece arrives as zeros
+  static_assert(NS == 2 || NS == 3, "waits below are written for two or three slots");
+  static_assert(NPW < 32, "load counter");
+
+  const int tid = pf.tid;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lane = tid & 63;
+  const int wm = wave & 1, wn = wave >> 1;
+  const int l32 = lane & 31, half = lane >> 5;
+
+  const int m0 = (int)T.m0, n0 = (int)T.n0;
+  const int m_end = m0 + (int)T.m_len, n_end = n0 + (int)T.n_len;
+  const int k_begin = (int)T.k0, k_stop = (int)T.k0 + (int)T.k_len;
+
+  const __amdgpu_buffer_rsrc_t descA = __builtin_amdgcn_make_buffer_rsrc((void *)L.baseA, 0, (int)L.extA, 0x00020000);
+  const __amdgpu_buffer_rsrc_t descB = __builtin_amdgcn_make_buffer_rsrc((void *)L.baseB, 0, (int)L.extB, 0x00020000);
+
+  // load map: instruction i of this wave fills rows 8 (wave + 4 i) .. + 7 of the operand's block; this lane
+  // supplies position lane & 7 of row 8 (wave + 4 i) + lane / 8, which holds the logical piece c_log
+  // (the swizzle of the lane's row is the same for every i)
+  const int lrow = lane >> 3;
+  const int c_log = (lane & 7) ^ (((wave & 1) << 2) | (lane >> 4));
+  uint32_t offA[NA];   // byte offset of this lane's piece of row i at reduction index 0 (tap (0,0), channel 0)
+  uint32_t tapsA[NA];  // convolution: bit (r*S + s) set if the row's pixel under tap (r, s) lies in the image
+#pragma unroll
+  for (int i = 0; i < NA; ++i) {
+    const int m = m0 + 8 * (wave + 4 * i) + lrow;
+    const bool in = m < m_end;  // rows past the edge arrive as zeros; never stored
+    if constexpr (!GATHER) {
+      offA[i] = in ? (uint32_t)((m - m0) * (int)P.lda * ES) + (uint32_t)c_log * 16u : NOWHERE;
+      tapsA[i] = 0;
+    } else {
+      const RowA r = row_of(P, in ? m : m_end - 1);
+      offA[i] = (uint32_t)((r.base - L.originA) * ES) + (uint32_t)c_log * 16u;
+      // filter rows rr with 0 <= hb + rr < H form a range [lo, hi), and so do the filter columns
+      const int hlo = max(0, -r.hb), hhi = min(P.R, P.H - r.hb);
+      const int wlo = max(0, -r.wb), whi = min(P.S, P.W - r.wb);
+      const uint32_t wmk = whi > wlo ? ((1u << whi) - 1u) & ~((1u << wlo) - 1u) : 0u;  // (at most 31 taps)
+      uint32_t taps = 0;
+      for (int rr = 0; rr < P.R; ++rr) taps |= (rr >= hlo && rr < hhi) ? wmk << (rr * P.S) : 0u;
+      tapsA[i] = in ? taps : 0u;
+    }
+  }
+  uint32_t offB[NBW];
+#pragma unroll
+  for (int i = 0; i < NBW; ++i) {
+    const int n = n0 + 8 * (wave + 4 * i) + lrow;
+    offB[i] = n < n_end ? (uint32_t)((n - n0) * (int)P.ldb * ES) + (uint32_t)c_log * 16u : NOWHERE;
+  }
+
+  f32x16 acc[FN][FM];
+#pragma unroll
+  for (int fn = 0; fn < FN; ++fn)
+#pragma unroll
+    for (int fm = 0; fm < FM; ++fm)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[fn][fm][i] = 0.f;
+
+  // scalar position of the next stage to load: reduction index k_next; for a convolution the tap
+  // (t_r, t_s) and the first channel t_c of the stage
+  int k_next = k_begin;
+  int t_r = 0, t_s = 0, t_c = 0;
+  if constexpr (GATHER) {
+    const int tap = fast_div(k_begin, P.div_cin);
+    t_c = k_begin - tap * P.Cin;
+    t_r = fast_div(tap, P.div_s);
+    t_s = tap - t_r * P.S;
+  }
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds;
+  const uint32_t my_blocks = lds_base + (uint32_t)wave * 1024u;  // + slot*SLOT + 4096 i (activations), + BM*128 + 4096 i (weights)
+  auto issue = [&](int slot) {
+    const uint32_t kbytes = (uint32_t)k_next * ES;
+    const uint32_t dst = my_blocks + (uint32_t)slot * SLOT;
+    if constexpr (GATHER) {
+      // (no reduction tail: the reduction length is a multiple of the channel count, that of a stage)
+      const uint32_t tapbit = 1u << ((t_r * P.S + t_s) & 31);
+      const uint32_t tapoff = (uint32_t)(((t_r * P.W + t_s) * P.Cin + t_c) * ES);
+#pragma unroll
+      for (int i = 0; i < NA; ++i) dma_piece(descA, (tapsA[i] & tapbit) ? offA[i] : NOWHERE, tapoff, dst + 4096u * i);
+#pragma unroll
+      for (int i = 0; i < NBW; ++i) dma_piece(descB, offB[i], kbytes, dst + BM * 128u + 4096u * i);
+      t_c += KB;
+      if (t_c >= P.Cin) {
+        t_c = 0;
+        if (++t_s == P.S) {
+          t_s = 0;
+          ++t_r;
+        }
+      }
+    } else {
+      // this lane's piece lies beyond the end of the reduction (last stage of a length that is not a
+      // multiple of a stage): nowhere
+      const uint32_t tail = k_next + c_log * CE < k_stop ? 0u : NOWHERE;
+#pragma unroll
+      for (int i = 0; i < NA; ++i) dma_piece(descA, offA[i] | tail, kbytes, dst + 4096u * i);
+#pragma unroll
+      for (int i = 0; i < NBW; ++i) dma_piece(descB, offB[i] | tail, kbytes, dst + BM * 128u + 4096u * i);
+    }
+    k_next += KB;
+  };
+
+  // fragment addresses inside a slot: row (w*F + f)*32 + l32, logical piece 2 kk + half at position
+  // (2 kk + half) ^ swizzle(row), and swizzle(row) = (l32 >> 1) & 7 for every block of 32 rows
+  const int frag_off = l32 * 128;
+  const int frag_pos = half ^ ((l32 >> 1) & 7);  // position of piece `half`; piece 2 kk + half is at frag_pos ^ 2 kk
+  const int a_base = wm * FM * 4096;
+  const int b_base = BM * 128 + wn * FN * 4096;
+
+#ifdef SK_DIAG_CLOCKS
+  const int diag_tile = pf.diag_tile;
+#endif
+  SK_DIAG(1);
+  const int nstages = (k_stop - k_begin + KB - 1) / KB;
+  // (the previous tile's readers of this LDS buffer have passed the barrier at the end of their tile)
+#pragma unroll
+  for (int u = 0; u < NS - 1; ++u)
+    if (u < nstages) issue(u);
+  int slot = 0;
+  for (int h = 0; h < nstages; ++h) {
+    pf.at_step(h, nstages, CLAIM_LEAD, ISSUE_GAP);
+    // this wave's loads of stage h have landed: the only loads issued after them are those of stage h+1
+    if (NS == 3 && h + 1 < nstages)
+      wait_loads_but<NPW>();
+    else
+      wait_loads_but<0>();
+    __builtin_amdgcn_s_barrier();  // ... and everyone's; everyone is done with stage h-1
+    asm volatile("" ::: "memory");
+    if (h == 0) SK_DIAG(2);
+    if (h + NS - 1 < nstages) issue(slot == 0 ? NS - 1 : slot - 1);  // stage h+NS-1 into the slot stage h-1 used
+    __builtin_amdgcn_sched_barrier(0);
+    const unsigned char *la = lds + slot * SLOT + a_base + frag_off;
+    const unsigned char *lb = lds + slot * SLOT + b_base + frag_off;
+    // the fragments of step kk+1 are requested before the MFMAs of step kk (the scheduler is held to
+    // that order: left alone it sinks every read to just above its first use).  Requesting all four
+    // steps' fragments at the start of the stage was measured slower: the waves of a workgroup leave
+    // the barrier together, and their reads then queue at the LDS.
+    u32x4 fa[2][FM], fb[2][FN];
+    auto frag = [&](int kk, u32x4(&xa)[FM], u32x4(&xb)[FN]) {
+      const int pos = (frag_pos ^ (2 * kk)) << 4;
+#pragma unroll
+      for (int fm = 0; fm < FM; ++fm) xa[fm] = *(const u32x4 *)(la + fm * 4096 + pos);
+#pragma unroll
+      for (int fn = 0; fn < FN; ++fn) xb[fn] = *(const u32x4 *)(lb + fn * 4096 + pos);
+    };
+    frag(0, fa[0], fb[0]);
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      if (kk + 1 < 4) frag(kk + 1, fa[(kk + 1) & 1], fb[(kk + 1) & 1]);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int fn = 0; fn < FN; ++fn)
+#pragma unroll
+        for (int fm = 0; fm < FM; ++fm) mma32<DT>(fb[kk & 1][fn], fa[kk & 1][fm], acc[fn][fm]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (h == 0) SK_DIAG(7);
+    slot = slot + 1 == NS ? 0 : slot + 1;
+  }
+  SK_DIAG(3);
+  __syncthreads();  // everyone is done with the last stage before the output tile is staged in the same LDS
+  finish_tile<DT, BM, BN, 2, 2>(P, T, sp, lds, s_flag, tid, acc);
+  SK_DIAG(4);
+}
+
 // One LDS tile: the lean path where the operator allows it.
 template <int DT, int BM, int BN>
 __device__ __forceinline__ void run_lds_tile(const DevProblem &P, const sk_tile &T, const SplitK &sp, unsigned char *lds,
@@ -1312,10 +1528,17 @@ __device__ __forceinline__ void run_lds_tile(const DevProblem &P, const sk_tile 
 #ifndef SK_NO_LEAN_TILES
   LeanOperands L;
   if (lean_operands<Elem<DT>::ES>(P, T, L)) {
+#ifdef SK_REGISTER_RING_TILES
     if (P.gather)
       run_tile_lean<DT, BM, BN, 2, 2, true>(P, T, sp, lds, s_flag, pf, L);
     else
       run_tile_lean<DT, BM, BN, 2, 2, false>(P, T, sp, lds, s_flag, pf, L);
+#else
+    if (P.gather)
+      run_tile_dma<DT, BM, BN, true>(P, T, sp, lds, s_flag, pf, L);
+    else
+      run_tile_dma<DT, BM, BN, false>(P, T, sp, lds, s_flag, pf, L);
+#endif
     return;
   }
 #endif
@@ -1703,6 +1926,9 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sk_superkernel(const TileWork *
   uint32_t t = a.tile_begin + blockIdx.x;
   TileWork W = load_uniform(work + (t < a.tile_end ? t : a.tile_end - 1u));
   int par = 0;
+#ifdef SK_DIAG_CLOCKS
+  int diag_tile = 0;
+#endif
   while (t < a.tile_end) {
     // Everything a tile derives from the thread index is derived again for each tile, from a
     // copy the compiler cannot see through: hoisted out of this loop those values would stay
@@ -1712,6 +1938,10 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sk_superkernel(const TileWork *
     asm volatile("" : "+v"(tid));
     Prefetch pf{work, a.dynamic ? &a.counters[0] : nullptr, a.dynamic ? a.tile_begin + gridDim.x : 0u, t + gridDim.x,
                 a.tile_end - 1u, tid};
+#ifdef SK_DIAG_CLOCKS
+    pf.diag_tile = diag_tile;
+#endif
+    SK_DIAG(0);
     const sk_tile &T = W.tile;
     const DevProblem &P = W.prob;
     if constexpr (ONLY_DT >= 0) {
@@ -1742,6 +1972,11 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sk_superkernel(const TileWork *
     t = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_mail[par][WORK_DWORDS]);
     W = unpack_uniform<TileWork>(s_mail[par]);
     par ^= 1;
+    SK_DIAG(5);
+#ifdef SK_DIAG_CLOCKS
+    if (blockIdx.x < 16 && diag_tile < 64 && threadIdx.x == 0) g_diag[(blockIdx.x * 64 + diag_tile) * 8 + 6] = 1;
+    ++diag_tile;
+#endif
   }
 
   // the last workgroup to leave re-arms the queue for the next launch

@@ -432,6 +432,18 @@ sk_status sk_plan_destroy(sk_plan *plan) {
   return st;
 }
 
+#ifdef SK_DIAG_CLOCKS
+int sk_diag_read(void *dst, uint64_t bytes) {
+  return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(sk::g_diag), bytes <= sizeof(sk::g_diag) ? bytes : sizeof(sk::g_diag));
+}
+int sk_diag_clear(void) {
+  void *p = nullptr;
+  hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(sk::g_diag));
+  if (e != hipSuccess) return (int)e;
+  return (int)hipMemset(p, 0, sizeof(sk::g_diag));
+}
+#endif
+
 sk_status sk_release_cached_memory(void) {
   hipError_t e = table_pool().trim();
   if (e != hipSuccess) return hip_error("hipFree", e);
