@@ -70,7 +70,9 @@ class QueueStats(C.Structure):
 
 
 def lib_path() -> str:
-    return os.path.join(HERE, "libsuperkernel.so")
+    """libsuperkernel.so next to this file; SK_LIBRARY names another build of it (the diagnostic one of
+    `tile_phases`)."""
+    return os.environ.get("SK_LIBRARY") or os.path.join(HERE, "libsuperkernel.so")
 
 
 _lib = None

@@ -23,18 +23,27 @@ HIPCC_FLAGS = [
 ]
 
 
-def build(force: bool = True, verbose: bool = False, extra=()) -> str:
+DIAG_LIB = os.path.join(HERE, "libsuperkernel_diag.so")  # -DSK_DIAG_CLOCKS: per-tile phase stamps (tile_phases.py)
+
+
+def build_diag(verbose: bool = False) -> str:
+    """The library once more with -DSK_DIAG_CLOCKS, as libsuperkernel_diag.so (a measuring aid: every tile
+    of the first workgroups stamps the device clock at its phase boundaries).  Not built by build()."""
+    return build(force=True, verbose=verbose, extra=("-DSK_DIAG_CLOCKS",), lib=DIAG_LIB, ceilings=False, tag="diag")
+
+
+def build(force: bool = True, verbose: bool = False, extra=(), lib: str = LIB, ceilings: bool = True, tag: str = "") -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     srcs = [os.path.join(CSRC, s) for s in SOURCES]
-    if not force and os.path.exists(LIB):
+    if not force and os.path.exists(lib):
         newest = max(os.path.getmtime(p) for p in srcs + [os.path.join(CSRC, h) if not os.path.isabs(h) else h
                                                           for h in HEADERS])
-        if os.path.getmtime(LIB) >= newest:
-            return LIB
+        if os.path.getmtime(lib) >= newest:
+            return lib
     inc = ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
     obj_dir = os.path.join(HERE, "_build")
     os.makedirs(obj_dir, exist_ok=True)
-    o_hip = os.path.join(obj_dir, "superkernel.o")
+    o_hip = os.path.join(obj_dir, f"superkernel{tag}.o")
     o_cpp = os.path.join(obj_dir, "planner.o")
     o_queue = os.path.join(obj_dir, "queue.o")
     steps = [
@@ -43,11 +52,12 @@ def build(force: bool = True, verbose: bool = False, extra=()) -> str:
         # host code that calls the HIP runtime (events): the host compiler with the runtime's headers
         ["g++", "-O2", "-std=c++17", "-fPIC", "-Wall", "-D__HIP_PLATFORM_AMD__", "-I", "/opt/rocm/include", *inc, "-c", srcs[2],
          "-o", o_queue],
-        [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", o_hip, o_cpp, o_queue, "-o", LIB],
-        [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         os.path.join(CSRC, "ceilings.hip"), "-o", CEILINGS_LIB],
+        [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", o_hip, o_cpp, o_queue, "-o", lib],
     ]
+    if ceilings:
+        steps.append([hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+                      "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+                      os.path.join(CSRC, "ceilings.hip"), "-o", CEILINGS_LIB])
     for cmd in steps:
         if verbose:
             print(" ".join(cmd))
@@ -58,7 +68,7 @@ def build(force: bool = True, verbose: bool = False, extra=()) -> str:
             raise RuntimeError("build step failed: " + " ".join(cmd) + "\n" + err)
         if verbose and err.strip():
             print(err)
-    return LIB
+    return lib
 
 
 if __name__ == "__main__":

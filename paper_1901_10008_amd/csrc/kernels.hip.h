@@ -98,12 +98,22 @@ struct KernelArgs {
 };
 
 #ifdef SK_DIAG_CLOCKS
-// diagnostic build only: per workgroup (first 16) and tile (first 64) eight clock stamps
-__device__ uint64_t g_diag[16 * 64 * 8];
-__device__ int g_diag_tile;  // unused
-#define SK_DIAG(slot_) do { if (blockIdx.x < 16 && diag_tile < 64 && threadIdx.x == 0) g_diag[(blockIdx.x * 64 + diag_tile) * 8 + (slot_)] = wall_clock64(); } while (0)
+// Diagnostic build (-DSK_DIAG_CLOCKS, a library of its own: see build_diag in build.py and tile_phases.py): thread 0
+// of the first SK_DIAG_WGS workgroups stamps the 100 MHz device clock at the phase boundaries of its first
+// SK_DIAG_TILES tiles.  Slots per tile: 0 tile taken up, 1 set-up done (before the first operand loads), 2 first
+// main-loop step multiplied, 3 main loop done, 4 outputs stored (and split-reduction hand-over done), 5 next
+// record handed to all waves, 6 = 1 + tile class + 100 * reduction slices.
+constexpr int SK_DIAG_WGS = 16, SK_DIAG_TILES = 64;
+__device__ uint64_t g_diag[SK_DIAG_WGS * SK_DIAG_TILES * 8];
+#define SK_DIAG(slot_)                                                               \
+  do {                                                                               \
+    if (blockIdx.x < SK_DIAG_WGS && diag_tile < SK_DIAG_TILES && threadIdx.x == 0)   \
+      g_diag[(blockIdx.x * SK_DIAG_TILES + diag_tile) * 8 + (slot_)] = wall_clock64(); \
+  } while (0)
 #else
-#define SK_DIAG(slot_) do { } while (0)
+#define SK_DIAG(slot_) \
+  do {                 \
+  } while (0)
 #endif
 
 // ---------------------------------------------------------------------------
@@ -664,6 +674,10 @@ __device__ __forceinline__ void run_skinny(const DevProblem &P, const sk_tile &T
     }
   };
 
+#ifdef SK_DIAG_CLOCKS
+  const int diag_tile = pf.diag_tile;
+#endif
+  SK_DIAG(1);
   set_load_rows(0);
   stage_load(0);
   u32x4 w[NB][4];
@@ -720,6 +734,7 @@ __device__ __forceinline__ void run_skinny(const DevProblem &P, const sk_tile &T
             mma16<DT>(y1, a1[mb], acc[1][mb]);
           }
         }
+        if (i0 + u == 0) SK_DIAG(2);
         if (++blk == nslots && it + 1 < iters) {
           // this weight group is done; the next one's loads are already in flight
           store_pass();
@@ -734,6 +749,7 @@ __device__ __forceinline__ void run_skinny(const DevProblem &P, const sk_tile &T
     }
   }
 
+  SK_DIAG(3);
   // last pass (the only one of a split rectangle, which has at most four weight groups)
   bool finish = true;
   if (T.S > 1) {
@@ -773,6 +789,7 @@ __device__ __forceinline__ void run_skinny(const DevProblem &P, const sk_tile &T
     }
   }
   if (finish) store_pass();
+  SK_DIAG(4);
 }
 
 // A slice of a split reduction hands its partial sums over; true in the workgroup that arrived last, with the
@@ -1484,7 +1501,6 @@ __device__ __forceinline__ void run_tile_dma(const DevProblem &P, const sk_tile 
       wait_loads_but<0>();
     __builtin_amdgcn_s_barrier();  // ... and everyone's; everyone is done with stage h-1
     asm volatile("" ::: "memory");
-    if (h == 0) SK_DIAG(2);
     if (h + NS - 1 < nstages) issue(slot == 0 ? NS - 1 : slot - 1);  // stage h+NS-1 into the slot stage h-1 used
     __builtin_amdgcn_sched_barrier(0);
     const unsigned char *la = lds + slot * SLOT + a_base + frag_off;
@@ -1512,7 +1528,7 @@ __device__ __forceinline__ void run_tile_dma(const DevProblem &P, const sk_tile 
         for (int fm = 0; fm < FM; ++fm) mma32<DT>(fb[kk & 1][fn], fa[kk & 1][fm], acc[fn][fm]);
       __builtin_amdgcn_sched_barrier(0);
     }
-    if (h == 0) SK_DIAG(7);
+    if (h == 0) SK_DIAG(2);
     slot = slot + 1 == NS ? 0 : slot + 1;
   }
   SK_DIAG(3);
@@ -1943,6 +1959,10 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sk_superkernel(const TileWork *
 #endif
     SK_DIAG(0);
     const sk_tile &T = W.tile;
+#ifdef SK_DIAG_CLOCKS
+    if (blockIdx.x < SK_DIAG_WGS && diag_tile < SK_DIAG_TILES && threadIdx.x == 0)
+      g_diag[(blockIdx.x * SK_DIAG_TILES + diag_tile) * 8 + 6] = 1 + T.cls + 100ull * T.S;
+#endif
     const DevProblem &P = W.prob;
     if constexpr (ONLY_DT >= 0) {
       run_class<ONLY_DT, ANY_ALIGNMENT>(P, T, &work[t].prob, &work[t].tile, sp, lds, &s_flag, pf);
@@ -1974,7 +1994,6 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sk_superkernel(const TileWork *
     par ^= 1;
     SK_DIAG(5);
 #ifdef SK_DIAG_CLOCKS
-    if (blockIdx.x < 16 && diag_tile < 64 && threadIdx.x == 0) g_diag[(blockIdx.x * 64 + diag_tile) * 8 + 6] = 1;
     ++diag_tile;
 #endif
   }

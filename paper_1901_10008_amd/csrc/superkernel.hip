@@ -433,6 +433,8 @@ sk_status sk_plan_destroy(sk_plan *plan) {
 }
 
 #ifdef SK_DIAG_CLOCKS
+// Diagnostic build only (not in include/superkernel.h): copies the phase stamps of the current device to `dst`
+// (host memory, at most `bytes`), resp. zeroes them.  Return a hipError_t.
 int sk_diag_read(void *dst, uint64_t bytes) {
   return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(sk::g_diag), bytes <= sizeof(sk::g_diag) ? bytes : sizeof(sk::g_diag));
 }

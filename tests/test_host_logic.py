@@ -73,3 +73,25 @@ def test_cotenancy_table_marks_both_optima():
            "mix_best_target": 2048, "solo_penalty_with_mix_best": 1.2, "mix_penalty_with_solo_best": 1.125}
     txt = tune.cotenancy_table(rep, "operator 0")
     assert "best alone" in txt.splitlines()[3] and "best for the mix" in txt.splitlines()[4] and "x1.2;" in txt
+
+
+def test_tile_phase_table_from_stamps():
+    """tile_phases: the table is built from the stamps alone (no device): tiles without stamps are skipped,
+    classes and reduction slices are told apart, times are differences of the 100 MHz stamps in microseconds."""
+    import numpy as np
+    from paper_1901_10008_amd import tile_phases as tp
+
+    st = np.zeros((tp.WGS, tp.TILES, 8), dtype=np.int64)
+    # one skinny 16-row tile: taken up at 1000, set-up 100 ticks, first step 300, loop 10000, outputs 50, hand-over 150
+    st[0, 0] = [1000, 1100, 1400, 11400, 11450, 11600, 1 + 0 + 100 * 1, 0]
+    # two 128x128 slices of a split reduction (3 slices) with different loop times
+    st[1, 0] = [0, 200, 400, 2400, 2600, 2700, 1 + 9 + 100 * 3, 0]
+    st[1, 1] = [5000, 5200, 5400, 9400, 9600, 9700, 1 + 9 + 100 * 3, 0]
+    st[2, 5] = [7, 0, 0, 0, 0, 0, 1 + 6 + 100, 0]   # a tile that left no further stamps: skipped
+    txt = tp.phase_table(st).splitlines()
+    assert len(txt) == 3
+    sk16 = txt[1].split()
+    assert txt[1].startswith("skinny, 16 rows") and sk16[-6:] == ["1.00", "3.00", "100.00", "0.50", "1.50", "106.00"] and sk16[-7] == "1"
+    sl = txt[2].split()
+    assert txt[2].startswith("LDS tile 128x128, slice") and sl[-7] == "2"
+    assert sl[-6:] == ["2.00", "2.00", "30.00", "2.00", "1.00", "37.00"]
