@@ -326,6 +326,20 @@ def measured_ceilings(torch, achieved_gbs, achieved_tflops):
             return {"error": f"sk_ceiling_lds_read status {st}"}
         res["lds_fragment_read_GBs"] = round(g.value, 1)
         res["lds_fragment_read_bytes_per_clk_per_cu"] = round(bpc.value, 1)
+        # the LDS-tile stage loop by itself on sixteen 2048-cubed products: whole, without operand loads, loads only
+        del buf
+        lib.sk_ceiling_tile_loop.argtypes = [C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_double)]
+        ta = (torch.randn(16 * 2048 * 2048, device="cuda") * 0.5).to(torch.bfloat16)
+        tb = (torch.randn(16 * 2048 * 2048, device="cuda") * 0.5).to(torch.bfloat16)
+        tc = torch.empty(16 * 2048 * 2048, dtype=torch.bfloat16, device="cuda")
+        for mode, name in ((0, "lds_tile_loop_TFLOPs"), (1, "lds_tile_loop_without_loads_TFLOPs"),
+                           (2, "lds_tile_loop_loads_only_TFLOPs")):
+            st = lib.sk_ceiling_tile_loop(mode, ta.data_ptr(), tb.data_ptr(), tc.data_ptr(), C.byref(v))
+            if st != 0:
+                return {"error": f"sk_ceiling_tile_loop status {st}"}
+            res[name] = round(v.value, 1)
+        del ta, tb, tc
+        buf = None
         best = max(res["stream_read_GBs_rows_of_16384B"], res["stream_read_GBs_rows_of_2048B"])
         res["achieved_over_stream_read"] = round(achieved_gbs / best, 4)
         res["achieved_over_mfma_loop"] = round(achieved_tflops / res["mfma_bf16_TFLOPs"], 4)

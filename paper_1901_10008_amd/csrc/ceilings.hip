@@ -98,6 +98,96 @@ __global__ void __launch_bounds__(256, 2) lds_read_loop(int iters, f32x4 *sink) 
   if (acc[0] == 12345.678f) sink[blockIdx.x] = acc;
 }
 
+// The stage loop of the LDS-tile class by itself, without anything of the superkernel around it: sixteen
+// 2048 x 2048 x 2048 bf16 products (C = A . B^T, both K-contiguous) in 128 x 128 tiles that are handed out
+// statically (workgroup b takes tiles b, b + grid, ...), operands by direct global-to-LDS loads into two
+// swizzled stage images, fragments one step ahead of the 32x32x16 MFMAs, one barrier per stage.
+// MODE 0: the whole loop.  1: no operand loads (fragment reads, MFMAs and the barrier: what LDS and the
+// matrix cores allow).  2: operand loads and barrier only (what the path from the L2s to LDS allows).
+__device__ __forceinline__ void tile_dma16(const void *gptr, uint32_t lds_addr) {
+  // lane i's 16 bytes land at lds_addr + 16 i
+  asm volatile("global_load_lds_dwordx4 %0, off" ::"v"(gptr), "{m0}"(lds_addr) : "memory");
+}
+template <int MODE>
+__global__ void __launch_bounds__(256, 2) tile_loop(const uint16_t *A, const uint16_t *B, uint16_t *Cout, int M, int N, int K,
+                                                    int nb, int rounds) {
+  constexpr int SLOT = 256 * 128;
+  __shared__ __attribute__((aligned(16))) unsigned char lds[2 * SLOT];
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds;
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+  const int wm = wave & 1, wn = wave >> 1, l32 = lane & 31, half = lane >> 5;
+  const int c_log = (lane & 7) ^ (((wave & 1) << 2) | (lane >> 4));
+  const int frag_off = l32 * 128, frag_pos = half ^ ((l32 >> 1) & 7);
+  const int TM = M / 128, TN = N / 128;
+  for (int it = 0; it < rounds; ++it) {
+    const int t = blockIdx.x + it * gridDim.x;
+    if (t >= nb * TM * TN) break;
+    const int b = t / (TM * TN), r = t - b * TM * TN, m0 = (r / TN) * 128, n0 = (r % TN) * 128;
+    const char *pa[4], *pb[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      pa[i] = (const char *)(A + ((size_t)b * M + m0 + 8 * (wave + 4 * i) + (lane >> 3)) * K + c_log * 8);
+      pb[i] = (const char *)(B + ((size_t)b * N + n0 + 8 * (wave + 4 * i) + (lane >> 3)) * K + c_log * 8);
+    }
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) acc[i >> 1][i & 1][j] = 0.f;
+    const int nst = K / 64;
+    auto issue = [&](int k, int slot) {
+      if (MODE == 1) return;
+      const uint32_t dst = lds_base + slot * SLOT + wave * 1024;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) tile_dma16(pa[i] + (size_t)k * 128, dst + 4096 * i);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) tile_dma16(pb[i] + (size_t)k * 128, dst + 128 * 128 + 4096 * i);
+    };
+    issue(0, 0);
+    for (int h = 0; h < nst; ++h) {
+      const int slot = h & 1;
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
+      if (h + 1 < nst) issue(h + 1, slot ^ 1);
+      __builtin_amdgcn_sched_barrier(0);
+      if (MODE != 2) {
+        const unsigned char *la = lds + slot * SLOT + wm * 2 * 4096 + frag_off;
+        const unsigned char *lb = lds + slot * SLOT + 128 * 128 + wn * 2 * 4096 + frag_off;
+        u32x4 fa[2][2], fb[2][2];
+        auto frag = [&](int kk, u32x4(&xa)[2], u32x4(&xb)[2]) {
+          const int pos = (frag_pos ^ (2 * kk)) << 4;
+          xa[0] = *(const u32x4 *)(la + pos), xa[1] = *(const u32x4 *)(la + 4096 + pos);
+          xb[0] = *(const u32x4 *)(lb + pos), xb[1] = *(const u32x4 *)(lb + 4096 + pos);
+        };
+        frag(0, fa[0], fb[0]);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          if (kk + 1 < 4) frag(kk + 1, fa[(kk + 1) & 1], fb[(kk + 1) & 1]);
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int fn = 0; fn < 2; ++fn)
+#pragma unroll
+            for (int fm = 0; fm < 2; ++fm)
+              acc[fn][fm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fb[kk & 1][fn]),
+                                                                    __builtin_bit_cast(bf16x8, fa[kk & 1][fm]), acc[fn][fm], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+    }
+    // one output per lane and accumulator block keeps the products alive (a measuring aid: C is not a full result)
+    uint16_t *C = Cout + (size_t)b * M * N;
+#pragma unroll
+    for (int fm = 0; fm < 2; ++fm)
+#pragma unroll
+      for (int fn = 0; fn < 2; ++fn)
+        C[(size_t)(m0 + (wm * 2 + fm) * 32 + l32) * N + n0 + (wn * 2 + fn) * 32 + 4 * half] =
+            (uint16_t)(__builtin_bit_cast(uint32_t, acc[fn][fm][0]) >> 16);
+    __syncthreads();
+  }
+}
+
 int cu_count() {
   int dev = 0, cus = 0;
   if (hipGetDevice(&dev) != hipSuccess) return 0;
@@ -193,6 +283,44 @@ int sk_ceiling_lds_read(int iters, void *sink, double *gb_per_s, double *bytes_p
   const double bytes = (double)grid.x * 256.0 * iters * 8.0 * 16.0;
   *gb_per_s = bytes / (ms * 1e-3) / 1e9;
   *bytes_per_clk_per_cu = bytes / cus / (ms * 1e-3) / ((double)khz * 1e3);
+  return 0;
+}
+
+// *tflops the stage loop of the LDS-tile class reaches by itself on sixteen 2048-cubed bf16 products (see
+// tile_loop; mode 0, 1 or 2; counted as if every mode did the products).  a, b: 16 * 2048 * 2048 bf16 each,
+// c: the same size, all device memory owned by the caller.
+int sk_ceiling_tile_loop(int mode, const void *a, const void *b, void *c, double *tflops) {
+  const int cus = cu_count();
+  if (!a || !b || !c || !tflops || cus <= 0 || mode < 0 || mode > 2) return (int)hipErrorInvalidValue;
+  const int M = 2048, N = 2048, K = 2048, nb = 16;
+  const dim3 grid(2 * cus), block(256);
+  const int rounds = (nb * (M / 128) * (N / 128) + (int)grid.x - 1) / (int)grid.x;
+  hipEvent_t e0, e1;
+  hipError_t e = hipEventCreate(&e0);
+  if (e != hipSuccess) return (int)e;
+  e = hipEventCreate(&e1);
+  if (e != hipSuccess) return (int)e;
+  auto launch = [&]() {
+    const uint16_t *pa = (const uint16_t *)a, *pb = (const uint16_t *)b;
+    uint16_t *pc = (uint16_t *)c;
+    if (mode == 0)
+      hipLaunchKernelGGL(tile_loop<0>, grid, block, 0, 0, pa, pb, pc, M, N, K, nb, rounds);
+    else if (mode == 1)
+      hipLaunchKernelGGL(tile_loop<1>, grid, block, 0, 0, pa, pb, pc, M, N, K, nb, rounds);
+    else
+      hipLaunchKernelGGL(tile_loop<2>, grid, block, 0, 0, pa, pb, pc, M, N, K, nb, rounds);
+  };
+  launch();
+  (void)hipEventRecord(e0, 0);
+  for (int i = 0; i < 5; ++i) launch();
+  (void)hipEventRecord(e1, 0);
+  e = hipEventSynchronize(e1);
+  float ms = 0.f;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (e != hipSuccess) return (int)e;
+  *tflops = 2.0 * nb * M * N * (double)K * 5 / (ms * 1e-3) / 1e12;
   return 0;
 }
 

@@ -15,9 +15,11 @@
 //     different 32-row weight groups; long reductions are split over several
 //     workgroups whose partial sums the last one to finish adds in fixed order.
 //   * LDS tiles (128x128, or 128x64 for operators with at most 64 output
-//     columns): classic staged GEMM, global -> registers -> LDS -> 32x32 MFMA;
-//     the activation operand may be gathered on the fly from an NHWC image
-//     (implicit GEMM for convolutions, any stride).
+//     columns): staged GEMM with 32x32 MFMAs; the operands go global -> LDS
+//     directly (buffer loads with the LDS modifier into a ring of swizzled
+//     stage images), through a ring of registers only where an operator is
+//     out of reach of 32-bit offsets; the activation operand may be gathered
+//     on the fly from an NHWC image (implicit GEMM for convolutions, any stride).
 //   * operands that cannot be read in aligned 16-byte pieces, and convolutions
 //     on channel-major (NCHW) arrays, whose patch rows and output rows are not
 //     contiguous: one output per thread for small rectangles, MFMA tiles
