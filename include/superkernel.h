@@ -122,15 +122,16 @@ typedef struct {
   int32_t host_only;      /* 1: plan on the host only, touch no device (launches then fail)  */
   int32_t skinny_max_m;   /* operators with at most this many rows stream their weights      */
                           /* straight to registers ("skinny" classes); 0..64, default 64     */
-  int64_t tile_bytes_max; /* skinny tiles: upper/lower clamp of the target weight bytes per  */
-  int64_t tile_bytes_min; /* tile (defaults 2 MiB, 32 KiB); the target is                    */
-                          /* sum(weight bytes) / balance_div                                 */
+  int64_t tile_bytes_max; /* upper/lower clamp of the target operand bytes per tile (defaults  */
+  int64_t tile_bytes_min; /* 2 MiB, 32 KiB); the target is sum(bytes the operators' tiles      */
+                          /* load) / balance_div: a streaming operator's weights, an LDS-tile  */
+                          /* operator's 128 + BN operand rows per output tile                  */
   int32_t balance_div;    /* default 512                                                     */
   int32_t max_groups;     /* cap on 32-row weight groups per skinny tile, default 256        */
   int32_t grid_limit;     /* upper bound on persistent workgroups per launch;                */
                           /* 0 = 2 per compute unit of the current device                    */
   int32_t tail_div;       /* tiles shrink towards the end of the table: an operator's target */
-                          /* is also capped by (weight bytes of it and of all operators      */
+                          /* is also capped by (such bytes of it and of all operators        */
                           /* after it in execution order) / tail_div, so that the launch     */
                           /* does not end on a few long tiles, but never below               */
                           /* 8 * tile_bytes_min; 0 = off, default 384                        */
