@@ -111,6 +111,32 @@ def test_ragged_shapes_all_paths():
     run_all_modes(RAGGED, seed=7, label="ragged")
 
 
+# The direct-load LDS tiles (operands of at least 65 rows that can be read in 16-byte pieces; convolutions with
+# whole stages of channels under every tap): reduction lengths with a tail in the last stage, one to many
+# stages, rows and columns that end inside a tile, every type (a stage is 64 halves or 32 floats), filters
+# from 1x1 to 5x5 and 1x7 (25 and 7 taps), padding on one side, strides 2 and 3, several images per tile,
+# the narrow class (at most 64 columns) with its three-stage ring and the wide one with two, single-stage
+# tiles, and one convolution with more than 31 taps, which keeps the register-ring path.
+DIRECT = [
+    g(65, 129, 64), g(200, 64, 72), g(130, 300, 520), g(129, 65, 8), g(256, 128, 4096), g(300, 40, 1096, "f16"),
+    g(131, 130, 32, "f32"), g(140, 70, 104, "f32"), g(128, 128, 136, "f32"),
+    c(12, 12, 64, 64, 3, 3, 1, 1), c(12, 12, 128, 130, 3, 3, 1, 1, nb=3), c(20, 9, 64, 40, 5, 5, 2, 2),
+    c(16, 16, 64, 200, 1, 7, 0, 3), c(17, 15, 64, 64, 3, 3, 1, 0, st=2), c(31, 31, 192, 96, 3, 3, 0, 0, "f16", st=3),
+    c(10, 10, 32, 48, 3, 3, 1, 1, "f32", nb=2), c(9, 9, 64, 8, 1, 1, 0, 0, nb=3), c(14, 14, 64, 64, 7, 7, 3, 3),
+]
+
+
+def test_direct_load_tiles():
+    run_all_modes(DIRECT, seed=31, label="direct-load tiles")
+    # small targets cut the long reductions into slices (hand-over through the workspace)
+    b = H.Batch([s for s in DIRECT if H.kg_of(s) >= 1024], seed=32)
+    with b.plan(tile_bytes_min=16384, tile_bytes_max=16384) as plan:
+        assert max(t["S"] for t in P.decode(sk.sk_plan_get_tiles(plan))) > 1
+        sk.sk_launch(plan, H.stream_handle())
+        _sync()
+        H.check_against_oracle(b, "direct-load tiles, split reductions")
+
+
 def nchw(h, w, cin, cout, r, s, ph, pw, dtype="bf16", nb=1, d=math.inf, st=1):
     return Problem(op="conv_nchw", dtype=dtype, Nb=nb, H=h, W=w, Cin=cin, Cout=cout, R=r, S=s, pad_h=ph, pad_w=pw,
                    stride=st, deadline_ms=d, a_dist=("uniform", 0.0, 1.0), b_dist=("normal", 0.1))
