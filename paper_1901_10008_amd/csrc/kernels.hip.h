@@ -779,12 +779,37 @@ __device__ __forceinline__ void run_skinny(const DevProblem &P, const sk_tile &T
       for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
         for (int mb = 0; mb < RM; ++mb) acc[rb][mb] = f32x4{0.f, 0.f, 0.f, 0.f};
-      for (int s2 = 0; s2 < T.S; ++s2) {
+      // All partial sums of a slice are requested before the first is added, and those of the next AHEAD - 1
+      // slices while this one's are added (left to the scheduler the loads went out two at a time, each pair
+      // waited for: eight memory round trips per slice, which made an operator cut into dozens of slices
+      // several times slower).  The sums are still taken in slice order.
+      constexpr int AHEAD = 2;  // slices in flight (four or eight for the classes with fewer rows: measured, no gain)
+      f32x4 part[AHEAD][2][RM];
+      auto request = [&](int s2, f32x4(&dst)[2][RM]) {
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
           for (int mb = 0; mb < RM; ++mb)
-            acc[rb][mb] += load_device_scope(mine + (size_t)s2 * (4 * 2 * RM * 64) + slot + (rb * RM + mb) * 64, lane);
+            dst[rb][mb] = load_device_scope(mine + (size_t)s2 * (4 * 2 * RM * 64) + slot + (rb * RM + mb) * 64, lane);
+      };
+      const int S = (int)T.S;
+#pragma unroll
+      for (int u = 0; u < AHEAD - 1; ++u)
+        if (u < S) request(u, part[u]);
+      for (int s0 = 0; s0 < S; s0 += AHEAD) {
+#pragma unroll
+        for (int u = 0; u < AHEAD; ++u) {
+          const int s2 = s0 + u;
+          if (s2 + AHEAD - 1 < S) request(s2 + AHEAD - 1, part[(u + AHEAD - 1) % AHEAD]);
+          __builtin_amdgcn_sched_barrier(0);
+          if (s2 < S) {
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+              for (int mb = 0; mb < RM; ++mb) acc[rb][mb] += part[u][rb][mb];
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
       if (tid == 0)  // re-arm for the next launch
         __hip_atomic_store(&sp.arrive[T.out_tile_id], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -829,17 +854,26 @@ __device__ __forceinline__ bool split_handover(const sk_tile &T, const SplitK &s
       for (int fm = 0; fm < FM; ++fm)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[fn][fm][i] = 0.f;
+    // (all partial sums of a slice are requested before the first is added: see run_skinny)
     for (int s2 = 0; s2 < T.S; ++s2) {
+      f32x4 part[FN][FM][4];
 #pragma unroll
       for (int fn = 0; fn < FN; ++fn)
 #pragma unroll
         for (int fm = 0; fm < FM; ++fm)
 #pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const f32x4 v = load_device_scope(mine + (size_t)s2 * PER_SLICE + ((fn * FM + fm) * 4 + j) * 64, lane);
+          for (int j = 0; j < 4; ++j)
+            part[fn][fm][j] = load_device_scope(mine + (size_t)s2 * PER_SLICE + ((fn * FM + fm) * 4 + j) * 64, lane);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) acc[fn][fm][4 * j + e] += v[e];
-          }
+      for (int fn = 0; fn < FN; ++fn)
+#pragma unroll
+        for (int fm = 0; fm < FM; ++fm)
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[fn][fm][4 * j + e] += part[fn][fm][j][e];
+      __builtin_amdgcn_sched_barrier(0);
     }
     if (tid == 0)  // re-arm for the next launch
       __hip_atomic_store(&sp.arrive[T.out_tile_id], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
