@@ -135,6 +135,15 @@ typedef struct {
                           /* after it in execution order) / tail_div, so that the launch     */
                           /* does not end on a few long tiles, but never below               */
                           /* 8 * tile_bytes_min; 0 = off, default 384                        */
+  int32_t xcd_part;       /* LDS tiles that share operands go to the same accelerator die    */
+                          /* (XCD: 32 compute units behind one L2): an operator's output     */
+                          /* rectangles are cut into the fewest 1, 2, 4 or 8 two-dimensional */
+                          /* parts of at most this many rectangles, one die per part         */
+                          /* (sk_plan_get_xcd_lists); 0 = tiles are taken in table order by  */
+                          /* whichever workgroup is free.  Default 0: the lists halve the    */
+                          /* memory traffic of compute-heavy plans and gain a few percent    */
+                          /* there (32 is the value measured), and cost mixed plans time     */
+  int32_t reserved;       /* 0                                                               */
 } sk_plan_params;
 
 /*
@@ -253,6 +262,11 @@ sk_status sk_plan_get_order(const sk_plan *plan, int32_t *order);
 sk_status sk_plan_get_ranges(const sk_plan *plan, int64_t *first_tile, int64_t *tile_count);
 /* Persistent workgroups sk_launch uses for this plan (0 for an empty or host-only plan). */
 int32_t sk_plan_grid(const sk_plan *plan);
+/* Which die takes which LDS tile (sk_plan_params.xcd_part; Section 1 item (c): the shape of the execution
+ * blocks is the runtime's to choose): offsets[9] and, if `tiles` is not null, at most `cap` table indices:
+ * tiles[offsets[x] .. offsets[x+1]) are the records die x takes, in order.  offsets[8] is the number of
+ * LDS tiles of the plan, 0 with xcd_part = 0.  Host memory, caller-owned. */
+sk_status sk_plan_get_xcd_lists(const sk_plan *plan, uint32_t *offsets, uint32_t *tiles, int64_t cap);
 
 /*
  * Per-operator latency of the LAST completed launch of this plan (Section 5.2:

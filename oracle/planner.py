@@ -14,7 +14,10 @@ behind the C ABI can be compared with it byte for byte:
   3. operator order: earliest deadline first, ties (and "no deadline") by
      submission index;
   4. the flat table: operators in that order, row blocks outer, column blocks
-     inner, reduction slices innermost; one fixed-size record per tile.
+     inner, reduction slices innermost; one fixed-size record per tile;
+  5. optionally (Section 1, item (c): the shape of the execution blocks is the
+     runtime's choice) which of the GPU's eight dies runs which LDS tile
+     (`die_lists`): tiles that share operand rows meet behind one L2.
 
 It shares no code with the product's planner.
 
@@ -165,6 +168,61 @@ def plan(problems: Sequence, prm: Params | None = None):
                 out_id += 1
         count[i] = len(recs) - first[i]
     return b"".join(recs), ordr, first, count
+
+
+def _z_order_8x8():
+    """(row offset, column offset) of the 64 cells of an 8 x 8 block along a Z-order curve that
+    starts with a step along the columns."""
+    cells = []
+    for code in range(64):
+        dn = sum(((code >> (2 * b)) & 1) << b for b in range(3))
+        dm = sum(((code >> (2 * b + 1)) & 1) << b for b in range(3))
+        cells.append((dm, dn))
+    return cells
+
+
+def die_lists(problems: Sequence, table: bytes, ordr: Sequence[int], first: Sequence[int], part: int):
+    """Eight lists of table indices: the LDS tiles of the table, die by die, in the order a die takes them.
+
+    Operators in execution order.  The MB x NB output rectangles of an LDS-tile operator are cut into
+    p = 1, 2, 4 or 8 parts (the fewest with at most `part` rectangles each), as a pm x pn grid with
+    pm * pn = p, pm <= MB, pn <= NB that fetches the fewest operand rows in all (every row block is read by pn
+    dies, every column block by pm: pn * MB * 128 + pm * NB * BN; ties go to fewer parts along the columns);
+    part (a, b) covers row blocks [a MB / pm, (a+1) MB / pm) and column blocks [b NB / pn, (b+1) NB / pn).
+    Parts go, a outer and b inner, to the die with the shortest list so far that this operator has not used yet
+    (lowest index on ties).  Inside a part: blocks of 8 x 8 rectangles row by row, a Z-order curve inside
+    each block, the reduction slices of a rectangle together."""
+    lists = [[] for _ in range(8)]
+    if part <= 0:
+        return lists
+    tiles = decode(table)
+    zcells = _z_order_8x8()
+    for i in ordr:
+        t0 = tiles[first[i]]
+        if t0["cls"] not in (CLS_TILE_128x128, CLS_TILE_128x64):
+            continue
+        mg, ng, _ = canonical(problems[i])
+        bn = 64 if t0["cls"] == CLS_TILE_128x64 else 128
+        MB, NB, S = -(-mg // 128), -(-ng // bn), t0["S"]
+        p = 1
+        while p < 8 and MB * NB > p * part:
+            p *= 2
+        grids = [(p // cn, cn) for cn in (1, 2, 4, 8) if cn <= p and p // cn <= MB and cn <= NB]
+        pm, pn = min(grids, key=lambda g: (g[1] * MB * 128 + g[0] * NB * bn, g[1])) if grids else (min(p, MB), 1)
+        used = set()
+        for a in range(pm):
+            for b in range(pn):
+                die = min((x for x in range(8) if x not in used), key=lambda x: (len(lists[x]), x))
+                used.add(die)
+                m_lo, m_hi = a * MB // pm, (a + 1) * MB // pm
+                n_lo, n_hi = b * NB // pn, (b + 1) * NB // pn
+                for bm in range(m_lo, m_hi, 8):
+                    for bc in range(n_lo, n_hi, 8):
+                        for dm, dn in zcells:
+                            if bm + dm < m_hi and bc + dn < n_hi:
+                                rect = (bm + dm) * NB + (bc + dn)
+                                lists[die].extend(first[i] + rect * S + ks for ks in range(S))
+    return lists
 
 
 def decode(table: bytes):

@@ -23,6 +23,7 @@ from .binding import (  # noqa: F401
     sk_plan_get_tiles,
     sk_plan_get_order,
     sk_plan_get_ranges,
+    sk_plan_get_xcd_lists,
     sk_plan_get_stamps,
     sk_plan_grid,
     sk_plan_params_default,

@@ -18,7 +18,7 @@ EXPORTED_SYMBOLS = [
     "sk_plan_params_default", "sk_plan_create", "sk_plan_destroy", "sk_launch", "sk_launch_sequential",
     "sk_launch_static",
     "sk_plan_num_tiles", "sk_plan_num_problems", "sk_plan_get_tiles", "sk_plan_get_order",
-    "sk_plan_get_ranges", "sk_plan_grid", "sk_plan_get_stamps", "sk_release_cached_memory", "sk_strerror", "sk_last_error",
+    "sk_plan_get_ranges", "sk_plan_grid", "sk_plan_get_xcd_lists", "sk_plan_get_stamps", "sk_release_cached_memory", "sk_strerror", "sk_last_error",
     "sk_queue_params_default", "sk_queue_create", "sk_queue_submit", "sk_queue_poll", "sk_queue_get_stats", "sk_queue_destroy",
 ]
 SK_QUEUE_SEQUENTIAL, SK_QUEUE_COALESCE, SK_QUEUE_OOO = 0, 1, 2
@@ -50,7 +50,7 @@ class PlanParams(C.Structure):
         ("edf", C.c_int32), ("stamps", C.c_int32), ("host_only", C.c_int32), ("skinny_max_m", C.c_int32),
         ("tile_bytes_max", C.c_int64), ("tile_bytes_min", C.c_int64),
         ("balance_div", C.c_int32), ("max_groups", C.c_int32), ("grid_limit", C.c_int32),
-        ("tail_div", C.c_int32),
+        ("tail_div", C.c_int32), ("xcd_part", C.c_int32), ("reserved", C.c_int32),
     ]
 
 
@@ -109,6 +109,8 @@ def lib():
     L.sk_plan_get_tiles.argtypes = [vp, vp, C.c_int64]
     L.sk_plan_get_order.restype = C.c_int
     L.sk_plan_get_order.argtypes = [vp, C.POINTER(C.c_int32)]
+    L.sk_plan_get_xcd_lists.restype = C.c_int
+    L.sk_plan_get_xcd_lists.argtypes = [vp, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32), C.c_int64]
     L.sk_plan_get_ranges.restype = C.c_int
     L.sk_plan_get_ranges.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
     L.sk_plan_get_stamps.restype = C.c_int
@@ -268,6 +270,16 @@ def sk_plan_get_ranges(plan: Plan):
     b = (C.c_int64 * max(n, 1))()
     _check(lib().sk_plan_get_ranges(plan.handle, a, b))
     return list(a[:n]), list(b[:n])
+
+
+def sk_plan_get_xcd_lists(plan: Plan) -> List[List[int]]:
+    """The eight per-die lists of LDS tiles (table indices, in the order the die takes them)."""
+    off = (C.c_uint32 * 9)()
+    _check(lib().sk_plan_get_xcd_lists(plan.handle, off, None, 0))
+    n = int(off[8])
+    arr = (C.c_uint32 * max(n, 1))()
+    _check(lib().sk_plan_get_xcd_lists(plan.handle, off, arr, n))
+    return [list(arr[off[x]:off[x + 1]]) for x in range(8)]
 
 
 def sk_plan_get_stamps(plan: Plan):

@@ -106,7 +106,9 @@ __global__ void __launch_bounds__(256, 2) lds_read_loop(int iters, f32x4 *sink) 
 // matrix cores allow).  2: operand loads and barrier only (what the path from the L2s to LDS allows).
 __device__ __forceinline__ void tile_dma16(const void *gptr, uint32_t lds_addr) {
   // lane i's 16 bytes land at lds_addr + 16 i
-  asm volatile("global_load_lds_dwordx4 %0, off" ::"v"(gptr), "{m0}"(lds_addr) : "memory");
+  // (one idle cycle between the write of M0 and the load that reads it: the compiler does not
+  // add wait states in front of inline assembly)
+  asm volatile("s_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "{m0}"(lds_addr) : "memory");
 }
 template <int MODE>
 __global__ void __launch_bounds__(256, 2) tile_loop(const uint16_t *A, const uint16_t *B, uint16_t *Cout, int M, int N, int K,

@@ -86,8 +86,15 @@ constexpr int WG_THREADS = 256;
 constexpr int LDS_ROW = 144;                  // 128 bytes of K + 16 bytes of padding (bank spread)
 constexpr int LDS_TILE_BYTES = 512 * LDS_ROW;  // 72 KB per workgroup: two workgroups share a CU's 160 KB
 
+// Queue counters of a table: [0] tiles handed out beyond the first grid-full, [1] finished workgroups,
+// [16 * (1 + x)] entries handed out from die x's list of LDS tiles (a 64-byte line each).
+constexpr int QUEUE_COUNTERS = 16 * 9 + 1;
+__device__ __forceinline__ uint32_t *die_list_head(uint32_t *counters, uint32_t x) { return counters + 16u * (1u + x); }
+
 struct KernelArgs {
-  uint32_t *counters;   // [0] tiles handed out beyond the first grid-full, [1] finished workgroups
+  uint32_t *counters;   // see QUEUE_COUNTERS
+  const TileWork *xwork;  // the LDS tiles' records, die by die (null: tiles are run where their ticket falls)
+  const uint32_t *xoff;   // [9] where die x's list starts in xwork
   uint32_t *remaining;  // per operator: tiles not yet retired (null = no stamps)
   uint64_t *stamps;     // [n] completion ticks, [n] = start tick
   uint32_t n_problems;
@@ -471,19 +478,35 @@ struct Prefetch {
   uint32_t last;      // last valid index of the launch
   int tid;            // this tile's copy of the thread index (see the tile loop)
   uint32_t word = 0;
+  // An LDS tile is run by the die whose list holds it (see the tile loop).  While such a tile runs, the
+  // workgroup also draws the next entry of its die's list (xhead not null), on the guess that its next
+  // ticket falls on an LDS tile again: thread 1 draws beside thread 0 in the same atomic instruction, and
+  // the one load of issue() brings the record of that entry (lanes below WORK_DWORDS) and, in lane 63, the
+  // dword of the ticket's own record that holds its tile class.  (One atomic and one load as without
+  // lists: with two of either in flight the compiler waits, in every step of the LDS-tile loops, until
+  // one load at most is outstanding, which also counts the operand loads it does not see.)
+  uint32_t *xhead = nullptr;
+  const TileWork *xrec = nullptr;  // first record of the die's list
+  uint32_t xlen = 0;               // its length (> 0 whenever xhead is set)
 #ifdef SK_DIAG_CLOCKS
   int diag_tile = 0;
 #endif
   __device__ __forceinline__ void claim() {
-    // (lanes other than thread 0 keep whatever `next` held: it is never used, and any
+    // (lanes other than threads 0 and 1 keep whatever `next` held: it is never used, and any
     // instruction that touched the register here would have to wait for an earlier answer)
-    if (counter && tid == 0) next = atomicAdd(counter, 1u);
+    if (counter && tid < (xhead ? 2 : 1)) next = atomicAdd(tid == 0 ? counter : xhead, 1u);
   }
   __device__ __forceinline__ void issue() {
     uint32_t idx = (uint32_t)__builtin_amdgcn_readfirstlane((int)next) + base;
     if (idx > last) idx = last;  // past the end of the table: the workgroup is about to leave
     const int lane = tid & 63;
-    word = as_global<uint32_t>(work + idx)[lane < WORK_DWORDS ? lane : 0];
+    const uint32_t SK_GLOBAL *src = as_global<uint32_t>(work + idx) + (lane < WORK_DWORDS ? lane : 0);
+    if (xhead) {
+      uint32_t k = (uint32_t)__builtin_amdgcn_readlane((int)next, 1);
+      if (k >= xlen) k = xlen - 1u;  // the list is used up
+      src = lane == 63 ? as_global<uint32_t>(work + idx) + 1 : as_global<uint32_t>(xrec + k) + (lane < WORK_DWORDS ? lane : 0);
+    }
+    word = *src;
   }
   // step `i` of `total` main-loop steps
   __device__ __forceinline__ void at_step(int i, int total, int lead, int gap) {
@@ -1391,8 +1414,49 @@ __device__ __forceinline__ void run_tile_lean(const DevProblem &P, const sk_tile
 //     hence "at most n outstanding" with n the loads of the stages issued later.  Loads and
 //     stores of the surrounding code that are also in flight only make these waits, and the
 //     compiler's own, wait for more than they need.
-__device__ __forceinline__ void dma_piece(__amdgpu_buffer_rsrc_t desc, uint32_t voff, uint32_t soff, uint32_t lds_addr) {
-  asm volatile("buffer_load_dwordx4 %0, %1, %2 offen lds" ::"v"(voff), "s"(desc), "s"(soff), "{m0}"(lds_addr) : "memory");
+//   * the compiler does not look into inline assembly for the wait states the hardware wants between
+//     instructions either.  Two matter here: a scalar register written by a vector instruction (the
+//     compiler keeps spilled scalars in lanes of a vector register and fetches them with v_readlane
+//     wherever it needs them, also right in front of these loads) must not be read by a memory
+//     instruction in the next five cycles, and M0 not by an LDS-writing load in the cycle after it
+//     was written.  So all loads of a stage sit in ONE statement that opens with the five cycles
+//     and moves M0 from piece to piece itself (the pieces of a wave lie 4 KB apart), and hands M0 back
+//     as it got it.
+template <int NA, int NBW>
+__device__ __forceinline__ void dma_stage(__amdgpu_buffer_rsrc_t descA, __amdgpu_buffer_rsrc_t descB, const uint32_t (&va)[NA],
+                                          const uint32_t (&vb)[NBW], uint32_t soffA, uint32_t soffB, uint32_t lds_addr) {
+  static_assert(NA == 4 && (NBW == 4 || NBW == 2), "written out for 128 rows of activations and 128 or 64 of weights");
+#define SK_DMA_NEXT "s_add_u32 m0, m0, 0x1000\n\ts_nop 0\n\t"
+  if constexpr (NBW == 4) {
+    asm volatile("s_nop 4\n\t"
+                 "buffer_load_dwordx4 %0, %8, %10 offen lds\n\t" SK_DMA_NEXT
+                 "buffer_load_dwordx4 %1, %8, %10 offen lds\n\t" SK_DMA_NEXT
+                 "buffer_load_dwordx4 %2, %8, %10 offen lds\n\t" SK_DMA_NEXT
+                 "buffer_load_dwordx4 %3, %8, %10 offen lds\n\t" SK_DMA_NEXT
+                 "buffer_load_dwordx4 %4, %9, %11 offen lds\n\t" SK_DMA_NEXT
+                 "buffer_load_dwordx4 %5, %9, %11 offen lds\n\t" SK_DMA_NEXT
+                 "buffer_load_dwordx4 %6, %9, %11 offen lds\n\t" SK_DMA_NEXT
+                 "buffer_load_dwordx4 %7, %9, %11 offen lds\n\t"
+                 "s_sub_u32 m0, m0, 0x7000"
+                 :
+                 : "v"(va[0]), "v"(va[1]), "v"(va[2]), "v"(va[3]), "v"(vb[0]), "v"(vb[1]), "v"(vb[2]), "v"(vb[3]), "s"(descA),
+                   "s"(descB), "s"(soffA), "s"(soffB), "{m0}"(lds_addr)
+                 : "memory", "scc");
+  } else {
+    asm volatile("s_nop 4\n\t"
+                 "buffer_load_dwordx4 %0, %6, %8 offen lds\n\t" SK_DMA_NEXT
+                 "buffer_load_dwordx4 %1, %6, %8 offen lds\n\t" SK_DMA_NEXT
+                 "buffer_load_dwordx4 %2, %6, %8 offen lds\n\t" SK_DMA_NEXT
+                 "buffer_load_dwordx4 %3, %6, %8 offen lds\n\t" SK_DMA_NEXT
+                 "buffer_load_dwordx4 %4, %7, %9 offen lds\n\t" SK_DMA_NEXT
+                 "buffer_load_dwordx4 %5, %7, %9 offen lds\n\t"
+                 "s_sub_u32 m0, m0, 0x5000"
+                 :
+                 : "v"(va[0]), "v"(va[1]), "v"(va[2]), "v"(va[3]), "v"(vb[0]), "v"(vb[1]), "s"(descA), "s"(descB), "s"(soffA),
+                   "s"(soffB), "{m0}"(lds_addr)
+                 : "memory", "scc");
+  }
+#undef SK_DMA_NEXT
 }
 template <int N>
 __device__ __forceinline__ void wait_loads_but() {
@@ -1412,6 +1476,7 @@ __device__ __forceinline__ void run_tile_dma(const DevProblem &P, const sk_tile 
   constexpr int NS = LDS_TILE_BYTES / SLOT;   // ring slots
   constexpr uint32_t NOWHERE = 0x80000000u;   // an offset outside every descriptor: the piece arrives as zeros
   static_assert(NS == 2 || NS == 3, "waits below are written for two or three slots");
+  static_assert(BM == 128, "a wave's pieces of a stage lie 4 KB apart, activations first (dma_stage)");
   static_assert(NPW < 32, "load counter");
 
   const int tid = pf.tid;
@@ -1483,14 +1548,16 @@ __device__ __forceinline__ void run_tile_dma(const DevProblem &P, const sk_tile 
   auto issue = [&](int slot) {
     const uint32_t kbytes = (uint32_t)k_next * ES;
     const uint32_t dst = my_blocks + (uint32_t)slot * SLOT;
+    uint32_t va[NA], vb[NBW];
     if constexpr (GATHER) {
       // (no reduction tail: the reduction length is a multiple of the channel count, that of a stage)
       const uint32_t tapbit = 1u << ((t_r * P.S + t_s) & 31);
       const uint32_t tapoff = (uint32_t)(((t_r * P.W + t_s) * P.Cin + t_c) * ES);
 #pragma unroll
-      for (int i = 0; i < NA; ++i) dma_piece(descA, (tapsA[i] & tapbit) ? offA[i] : NOWHERE, tapoff, dst + 4096u * i);
+      for (int i = 0; i < NA; ++i) va[i] = (tapsA[i] & tapbit) ? offA[i] : NOWHERE;
 #pragma unroll
-      for (int i = 0; i < NBW; ++i) dma_piece(descB, offB[i], kbytes, dst + BM * 128u + 4096u * i);
+      for (int i = 0; i < NBW; ++i) vb[i] = offB[i];
+      dma_stage<NA, NBW>(descA, descB, va, vb, tapoff, kbytes, dst);
       t_c += KB;
       if (t_c >= P.Cin) {
         t_c = 0;
@@ -1504,9 +1571,10 @@ __device__ __forceinline__ void run_tile_dma(const DevProblem &P, const sk_tile 
       // multiple of a stage): nowhere
       const uint32_t tail = k_next + c_log * CE < k_stop ? 0u : NOWHERE;
 #pragma unroll
-      for (int i = 0; i < NA; ++i) dma_piece(descA, offA[i] | tail, kbytes, dst + 4096u * i);
+      for (int i = 0; i < NA; ++i) va[i] = offA[i] | tail;
 #pragma unroll
-      for (int i = 0; i < NBW; ++i) dma_piece(descB, offB[i] | tail, kbytes, dst + BM * 128u + 4096u * i);
+      for (int i = 0; i < NBW; ++i) vb[i] = offB[i] | tail;
+      dma_stage<NA, NBW>(descA, descB, va, vb, kbytes, kbytes, dst);
     }
     k_next += KB;
   };
@@ -1964,24 +2032,171 @@ __global__ void sk_arm_start_stamp(uint64_t *slot) { *slot = ~0ull; }
 template <int ONLY_DT, bool ANY_ALIGNMENT>
 __global__ void __launch_bounds__(WG_THREADS, 2) sk_superkernel(const TileWork *__restrict__ work, KernelArgs a) {
   __shared__ __attribute__((aligned(16))) unsigned char lds[LDS_TILE_BYTES];
-  __shared__ __attribute__((aligned(16))) uint32_t s_mail[2][WORK_DWORDS + 4];  // next record + its index, by parity
+  // next record by parity; behind it [0] its ticket, [1] flags (MAIL_*), [2] its index in xwork
+  __shared__ __attribute__((aligned(16))) uint32_t s_mail[2][WORK_DWORDS + 4];
+  // a record of the die's list that was drawn in advance and has not run yet; behind it its index in xwork
+  __shared__ __attribute__((aligned(16))) uint32_t s_kept[WORK_DWORDS + 4];
   __shared__ uint32_t s_flag;
   const SplitK sp{a.ws, a.ws_off, a.arrive};
+  enum : uint32_t { MAIL_RUN = 1, MAIL_FROM_LIST = 2, MAIL_KEPT = 4 };
 
   // Start of the launch = the earliest first clock of any workgroup (the host has set the slot to all ones).
   if (a.write_start && a.stamps && threadIdx.x == 0)
     __hip_atomic_fetch_min((unsigned long long *)&a.stamps[a.n_problems], (unsigned long long)wall_clock64(),
                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
-  // The first tile of every workgroup is fixed (its block index); further tiles come from the
-  // queue.  (The host never launches more workgroups than tiles.)
-  uint32_t t = a.tile_begin + blockIdx.x;
-  TileWork W = load_uniform(work + (t < a.tile_end ? t : a.tile_end - 1u));
+  // Tickets and lists.  The queue hands out positions of the table in order ("tickets"); the first ticket of
+  // a workgroup is its block index.  A ticket that falls on a skinny tile is that tile.  A ticket that
+  // falls on an LDS tile only says that one LDS tile is due: which one, the workgroup takes from the list
+  // of its die (the host has sorted every LDS tile of the table into one of eight lists so that tiles
+  // sharing operand panels meet behind one L2; workgroups go to the dies round robin by block index), and
+  // from the other dies' lists once its own is used up.  While an LDS tile runs, the next entry of the
+  // list is drawn together with the next ticket (Prefetch), on the guess that the ticket falls on an LDS
+  // tile again; if it does not, the entry is kept for the workgroup's next such ticket, and run at the
+  // latest when the tickets are used up.  Such an entry ran without a ticket, so at the very end of the
+  // launch some tickets find every list empty and stand for nothing.  Every entry is drawn exactly once and
+  // run by the workgroup that drew it, so every tile of the table runs exactly once.
+  const uint32_t last = a.tile_end - 1u;
+  const bool lists = a.xoff != nullptr;
+  const uint32_t die = blockIdx.x & 7u;
+  uint32_t xbeg = 0, xlen = 0;
+  if (lists) {
+    xbeg = a.xoff[die];
+    xlen = a.xoff[die + 1] - xbeg;
+  }
+  uint32_t used_up = xlen == 0 ? 1u << die : 0u;  // lists seen empty (wave 0's copy is the one that counts)
+  bool kept = false;                               // s_kept holds a record
+
+  const int wave0 = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) == 0;
+  const int lane0 = (int)(threadIdx.x & 63u);
+  const int wlane = lane0 < WORK_DWORDS ? lane0 : 0;
+  // What the tile just run fetched for the next one (Prefetch): lane 0 of `got` holds the ticket (less
+  // `got_base`), lane 1 the entry drawn from the die's list if `drew`; `got_word` the record of the ticket,
+  // or, if `drew`, the record of that entry with the ticket's tile class in lane 63.
+  uint32_t got = blockIdx.x, got_base = a.tile_begin;
+  uint32_t got_word = 0;
+  if (wave0) got_word = as_global<uint32_t>(work + (a.tile_begin + blockIdx.x <= last ? a.tile_begin + blockIdx.x : last))[wlane];
+  bool drew = false;
+  bool have_done = false;  // a tile has just been run: its operator and that operator's tile count
+  uint32_t done_problem = 0, done_count = 0;
   int par = 0;
 #ifdef SK_DIAG_CLOCKS
   int diag_tile = 0;
 #endif
-  while (t < a.tile_end) {
+  for (;;) {
+    if (wave0) {
+      // wave 0 decides what runs next and hands the record to the other waves
+      uint32_t idx = (uint32_t)__builtin_amdgcn_readfirstlane((int)got) + got_base;
+      uint32_t word = got_word, flags = 0, xi = 0;
+      if (!lists) {
+        flags = idx <= last ? MAIL_RUN : 0u;
+      } else {
+        const uint32_t k = drew ? (uint32_t)__builtin_amdgcn_readlane((int)got, 1) : 0u;
+        bool drawn = drew && k < xlen;  // `word` is the record of entry k of the die's list
+        if (drew && !drawn) used_up |= 1u << die;
+        bool have_record = !drew;       // `word` is the table's record at the ticket
+        for (;;) {
+          const bool ticket = idx <= last;
+          // the ticket's tile class: sk_tile's dword 1, low half
+          const uint32_t cls = (uint32_t)__builtin_amdgcn_readlane((int)word, have_record ? 1 : 63) & 0xffffu;
+          if (ticket && cls >= CLS_TILE_128x128) {
+            if (kept) {
+              word = s_kept[wlane];
+              xi = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_kept[WORK_DWORDS]);
+              kept = false;
+              flags = MAIL_RUN | MAIL_FROM_LIST;
+              break;
+            }
+            if (drawn) {
+              xi = xbeg + k;
+              flags = MAIL_RUN | MAIL_FROM_LIST;
+              break;
+            }
+            // nothing in hand: draw now, from the own list first
+            bool found = false;
+            for (uint32_t d = 0; d < 8u && !found; ++d) {
+              const uint32_t x2 = (die + d) & 7u;
+              if ((used_up >> x2) & 1u) continue;
+              const uint32_t b2 = a.xoff[x2], l2 = a.xoff[x2 + 1] - b2;
+              uint32_t k2 = l2;
+              if (l2 != 0 && lane0 == 0) k2 = atomicAdd(die_list_head(a.counters, x2), 1u);
+              k2 = (uint32_t)__builtin_amdgcn_readfirstlane((int)k2);
+              if (k2 < l2) {
+                xi = b2 + k2;
+                found = true;
+              } else {
+                used_up |= 1u << x2;
+              }
+            }
+            if (found) {
+              word = as_global<uint32_t>(a.xwork + xi)[wlane];
+              flags = MAIL_RUN | MAIL_FROM_LIST;
+              break;
+            }
+            // every list is empty: the tile this ticket stood for has run already; take the next ticket
+            uint32_t n2 = 0;
+            if (lane0 == 0) n2 = atomicAdd(&a.counters[0], 1u);
+            idx = (uint32_t)__builtin_amdgcn_readfirstlane((int)n2) + a.tile_begin + gridDim.x;
+            word = as_global<uint32_t>(work + (idx <= last ? idx : last))[wlane];
+            have_record = true;
+            continue;
+          }
+          if (ticket) {  // a skinny tile: the ticket is the tile
+            flags = MAIL_RUN;
+            if (drawn) {  // the entry drawn in advance waits for the next ticket that falls on an LDS tile
+              if (lane0 < WORK_DWORDS) s_kept[lane0] = word;
+              if (lane0 == 0) s_kept[WORK_DWORDS] = xbeg + k;
+              kept = true;
+            }
+            if (!have_record) word = as_global<uint32_t>(work + idx)[wlane];
+            break;
+          }
+          // the tickets are used up: run what is still in hand
+          idx = last;
+          if (kept) {
+            word = s_kept[wlane];
+            xi = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_kept[WORK_DWORDS]);
+            kept = false;
+            flags = MAIL_RUN | MAIL_FROM_LIST;
+          } else if (drawn) {
+            xi = xbeg + k;
+            flags = MAIL_RUN | MAIL_FROM_LIST;
+          }
+          break;
+        }
+        if (kept) flags |= MAIL_KEPT;
+      }
+      if (lane0 < WORK_DWORDS) s_mail[par][lane0] = word;
+      if (lane0 == 0) {
+        s_mail[par][WORK_DWORDS] = idx;
+        s_mail[par][WORK_DWORDS + 1] = flags;
+        s_mail[par][WORK_DWORDS + 2] = xi;
+      }
+    }
+    __syncthreads();
+    if (a.remaining && have_done && threadIdx.x == 0) {
+      // the workgroup that retires an operator's last tile stamps it and re-arms the count
+      const uint32_t left = atomicSub(&a.remaining[done_problem], 1u);
+      if (left == 1u) {
+        a.stamps[done_problem] = wall_clock64();
+        a.remaining[done_problem] = done_count;
+      }
+    }
+    const uint32_t flags = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_mail[par][WORK_DWORDS + 1]);
+#ifdef SK_DIAG_CLOCKS
+    if (have_done) {
+      SK_DIAG(5);
+      ++diag_tile;
+    }
+#endif
+    if (!(flags & MAIL_RUN)) break;
+    const uint32_t t = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_mail[par][WORK_DWORDS]);
+    const TileWork W = unpack_uniform<TileWork>(s_mail[par]);
+    const TileWork *cur =
+        (flags & MAIL_FROM_LIST) ? a.xwork + (uint32_t)__builtin_amdgcn_readfirstlane((int)s_mail[par][WORK_DWORDS + 2]) : work + t;
+    kept = (flags & MAIL_KEPT) != 0;
+    par ^= 1;
+
     // Everything a tile derives from the thread index is derived again for each tile, from a
     // copy the compiler cannot see through: hoisted out of this loop those values would stay
     // live across all tile classes, spill, and every reload of a spilled register waits for all
@@ -1989,49 +2204,40 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sk_superkernel(const TileWork *
     int tid = threadIdx.x;
     asm volatile("" : "+v"(tid));
     Prefetch pf{work, a.dynamic ? &a.counters[0] : nullptr, a.dynamic ? a.tile_begin + gridDim.x : 0u, t + gridDim.x,
-                a.tile_end - 1u, tid};
+                last, tid};
+    const sk_tile &T = W.tile;
+    drew = lists && T.cls >= CLS_TILE_128x128 && !kept && !((used_up >> die) & 1u);
+    if (drew) {
+      pf.xhead = die_list_head(a.counters, die);
+      pf.xrec = a.xwork + xbeg;
+      pf.xlen = xlen;
+    }
 #ifdef SK_DIAG_CLOCKS
     pf.diag_tile = diag_tile;
 #endif
     SK_DIAG(0);
-    const sk_tile &T = W.tile;
 #ifdef SK_DIAG_CLOCKS
     if (blockIdx.x < SK_DIAG_WGS && diag_tile < SK_DIAG_TILES && threadIdx.x == 0)
       g_diag[(blockIdx.x * SK_DIAG_TILES + diag_tile) * 8 + 6] = 1 + T.cls + 100ull * T.S;
 #endif
     const DevProblem &P = W.prob;
     if constexpr (ONLY_DT >= 0) {
-      run_class<ONLY_DT, ANY_ALIGNMENT>(P, T, &work[t].prob, &work[t].tile, sp, lds, &s_flag, pf);
+      run_class<ONLY_DT, ANY_ALIGNMENT>(P, T, &cur->prob, &cur->tile, sp, lds, &s_flag, pf);
     } else {
       switch (P.dtype) {
-        case SK_BF16: run_class<SK_BF16, ANY_ALIGNMENT>(P, T, &work[t].prob, &work[t].tile, sp, lds, &s_flag, pf); break;
-        case SK_F16: run_class<SK_F16, ANY_ALIGNMENT>(P, T, &work[t].prob, &work[t].tile, sp, lds, &s_flag, pf); break;
-        default: run_class<SK_F32, ANY_ALIGNMENT>(P, T, &work[t].prob, &work[t].tile, sp, lds, &s_flag, pf); break;
+        case SK_BF16: run_class<SK_BF16, ANY_ALIGNMENT>(P, T, &cur->prob, &cur->tile, sp, lds, &s_flag, pf); break;
+        case SK_F16: run_class<SK_F16, ANY_ALIGNMENT>(P, T, &cur->prob, &cur->tile, sp, lds, &s_flag, pf); break;
+        default: run_class<SK_F32, ANY_ALIGNMENT>(P, T, &cur->prob, &cur->tile, sp, lds, &s_flag, pf); break;
       }
     }
 
     if (a.remaining) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    if (tid < 64) {
-      // wave 0 hands the next record to the other waves
-      if (tid < WORK_DWORDS) s_mail[par][tid] = pf.word;
-      if (tid == 0) s_mail[par][WORK_DWORDS] = pf.next + pf.base;
-    }
-    __syncthreads();
-    if (a.remaining && tid == 0) {
-      // the workgroup that retires an operator's last tile stamps it and re-arms the count
-      const uint32_t left = atomicSub(&a.remaining[T.problem], 1u);
-      if (left == 1u) {
-        a.stamps[T.problem] = wall_clock64();
-        a.remaining[T.problem] = (uint32_t)P.tile_count;
-      }
-    }
-    t = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_mail[par][WORK_DWORDS]);
-    W = unpack_uniform<TileWork>(s_mail[par]);
-    par ^= 1;
-    SK_DIAG(5);
-#ifdef SK_DIAG_CLOCKS
-    ++diag_tile;
-#endif
+    got = pf.next;
+    got_base = pf.base;
+    got_word = pf.word;
+    have_done = true;
+    done_problem = T.problem;
+    done_count = (uint32_t)P.tile_count;
   }
 
   // the last workgroup to leave re-arms the queue for the next launch
@@ -2040,6 +2246,8 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sk_superkernel(const TileWork *
     if (done == gridDim.x - 1) {
       a.counters[0] = 0u;
       a.counters[1] = 0u;
+      if (lists)
+        for (uint32_t x = 0; x < 8u; ++x) *die_list_head(a.counters, x) = 0u;
       __threadfence();
     }
   }

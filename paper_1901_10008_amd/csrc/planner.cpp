@@ -106,6 +106,73 @@ static int64_t stream_bytes(int64_t Mg, int64_t Ng, int64_t Kg, int64_t es, cons
   return ((Mg + 127) / 128) * ((Ng + bn - 1) / bn) * (128 + bn) * Kg * es;
 }
 
+// Which accelerator die (XCD: 32 compute units behind one 4 MB L2) runs which LDS tile.  The tiles of an
+// operator in the LDS-tile classes share operands: the tiles of one row block read the same 128 activation
+// rows, those of one column block the same weight rows.  Handed out in table order they land on all eight
+// dies, and every die fetches every panel from memory for itself.  So the output rectangles of such an
+// operator are cut into `p` two-dimensional parts (p = 1, 2, 4 or 8: the fewest with at most xcd_part
+// rectangles each; the pm x pn grid of parts that fetches the fewest operand rows in total), each part goes to
+// one die (the dies with the fewest entries so far, lowest index first), and within a part the rectangles
+// follow a Z-order curve in blocks of 8 x 8, so that the handful of tiles a die runs at any one time share panels as well.
+// The reduction slices of a rectangle stay together.  The lists name tiles of the table; the table itself,
+// and with it the order in which the launch takes LDS tiles up, does not change.
+static void build_xcd_lists(HostPlan &out, const std::vector<Canon> &canon) {
+  out.xorder.clear();
+  std::fill(std::begin(out.xoff), std::end(out.xoff), 0u);
+  const int64_t part = out.params.xcd_part;
+  if (part <= 0) return;
+  std::vector<uint32_t> lists[8];
+  for (const int32_t i : out.order) {
+    if (out.count[i] == 0) continue;
+    const sk_tile &t0 = out.tiles[(size_t)out.first[i]];
+    if (t0.cls != CLS_TILE_128x128 && t0.cls != CLS_TILE_128x64) continue;
+    const int64_t bn = t0.cls == CLS_TILE_128x64 ? 64 : 128;
+    const int64_t MB = (canon[i].Mg + 127) / 128, NB = (canon[i].Ng + bn - 1) / bn, S = t0.S;
+    int64_t p = 1;
+    while (p < 8 && MB * NB > p * part) p *= 2;
+    // pn parts along the columns: every row block is then fetched by pn dies, every column block by pm
+    int64_t pm = 1, pn = 1, best = -1;
+    for (int64_t cn = 1; cn <= p; cn *= 2) {
+      const int64_t cm = p / cn;
+      if (cm > MB || cn > NB) continue;
+      const int64_t rows = cn * MB * 128 + cm * NB * bn;
+      if (best < 0 || rows < best) best = rows, pm = cm, pn = cn;
+    }
+    if (best < 0) {  // more parts than row or column blocks allow (cannot happen for part >= 1; kept for safety)
+      pm = std::min<int64_t>(p, MB);
+      pn = 1;
+    }
+    bool used[8] = {};
+    for (int64_t a = 0; a < pm; ++a) {
+      for (int64_t b = 0; b < pn; ++b) {
+        int die = -1;
+        for (int x = 0; x < 8; ++x)
+          if (!used[x] && (die < 0 || lists[x].size() < lists[die].size())) die = x;
+        used[die] = true;
+        const int64_t m_lo = a * MB / pm, m_hi = (a + 1) * MB / pm, n_lo = b * NB / pn, n_hi = (b + 1) * NB / pn;
+        // blocks of 8 x 8 rectangles row by row, a Z-order curve inside each block
+        for (int64_t bm = m_lo; bm < m_hi; bm += 8) {
+          for (int64_t bnn = n_lo; bnn < n_hi; bnn += 8) {
+            for (int code = 0; code < 64; ++code) {
+              // even bits of the code: column offset, odd bits: row offset
+              const int64_t dn = (code & 1) | ((code >> 1) & 2) | ((code >> 2) & 4);
+              const int64_t dm = ((code >> 1) & 1) | ((code >> 2) & 2) | ((code >> 3) & 4);
+              if (bm + dm >= m_hi || bnn + dn >= n_hi) continue;
+              const int64_t rect = (bm + dm) * NB + (bnn + dn);
+              for (int64_t ks = 0; ks < S; ++ks) lists[die].push_back((uint32_t)(out.first[i] + rect * S + ks));
+            }
+          }
+        }
+      }
+    }
+  }
+  for (int x = 0; x < 8; ++x) {
+    out.xoff[x] = (uint32_t)out.xorder.size();
+    out.xorder.insert(out.xorder.end(), lists[x].begin(), lists[x].end());
+  }
+  out.xoff[8] = (uint32_t)out.xorder.size();
+}
+
 sk_status plan_host(const sk_problem *problems, int32_t n, const sk_plan_params *params, HostPlan &out,
                     std::string &err) {
   if (n < 0 || (n > 0 && !problems)) {
@@ -119,7 +186,7 @@ sk_status plan_host(const sk_problem *problems, int32_t n, const sk_plan_params 
     sk_plan_params_default(&prm);
   if (prm.skinny_max_m < 0 || prm.skinny_max_m > 64 || prm.tile_bytes_min < 1 ||
       prm.tile_bytes_max < prm.tile_bytes_min || prm.balance_div < 1 || prm.max_groups < 1 ||
-      prm.max_groups > 256 || prm.grid_limit < 0 || prm.tail_div < 0) {
+      prm.max_groups > 256 || prm.grid_limit < 0 || prm.tail_div < 0 || prm.xcd_part < 0) {
     err = "sk_plan_params field out of range";
     return SK_ERR_INVALID_ARG;
   }
@@ -335,6 +402,7 @@ sk_status plan_host(const sk_problem *problems, int32_t n, const sk_plan_params 
     out.dev[i].tile_first = (int32_t)out.first[i];
     out.dev[i].tile_count = (int32_t)out.count[i];
   }
+  build_xcd_lists(out, canon);
   return SK_OK;
 }
 
@@ -462,4 +530,6 @@ extern "C" void sk_plan_params_default(sk_plan_params *p) {
   p->max_groups = 256;
   p->grid_limit = 0;
   p->tail_div = 384;
+  p->xcd_part = 0;
+  p->reserved = 0;
 }

@@ -78,6 +78,10 @@ struct HostPlan {
   std::vector<int64_t> first, count;
   std::vector<uint32_t> ws_off;  // per output rectangle: offset of its split-K partials, in 16-byte units
   int64_t ws_f32x4 = 0;          // size of the split-K workspace, in 16-byte units
+  // The LDS tiles of the table once more, as eight lists (one per accelerator die): xorder[xoff[x] .. xoff[x+1])
+  // are the table indices of the tiles die x takes, in the order it takes them.  Empty when xcd_part is 0.
+  std::vector<uint32_t> xorder;
+  uint32_t xoff[9] = {};
   sk_plan_params params;
   int64_t target_tile_bytes = 0;
 };

@@ -206,12 +206,15 @@ StaticScratch &static_scratch() {
 }  // namespace
 
 // The device side of one tile table: one allocation holding
-//   work records (tile + its operator's descriptor) | queue counters | tiles left per operator |
-//   completion stamps | split-K offsets | split-K arrival counters | split-K workspace
+//   work records (tile + its operator's descriptor) | the LDS tiles' records once more, die by die, and the
+//   lists' offsets | queue counters | tiles left per operator | completion stamps | split-K offsets |
+//   split-K arrival counters | split-K workspace
 struct DeviceTables {
   void *blob = nullptr;
   size_t blob_bytes = 0;  // size of the pooled block behind `blob`
   sk::TileWork *work = nullptr;
+  sk::TileWork *xwork = nullptr;  // null: the plan has no per-die lists
+  uint32_t *xoff = nullptr;       // [9]
   uint32_t *counters = nullptr;
   uint32_t *remaining = nullptr;
   uint64_t *stamps = nullptr;
@@ -252,7 +255,7 @@ namespace {
 
 // Where the parts of a table set lie inside its one block of device memory.
 struct TableLayout {
-  size_t off_work, off_cnt, off_rem, off_stamps, off_wsoff, off_arrive;
+  size_t off_work, off_xwork, off_xoff, off_cnt, off_rem, off_stamps, off_wsoff, off_arrive;
   size_t upload;  // bytes the host fills in (everything before the workspace)
   size_t total;   // upload + split-K workspace
 };
@@ -261,8 +264,10 @@ TableLayout layout_of(const sk::HostPlan &hp) {
   const size_t nt = hp.tiles.size(), np = hp.dev.size(), nrect = hp.ws_off.size();
   TableLayout l;
   l.off_work = 0;
-  l.off_cnt = align_up(l.off_work + nt * sizeof(sk::TileWork), 256);
-  l.off_rem = align_up(l.off_cnt + 2 * sizeof(uint32_t), 256);
+  l.off_xwork = align_up(l.off_work + nt * sizeof(sk::TileWork), 256);
+  l.off_xoff = align_up(l.off_xwork + hp.xorder.size() * sizeof(sk::TileWork), 256);
+  l.off_cnt = align_up(l.off_xoff + 9 * sizeof(uint32_t), 256);
+  l.off_rem = align_up(l.off_cnt + sk::QUEUE_COUNTERS * sizeof(uint32_t), 256);
   l.off_stamps = align_up(l.off_rem + np * sizeof(uint32_t), 256);
   l.off_wsoff = align_up(l.off_stamps + (np + 1) * sizeof(uint64_t), 256);
   l.off_arrive = align_up(l.off_wsoff + nrect * sizeof(uint32_t), 256);
@@ -284,6 +289,10 @@ void fill_image(const sk::HostPlan &hp, const TableLayout &l, char *stage) {
     w.prob = hp.dev[w.tile.problem];
     std::memcpy(&stage[l.off_work + i * sizeof(w)], &w, sizeof(w));
   }
+  for (size_t i = 0; i < hp.xorder.size(); ++i)
+    std::memcpy(&stage[l.off_xwork + i * sizeof(sk::TileWork)], &stage[l.off_work + hp.xorder[i] * sizeof(sk::TileWork)],
+                sizeof(sk::TileWork));
+  std::memcpy(&stage[l.off_xoff], hp.xoff, sizeof(hp.xoff));
   for (size_t i = 0; i < np; ++i) {
     const uint32_t c = (uint32_t)hp.count[i];
     std::memcpy(&stage[l.off_rem + i * sizeof(uint32_t)], &c, sizeof(c));
@@ -293,6 +302,8 @@ void fill_image(const sk::HostPlan &hp, const TableLayout &l, char *stage) {
 void bind_tables(DeviceTables &dt, void *base, const TableLayout &l) {
   char *b = (char *)base;
   dt.work = (sk::TileWork *)(b + l.off_work);
+  dt.xwork = l.off_xoff > l.off_xwork ? (sk::TileWork *)(b + l.off_xwork) : nullptr;
+  dt.xoff = (uint32_t *)(b + l.off_xoff);
   dt.counters = (uint32_t *)(b + l.off_cnt);
   dt.remaining = (uint32_t *)(b + l.off_rem);
   dt.stamps = (uint64_t *)(b + l.off_stamps);
@@ -453,9 +464,13 @@ sk_status sk_release_cached_memory(void) {
 }
 
 static sk_status launch_range(sk_plan *plan, const DeviceTables &dt, hipStream_t stream, uint32_t begin, uint32_t end,
-                              int grid, bool dynamic, bool write_start) {
+                              int grid, bool dynamic, bool write_start, bool whole_table = false) {
   if (end <= begin || grid <= 0) return SK_OK;
   sk::KernelArgs a;
+  // the per-die lists cover the LDS tiles of the whole table, and only the queue hands them out
+  const bool lists = whole_table && dynamic && dt.xwork != nullptr;
+  a.xwork = lists ? dt.xwork : nullptr;
+  a.xoff = lists ? dt.xoff : nullptr;
   a.counters = dt.counters;
   a.remaining = plan->host.params.stamps ? dt.remaining : nullptr;
   a.stamps = plan->host.params.stamps ? plan->dev.stamps : nullptr;  // one set of stamps, whichever table ran last
@@ -547,7 +562,7 @@ sk_status sk_launch(sk_plan *plan, void *hip_stream) {
   st = arm_start_stamp(plan, stream);
   if (st != SK_OK) return st;
   st = launch_range(plan, plan->dev, stream, 0u, (uint32_t)plan->host.tiles.size(), plan->grid,
-                    !plan->fixed_assignment, true);
+                    !plan->fixed_assignment, true, true);
   note_launch(plan, stream, capturing);
   return st;
 }
@@ -613,12 +628,22 @@ sk_status sk_launch_static(sk_plan *plan, void *hip_stream) {
   const int64_t ntiles = (int64_t)plan->host.tiles.size();
   plan->grid_cap = limit;
   plan->grid = (int)(ntiles < limit ? ntiles : limit);
-  return launch_range(plan, dt, stream, 0u, (uint32_t)ntiles, plan->grid, !plan->fixed_assignment, false);
+  return launch_range(plan, dt, stream, 0u, (uint32_t)ntiles, plan->grid, !plan->fixed_assignment, false, true);
 }
 
 int64_t sk_plan_num_tiles(const sk_plan *plan) { return plan ? (int64_t)plan->host.tiles.size() : -1; }
 int32_t sk_plan_num_problems(const sk_plan *plan) { return plan ? (int32_t)plan->host.dev.size() : -1; }
 int32_t sk_plan_grid(const sk_plan *plan) { return plan ? plan->grid : -1; }
+
+sk_status sk_plan_get_xcd_lists(const sk_plan *plan, uint32_t *offsets, uint32_t *tiles, int64_t cap) {
+  if (!plan || !offsets) return set_error(SK_ERR_INVALID_ARG, "plan or offsets is null");
+  std::memcpy(offsets, plan->host.xoff, sizeof(plan->host.xoff));
+  if (tiles) {
+    if (cap < (int64_t)plan->host.xorder.size()) return set_error(SK_ERR_INVALID_ARG, "destination too small for the lists");
+    if (!plan->host.xorder.empty()) std::memcpy(tiles, plan->host.xorder.data(), plan->host.xorder.size() * sizeof(uint32_t));
+  }
+  return SK_OK;
+}
 
 sk_status sk_plan_get_tiles(const sk_plan *plan, void *dst, int64_t dst_bytes) {
   if (!plan) return set_error(SK_ERR_INVALID_ARG, "plan is null");

@@ -36,6 +36,7 @@ DEFAULT_GRID: Dict[str, Sequence[int]] = {
     "tail_div": (0, 256, 384, 768),
     "balance_div": (256, 512, 2048),
     "skinny_max_m": (32, 64),   # which operators stream their weights and which take the LDS tiles
+    "xcd_part": (0, 32),        # LDS tiles by table order, or die by die (pays on compute-heavy plans only)
 }
 
 

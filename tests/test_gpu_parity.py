@@ -7,6 +7,7 @@ and the coalesced launch against the one-launch-per-operator baseline wherever
 their tile tables coincide (plans of one operator); with several operators the
 baseline tiles each operator as if it were alone, so its reduction slices can
 differ and both are held to the oracle instead."""
+import dataclasses
 import math
 import os
 
@@ -64,6 +65,17 @@ def run_all_modes(specs, seed=0, label="", **batch_kw):
         _sync()
         for i, (x, y) in enumerate(zip(coalesced, b.all_output_bits())):
             assert np.array_equal(x, y), f"{label}: index-order plan differs on operator {i}"
+    # LDS tiles handed out through the per-die lists: same table, same bits, whoever runs a tile (twice: the
+    # lists' counters re-arm themselves like the queue's)
+    for part in (32, 1):
+        with b.plan(xcd_part=part) as plan:
+            assert sk.sk_plan_get_tiles(plan) == table
+            for rnd in range(2):
+                b.reset_outputs()
+                sk.sk_launch(plan, H.stream_handle())
+                _sync()
+                for i, (x, y) in enumerate(zip(coalesced, b.all_output_bits())):
+                    assert np.array_equal(x, y), f"{label}: xcd_part={part}, launch {rnd}: operator {i} differs"
     return worst
 
 
@@ -196,15 +208,49 @@ def test_random_mixes_under_random_plan_parameters(seed):
            "tile_bytes_max": tmin * int(rng.choice([1, 4, 16])), "balance_div": int(rng.choice([16, 2048])),
            "max_groups": int(rng.choice([4, 8, 256])), "tail_div": int(rng.choice([0, 8, 384])),
            "grid_limit": int(rng.choice([0, 7, 100]))}
+    prm["xcd_part"] = [0, 2, 32, 1][seed % 4]   # seeds 1 to 3: LDS tiles handed out through the per-die lists
     b = H.Batch(specs, seed=seed)
     with b.plan(**prm) as plan:
-        ref = {k: v for k, v in prm.items() if k != "grid_limit"}
+        ref = {k: v for k, v in prm.items() if k not in ("grid_limit", "xcd_part")}
         assert sk.sk_plan_get_tiles(plan) == P.plan(specs, P.Params(**ref))[0]
         for launch in (sk.sk_launch, sk.sk_launch_sequential, sk.sk_launch):
             b.reset_outputs()
             launch(plan, H.stream_handle())
             _sync()
             H.check_against_oracle(b, f"random mix {seed} {prm}")
+
+
+@pytest.mark.parametrize("grid", [3, 9, 40, 0])
+def test_die_lists_under_every_hand_over(grid):
+    """LDS tiles taken from the per-die lists with few workgroups (so that each runs many tiles and every way
+    from one tile to the next occurs: an entry drawn in advance and used, drawn and kept over skinny tiles,
+    drawn on the spot, taken from another die's list, run after the tickets are used up, tickets that stand
+    for nothing), with split reductions and completion stamps: bit for bit what the plain queue gives."""
+    specs = (workloads.config(3, seed=0) + workloads.config(2, seed=2)[:6] + workloads.config(4, seed=0)[:5]
+             + workloads.config(3, seed=1, dtype="f16")[3:6] + [g(200, 300, 72, "f32"), g(130, 129, 1001, "bf16")])
+    # interleave skinny and LDS-tile operators in the execution order
+    specs = [dataclasses.replace(s, deadline_ms=1.0 + (7 * i) % len(specs)) for i, s in enumerate(specs)]
+    b = H.Batch(specs, seed=5)
+    prm = {"grid_limit": grid, "tile_bytes_min": 16384, "tile_bytes_max": 262144}
+    with b.plan(**prm) as plan:
+        sk.sk_launch(plan, H.stream_handle())
+        _sync()
+        H.check_against_oracle(b, f"die lists, grid {grid}: plain queue")
+        want = b.all_output_bits()
+        n_lds = sum(t["cls"] >= P.CLS_TILE_128x128 for t in P.decode(sk.sk_plan_get_tiles(plan)))
+        n_all = sk.sk_plan_num_tiles(plan)
+    assert 0 < n_lds < n_all
+    for part in (1, 4, 32):
+        with b.plan(xcd_part=part, stamps=1, **prm) as plan:
+            assert sum(len(l) for l in sk.sk_plan_get_xcd_lists(plan)) == n_lds
+            for rnd in range(3):
+                b.reset_outputs()
+                sk.sk_launch(plan, H.stream_handle())
+                _sync()
+                for i, (x, y) in enumerate(zip(want, b.all_output_bits())):
+                    assert np.array_equal(x, y), f"grid {grid}, xcd_part {part}, launch {rnd}: operator {i} differs"
+                done, start, rate = sk.sk_plan_get_stamps(plan)
+                assert all(d >= start for d in done), "an operator without a completion stamp"
 
 
 def test_tuner_sweeps_plan_parameters():

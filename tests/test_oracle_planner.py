@@ -297,3 +297,47 @@ def test_targets_count_the_bytes_the_tiles_load():
     sk = [x for x in t if x["problem"] == 1]
     assert len(sk) == 32 * 4 and {(x["n_len"], x["S"], x["k_len"]) for x in sk} == {(128, 4, 1024)}
     assert all(x["S"] == 1 for x in t if x["problem"] == 0)   # 256 * 4096 * 2 = 2 MiB <= 2 * 2 MiB
+
+
+def test_die_lists_hand_worked():
+    """Which die takes which LDS tile, on cases small enough to enumerate by hand."""
+    # 300 x 520 GEMM: MB = 3 row blocks, NB = 5 column blocks of 128 (the last 8 wide), 15 rectangles, one slice
+    # each: table index = 5 * row block + column block.
+    big = NS(op="gemm", dtype="bf16", M=300, N=520, K=256, deadline_ms=math.inf)
+    small = NS(op="gemm", dtype="bf16", M=8, N=64, K=256, deadline_ms=math.inf)       # skinny: in no list
+    ops = [small, big]
+    table, order, first, count = P.plan(ops, P.Params(tile_bytes_min=1 << 20, tile_bytes_max=1 << 20))
+    assert first[1] == count[0] and count[1] == 15
+    f = first[1]
+    # part = 16: one part, one die (die 0: all lists are empty); Z-order inside the 8 x 8 block: (0,0) (0,1) (1,0)
+    # (1,1) (0,2) (0,3) (1,2) (1,3) (2,0) (2,1) then row 3 does not exist, (2,2) (2,3), then columns 4..7 of
+    # rows 0..3: (0,4) (1,4) (2,4)
+    lists = P.die_lists(ops, table, order, first, 16)
+    rc = lambda r, c: f + 5 * r + c
+    assert lists[0] == [rc(0, 0), rc(0, 1), rc(1, 0), rc(1, 1), rc(0, 2), rc(0, 3), rc(1, 2), rc(1, 3),
+                        rc(2, 0), rc(2, 1), rc(2, 2), rc(2, 3), rc(0, 4), rc(1, 4), rc(2, 4)]
+    assert lists[1:] == [[]] * 7
+    # part = 8: 15 > 8 -> two parts.  Grids: 2 x 1 (pm = 2, pn = 1) fetches 1 * 3 * 128 + 2 * 5 * 128 = 1664 rows,
+    # 1 x 2 fetches 2 * 3 * 128 + 1 * 5 * 128 = 1408: the columns are cut, [0, 2) and [2, 5); dies 0 and 1.
+    lists = P.die_lists(ops, table, order, first, 8)
+    assert lists[0] == [rc(0, 0), rc(0, 1), rc(1, 0), rc(1, 1), rc(2, 0), rc(2, 1)]
+    assert lists[1] == [rc(0, 2), rc(0, 3), rc(1, 2), rc(1, 3), rc(0, 4), rc(1, 4), rc(2, 2), rc(2, 3), rc(2, 4)]
+    assert lists[2:] == [[]] * 6
+    # part = 1: eight parts at most.  Grids with pm <= 3, pn <= 5: only 2 x 4 (rows cut in [0,1) [1,3), columns in
+    # [0,1) [1,2) [2,3) [3,5)); parts row-major onto dies 0..7
+    lists = P.die_lists(ops, table, order, first, 1)
+    assert lists == [[rc(0, 0)], [rc(0, 1)], [rc(0, 2)], [rc(0, 3), rc(0, 4)],
+                     [rc(1, 0), rc(2, 0)], [rc(1, 1), rc(2, 1)], [rc(1, 2), rc(2, 2)], [rc(1, 3), rc(1, 4), rc(2, 3), rc(2, 4)]]
+    # a second operator goes to the dies with the shortest lists: after part = 8 above, dies 2 and 3
+    two = [big, big]
+    table, order, first, count = P.plan(two, P.Params(tile_bytes_min=1 << 20, tile_bytes_max=1 << 20))
+    lists = P.die_lists(two, table, order, first, 8)
+    assert [len(l) for l in lists] == [6, 9, 6, 9, 0, 0, 0, 0]
+    assert lists[2][0] == first[1] and lists[3][0] == first[1] + 2
+    # reduction slices of a rectangle stay together; part = 0 switches the lists off
+    deep = NS(op="gemm", dtype="bf16", M=128, N=256, K=8192, deadline_ms=math.inf)
+    table, order, first, count = P.plan([deep], P.Params(tile_bytes_min=4096, tile_bytes_max=4096, balance_div=1))
+    S = P.decode(table)[0]["S"]
+    assert S > 1 and count[0] == 2 * S
+    assert P.die_lists([deep], table, order, first, 32)[0] == list(range(2 * S))
+    assert P.die_lists([deep], table, order, first, 0) == [[]] * 8

@@ -129,12 +129,25 @@ def test_plan_bytes_match_reference_on_random_mixes(seed):
            "tile_bytes_min": tmin, "tile_bytes_max": tmin * int(rng.choice([1, 2, 16, 64])),
            "balance_div": int(rng.choice([1, 7, 64, 2048])), "max_groups": int(rng.choice([1, 3, 4, 64, 256])),
            "tail_div": int(rng.choice([0, 1, 16, 384, 5000]))}
-    with host_plan(specs, **prm) as plan:
+    part = int(rng.choice([0, 1, 3, 32, 1000]))
+    with host_plan(specs, xcd_part=part, **prm) as plan:
         table, order, first, count = P.plan(specs, ref_params(**prm))
         assert sk.sk_plan_get_tiles(plan) == table, prm
         assert sk.sk_plan_get_order(plan) == order
         assert sk.sk_plan_get_ranges(plan) == (first, count)
         P.check_coverage(specs, table)
+        assert sk.sk_plan_get_xcd_lists(plan) == P.die_lists(specs, table, order, first, part), (prm, part)
+
+
+@pytest.mark.parametrize("idx,rep,part", [(3, 16, 32), (5, 1, 32), (8, 2, 32), (9, 1, 32), (9, 1, 7), (4, 16, 1), (7, 3, 0)])
+def test_die_lists_match_reference_on_configs(idx, rep, part):
+    specs = [s for _ in range(rep) for s in workloads.config(idx, seed=0)]
+    with host_plan(specs, xcd_part=part) as plan:
+        table, order, first, count = P.plan(specs)
+        got = sk.sk_plan_get_xcd_lists(plan)
+        assert got == P.die_lists(specs, table, order, first, part)
+        lds = [i for i, t in enumerate(P.decode(table)) if t["cls"] >= P.CLS_TILE_128x128]
+        assert sorted(x for l in got for x in l) == (lds if part else [])
 
 
 def test_permuting_operators_permutes_the_plan_consistently():
@@ -258,4 +271,4 @@ def test_struct_layout_matches_header():
     import ctypes
     from paper_1901_10008_amd import binding
     assert ctypes.sizeof(binding.sk_problem) == 120
-    assert ctypes.sizeof(binding.PlanParams) == 48
+    assert ctypes.sizeof(binding.PlanParams) == 56
