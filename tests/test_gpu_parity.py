@@ -182,7 +182,7 @@ def test_misaligned_and_strided_operands():
     run_all_modes(convs, seed=11, label="misaligned conv", a_off=4, b_off=4, c_off=4)
 
 
-@pytest.mark.parametrize("seed", [int(x) for x in os.environ.get("SK_RANDOM_MIX_SEEDS", "0,1,2,3").split(",")])
+@pytest.mark.parametrize("seed", [int(x) for x in os.environ.get("SK_RANDOM_MIX_SEEDS", "0,1,2,3,4,5,6,7,8,9,10,11").split(",")])
 def test_random_mixes_under_random_plan_parameters(seed):
     """Seeded random operator lists under random plan parameters (small tile targets force split reductions in
     every class, including the LDS tiles; tiny group caps force many passes): outputs against the oracle."""

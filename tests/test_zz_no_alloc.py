@@ -40,6 +40,9 @@ def test_static_launch_matches_the_allocating_one_twice_in_a_row():
     _both_ways(bs, {"tile_bytes_min": 8192, "tile_bytes_max": 8192}, "second call, smaller input")
     _both_ways(bb, {}, "third call, default tiles")
     _both_ways(bs, {"grid_limit": 5}, "fourth call, five workgroups")
+    # LDS tiles handed out through the per-die lists: their records and counters live in the scratch as well
+    _both_ways(bb, {"xcd_part": 4, "tile_bytes_min": 8192, "tile_bytes_max": 65536}, "fifth call, per-die lists")
+    _both_ways(bs, {"xcd_part": 1, "grid_limit": 11}, "sixth call, per-die lists, eleven workgroups")
 
 
 def test_static_launch_refuses_what_it_cannot_hold_or_serve():
