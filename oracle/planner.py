@@ -187,7 +187,8 @@ def die_lists(problems: Sequence, table: bytes, ordr: Sequence[int], first: Sequ
     Operators in execution order.  The MB x NB output rectangles of an LDS-tile operator are cut into
     p = 1, 2, 4 or 8 parts (the fewest with at most `part` rectangles each), as a pm x pn grid with
     pm * pn = p, pm <= MB, pn <= NB that fetches the fewest operand rows in all (every row block is read by pn
-    dies, every column block by pm: pn * MB * 128 + pm * NB * BN; ties go to fewer parts along the columns);
+    dies, every column block by pm: pn * MB * 128 + pm * NB * BN; ties go to fewer parts along the columns; if no
+    such grid exists, min(p, MB) parts along the rows only);
     part (a, b) covers row blocks [a MB / pm, (a+1) MB / pm) and column blocks [b NB / pn, (b+1) NB / pn).
     Parts go, a outer and b inner, to the die with the shortest list so far that this operator has not used yet
     (lowest index on ties).  Inside a part: blocks of 8 x 8 rectangles row by row, a Z-order curve inside

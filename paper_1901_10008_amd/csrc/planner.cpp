@@ -138,7 +138,7 @@ static void build_xcd_lists(HostPlan &out, const std::vector<Canon> &canon) {
       const int64_t rows = cn * MB * 128 + cm * NB * bn;
       if (best < 0 || rows < best) best = rows, pm = cm, pn = cn;
     }
-    if (best < 0) {  // more parts than row or column blocks allow (cannot happen for part >= 1; kept for safety)
+    if (best < 0) {  // no such grid (three column blocks and one row block cut in four, say): cut the rows only
       pm = std::min<int64_t>(p, MB);
       pn = 1;
     }
