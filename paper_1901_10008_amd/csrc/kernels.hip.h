@@ -1499,6 +1499,14 @@ __device__ __forceinline__ void run_tile_dma(const DevProblem &P, const sk_tile 
   const int c_log = (lane & 7) ^ (((wave & 1) << 2) | (lane >> 4));
   uint32_t offA[NA];   // byte offset of this lane's piece of row i at reduction index 0 (tap (0,0), channel 0)
   uint32_t tapsA[NA];  // convolution: bit (r*S + s) set if the row's pixel under tap (r, s) lies in the image
+  // convolution, scalar: pixels per image, first image of the tile, bit rr*S for every filter row rr
+  int g_hw = 0, g_b0 = 0;
+  uint32_t g_rows = 0;
+  if constexpr (GATHER) {
+    g_hw = P.Ho * P.Wo;
+    g_b0 = fast_div(m0, P.div_hw);
+    for (int rr = 0; rr < P.R; ++rr) g_rows |= 1u << (rr * P.S);
+  }
 #pragma unroll
   for (int i = 0; i < NA; ++i) {
     const int m = m0 + 8 * (wave + 4 * i) + lrow;
@@ -1507,15 +1515,23 @@ __device__ __forceinline__ void run_tile_dma(const DevProblem &P, const sk_tile 
       offA[i] = in ? (uint32_t)((m - m0) * (int)P.lda * ES) + (uint32_t)c_log * 16u : NOWHERE;
       tapsA[i] = 0;
     } else {
-      const RowA r = row_of(P, in ? m : m_end - 1);
-      offA[i] = (uint32_t)((r.base - L.originA) * ES) + (uint32_t)c_log * 16u;
-      // filter rows rr with 0 <= hb + rr < H form a range [lo, hi), and so do the filter columns
-      const int hlo = max(0, -r.hb), hhi = min(P.R, P.H - r.hb);
-      const int wlo = max(0, -r.wb), whi = min(P.S, P.W - r.wb);
-      const uint32_t wmk = whi > wlo ? ((1u << whi) - 1u) & ~((1u << wlo) - 1u) : 0u;  // (at most 31 taps)
-      uint32_t taps = 0;
-      for (int rr = 0; rr < P.R; ++rr) taps |= (rr >= hlo && rr < hhi) ? wmk << (rr * P.S) : 0u;
-      tapsA[i] = in ? taps : 0u;
+      // Pixel (b, ho, wo) of the row; its offset from the descriptor's origin (the corner of the padded first
+      // image of the tile) in 32 bits: lean_operands has checked that the tile's images lie within 2^31 bytes.
+      const int mm = in ? m : m_end - 1;
+      const int b = fast_div(mm, P.div_hw);
+      const int rem = mm - b * g_hw;
+      const int ho = fast_div(rem, P.div_wo);
+      const int hs = ho * P.stride, ws = (rem - ho * P.Wo) * P.stride;  // row and column of tap (0,0) in the padded image
+      offA[i] = (uint32_t)((((b - g_b0) * P.H + hs) * P.W + ws) * P.Cin * ES) + (uint32_t)c_log * 16u;
+      // filter rows rr with 0 <= hb + rr < H form a range [lo, hi), and so do the filter columns; the
+      // columns' bits times the bits rr*S of the rows in range is the mask of all taps in the image (no two
+      // products overlap: the columns' bits lie below S; at most 31 taps)
+      const int hb = hs - P.pad_h, wb = ws - P.pad_w;
+      const int hlo = max(0, -hb), hhi = min(P.R, P.H - hb);
+      const int wlo = max(0, -wb), whi = min(P.S, P.W - wb);
+      const uint32_t wmk = whi > wlo ? ((1u << whi) - 1u) & ~((1u << wlo) - 1u) : 0u;
+      const uint32_t rmk = hhi > hlo ? g_rows & ((1u << (hhi * P.S)) - 1u) & ~((1u << (hlo * P.S)) - 1u) : 0u;
+      tapsA[i] = in ? wmk * rmk : 0u;
     }
   }
   uint32_t offB[NBW];
