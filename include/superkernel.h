@@ -201,7 +201,11 @@ sk_status sk_release_cached_memory(void);
  * from the table in order, so operators with earlier deadlines start first:
  * workgroup b starts on tile b and takes further tiles through a single atomic
  * counter; a plan whose tiles are all short (at most 64 KB of operands each)
- * skips the counter and gives workgroup b the tiles b, b + grid, ...
+ * skips the counter and gives workgroup b the tiles b, b + grid, ...  With
+ * params.xcd_part > 0 a position of the table that holds an LDS tile only says
+ * that one LDS tile is due: the workgroup runs the next tile of its die's list
+ * (sk_plan_get_xcd_lists), so operators still start in table order, and every
+ * tile runs exactly once with the same result bits.
  * Asynchronous.  Needs a device-resident plan (SK_ERR_STATE otherwise).
  * A plan has one tile queue and one set of split-reduction counters, which the
  * kernel re-arms itself when it ends: launches of ONE plan must not overlap
