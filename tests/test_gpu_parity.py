@@ -147,6 +147,16 @@ def test_direct_load_tiles():
         sk.sk_launch(plan, H.stream_handle())
         _sync()
         H.check_against_oracle(b, "direct-load tiles, split reductions")
+    # the same tiles in the kernel instantiation for mixed types and operands of any alignment (one operator with
+    # an odd reduction length brings it in): the build with the most registers in use, where the compiler keeps
+    # scalars in spill lanes and fetches them right in front of the direct loads
+    b = H.Batch(DIRECT + [g(7, 33, 77, "f32"), g(70, 40, 1001)], seed=33)
+    for prm in ({}, {"xcd_part": 2, "grid_limit": 37}, {"tile_bytes_min": 16384, "tile_bytes_max": 16384}):
+        with b.plan(**prm) as plan:
+            b.reset_outputs()
+            sk.sk_launch(plan, H.stream_handle())
+            _sync()
+            H.check_against_oracle(b, f"direct-load tiles among operands of any alignment {prm}")
 
 
 def nchw(h, w, cin, cout, r, s, ph, pw, dtype="bf16", nb=1, d=math.inf, st=1):
