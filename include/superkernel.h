@@ -141,8 +141,9 @@ typedef struct {
                           /* parts of at most this many rectangles, one die per part         */
                           /* (sk_plan_get_xcd_lists); 0 = tiles are taken in table order by  */
                           /* whichever workgroup is free.  Default 0: the lists halve the    */
-                          /* memory traffic of compute-heavy plans and gain a few percent    */
-                          /* there (32 is the value measured), and cost mixed plans time     */
+                          /* memory traffic of compute-heavy plans and gain 4 to 10 percent  */
+                          /* there (32, or a value above any operator's tile count where     */
+                          /* there are more operators than dies), and cost mixed plans time  */
   int32_t reserved;       /* 0                                                               */
 } sk_plan_params;
 

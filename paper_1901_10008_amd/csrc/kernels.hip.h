@@ -2048,13 +2048,12 @@ __global__ void sk_arm_start_stamp(uint64_t *slot) { *slot = ~0ull; }
 template <int ONLY_DT, bool ANY_ALIGNMENT>
 __global__ void __launch_bounds__(WG_THREADS, 2) sk_superkernel(const TileWork *__restrict__ work, KernelArgs a) {
   __shared__ __attribute__((aligned(16))) unsigned char lds[LDS_TILE_BYTES];
-  // next record by parity; behind it [0] its ticket, [1] flags (MAIL_*), [2] its index in xwork
+  // next record by parity; behind it [0] its ticket, [1] flags (MAIL_*), [2] its index in xwork, [3] the ticket
+  // that waits while it runs
   __shared__ __attribute__((aligned(16))) uint32_t s_mail[2][WORK_DWORDS + 4];
-  // a record of the die's list that was drawn in advance and has not run yet; behind it its index in xwork
-  __shared__ __attribute__((aligned(16))) uint32_t s_kept[WORK_DWORDS + 4];
   __shared__ uint32_t s_flag;
   const SplitK sp{a.ws, a.ws_off, a.arrive};
-  enum : uint32_t { MAIL_RUN = 1, MAIL_FROM_LIST = 2, MAIL_KEPT = 4 };
+  enum : uint32_t { MAIL_RUN = 1, MAIL_FROM_LIST = 2, MAIL_PENDING = 4, MAIL_OWES = 8 };
 
   // Start of the launch = the earliest first clock of any workgroup (the host has set the slot to all ones).
   if (a.write_start && a.stamps && threadIdx.x == 0)
@@ -2068,10 +2067,16 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sk_superkernel(const TileWork *
   // sharing operand panels meet behind one L2; workgroups go to the dies round robin by block index), and
   // from the other dies' lists once its own is used up.  While an LDS tile runs, the next entry of the
   // list is drawn together with the next ticket (Prefetch), on the guess that the ticket falls on an LDS
-  // tile again; if it does not, the entry is kept for the workgroup's next such ticket, and run at the
-  // latest when the tickets are used up.  Such an entry ran without a ticket, so at the very end of the
-  // launch some tickets find every list empty and stand for nothing.  Every entry is drawn exactly once and
-  // run by the workgroup that drew it, so every tile of the table runs exactly once.
+  // tile again; if it falls on a skinny tile instead, the entry runs first and the ticket's tile right after
+  // it (its record is fetched while the entry runs, no new ticket is taken).  Work that is bound to a
+  // workgroup is thus always its very next tile: an entry held back until the workgroup's next LDS ticket
+  // left dozens of workgroups with a tile still to run when the tickets ran out, and cost mixed plans a
+  // tenth of their time.  Such an entry ran without a ticket: the workgroup owes one, and the next ticket of
+  // its own that falls on an LDS tile stands for nothing (it takes another ticket at once, and draws nothing
+  // in advance while it owes).  Without that the LDS tiles as a whole ran ahead of their tickets by one tile
+  // per wrong guess, and the launch ended on long skinny tiles with nothing short left to fill in.  What is
+  // still owed when the tickets run out shows as tickets that find every list empty.  Every entry is drawn
+  // exactly once and run by the workgroup that drew it, so every tile of the table runs exactly once.
   const uint32_t last = a.tile_end - 1u;
   const bool lists = a.xoff != nullptr;
   const uint32_t die = blockIdx.x & 7u;
@@ -2081,7 +2086,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sk_superkernel(const TileWork *
     xlen = a.xoff[die + 1] - xbeg;
   }
   uint32_t used_up = xlen == 0 ? 1u << die : 0u;  // lists seen empty (wave 0's copy is the one that counts)
-  bool kept = false;                               // s_kept holds a record
+  bool owes = false;                               // an entry of a list has run without a ticket
 
   const int wave0 = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) == 0;
   const int lane0 = (int)(threadIdx.x & 63u);
@@ -2103,7 +2108,7 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sk_superkernel(const TileWork *
     if (wave0) {
       // wave 0 decides what runs next and hands the record to the other waves
       uint32_t idx = (uint32_t)__builtin_amdgcn_readfirstlane((int)got) + got_base;
-      uint32_t word = got_word, flags = 0, xi = 0;
+      uint32_t word = got_word, flags = 0, xi = 0, waits = 0;
       if (!lists) {
         flags = idx <= last ? MAIL_RUN : 0u;
       } else {
@@ -2116,12 +2121,14 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sk_superkernel(const TileWork *
           // the ticket's tile class: sk_tile's dword 1, low half
           const uint32_t cls = (uint32_t)__builtin_amdgcn_readlane((int)word, have_record ? 1 : 63) & 0xffffu;
           if (ticket && cls >= CLS_TILE_128x128) {
-            if (kept) {
-              word = s_kept[wlane];
-              xi = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_kept[WORK_DWORDS]);
-              kept = false;
-              flags = MAIL_RUN | MAIL_FROM_LIST;
-              break;
+            if (owes) {  // this ticket pays for the entry that ran without one
+              owes = false;
+              uint32_t n2 = 0;
+              if (lane0 == 0) n2 = atomicAdd(&a.counters[0], 1u);
+              idx = (uint32_t)__builtin_amdgcn_readfirstlane((int)n2) + a.tile_begin + gridDim.x;
+              word = as_global<uint32_t>(work + (idx <= last ? idx : last))[wlane];
+              have_record = true;
+              continue;
             }
             if (drawn) {
               xi = xbeg + k;
@@ -2158,35 +2165,34 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sk_superkernel(const TileWork *
             continue;
           }
           if (ticket) {  // a skinny tile: the ticket is the tile
-            flags = MAIL_RUN;
-            if (drawn) {  // the entry drawn in advance waits for the next ticket that falls on an LDS tile
-              if (lane0 < WORK_DWORDS) s_kept[lane0] = word;
-              if (lane0 == 0) s_kept[WORK_DWORDS] = xbeg + k;
-              kept = true;
+            if (drawn) {  // the entry drawn in advance runs first; the ticket's tile follows it
+              xi = xbeg + k;
+              waits = idx;
+              owes = true;
+              flags = MAIL_RUN | MAIL_FROM_LIST | MAIL_PENDING;
+            } else {
+              flags = MAIL_RUN;
+              // (a draw that found the list used up has left no record of the ticket)
+              if (!have_record) word = as_global<uint32_t>(work + idx)[wlane];
             }
-            if (!have_record) word = as_global<uint32_t>(work + idx)[wlane];
             break;
           }
           // the tickets are used up: run what is still in hand
           idx = last;
-          if (kept) {
-            word = s_kept[wlane];
-            xi = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_kept[WORK_DWORDS]);
-            kept = false;
-            flags = MAIL_RUN | MAIL_FROM_LIST;
-          } else if (drawn) {
+          if (drawn) {
             xi = xbeg + k;
             flags = MAIL_RUN | MAIL_FROM_LIST;
           }
           break;
         }
-        if (kept) flags |= MAIL_KEPT;
+        if (owes) flags |= MAIL_OWES;
       }
       if (lane0 < WORK_DWORDS) s_mail[par][lane0] = word;
       if (lane0 == 0) {
         s_mail[par][WORK_DWORDS] = idx;
         s_mail[par][WORK_DWORDS + 1] = flags;
         s_mail[par][WORK_DWORDS + 2] = xi;
+        s_mail[par][WORK_DWORDS + 3] = waits;
       }
     }
     __syncthreads();
@@ -2210,7 +2216,9 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sk_superkernel(const TileWork *
     const TileWork W = unpack_uniform<TileWork>(s_mail[par]);
     const TileWork *cur =
         (flags & MAIL_FROM_LIST) ? a.xwork + (uint32_t)__builtin_amdgcn_readfirstlane((int)s_mail[par][WORK_DWORDS + 2]) : work + t;
-    kept = (flags & MAIL_KEPT) != 0;
+    const bool pending = (flags & MAIL_PENDING) != 0;  // a ticket waits: this tile takes no new one
+    owes = (flags & MAIL_OWES) != 0;
+    const uint32_t waits = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_mail[par][WORK_DWORDS + 3]);
     par ^= 1;
 
     // Everything a tile derives from the thread index is derived again for each tile, from a
@@ -2219,10 +2227,11 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sk_superkernel(const TileWork *
     // the loads and stores in flight.
     int tid = threadIdx.x;
     asm volatile("" : "+v"(tid));
-    Prefetch pf{work, a.dynamic ? &a.counters[0] : nullptr, a.dynamic ? a.tile_begin + gridDim.x : 0u, t + gridDim.x,
-                last, tid};
+    const bool queue = a.dynamic && !pending;
+    Prefetch pf{work, queue ? &a.counters[0] : nullptr, queue ? a.tile_begin + gridDim.x : 0u,
+                pending ? waits : t + gridDim.x, last, tid};
     const sk_tile &T = W.tile;
-    drew = lists && T.cls >= CLS_TILE_128x128 && !kept && !((used_up >> die) & 1u);
+    drew = lists && T.cls >= CLS_TILE_128x128 && !pending && !owes && !((used_up >> die) & 1u);
     if (drew) {
       pf.xhead = die_list_head(a.counters, die);
       pf.xrec = a.xwork + xbeg;

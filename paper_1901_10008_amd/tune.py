@@ -36,7 +36,8 @@ DEFAULT_GRID: Dict[str, Sequence[int]] = {
     "tail_div": (0, 256, 384, 768),
     "balance_div": (256, 512, 2048),
     "skinny_max_m": (32, 64),   # which operators stream their weights and which take the LDS tiles
-    "xcd_part": (0, 32),        # LDS tiles by table order, or die by die (pays on compute-heavy plans only)
+    "xcd_part": (0, 32, 1024),  # LDS tiles by table order, or die by die in parts of 32 output tiles, or whole
+                                # operators per die (pays on compute-heavy plans only)
 }
 
 
