@@ -24,11 +24,16 @@ HIPCC_FLAGS = [
 
 
 DIAG_LIB = os.path.join(HERE, "libsuperkernel_diag.so")  # -DSK_DIAG_CLOCKS: per-tile phase stamps (tile_phases.py)
+DIAG_ALL_LIB = os.path.join(HERE, "libsuperkernel_diag_all.so")  # the same with every workgroup of a launch stamped
 
 
-def build_diag(verbose: bool = False) -> str:
+def build_diag(verbose: bool = False, all_workgroups: bool = False) -> str:
     """The library once more with -DSK_DIAG_CLOCKS, as libsuperkernel_diag.so (a measuring aid: every tile
-    of the first workgroups stamps the device clock at its phase boundaries).  Not built by build()."""
+    of the first 16 workgroups stamps the device clock at its phase boundaries), or, with `all_workgroups`, as
+    libsuperkernel_diag_all.so (512 workgroups, their first 24 tiles).  Not built by build()."""
+    if all_workgroups:
+        return build(force=True, verbose=verbose, extra=("-DSK_DIAG_CLOCKS", "-DSK_DIAG_WGS_N=512", "-DSK_DIAG_TILES_N=24"),
+                     lib=DIAG_ALL_LIB, ceilings=False, tag="diag_all")
     return build(force=True, verbose=verbose, extra=("-DSK_DIAG_CLOCKS",), lib=DIAG_LIB, ceilings=False, tag="diag")
 
 

@@ -111,8 +111,16 @@ struct KernelArgs {
 // of the first SK_DIAG_WGS workgroups stamps the 100 MHz device clock at the phase boundaries of its first
 // SK_DIAG_TILES tiles.  Slots per tile: 0 tile taken up, 1 set-up done (before the first operand loads), 2 first
 // main-loop step multiplied, 3 main loop done, 4 outputs stored (and split-reduction hand-over done), 5 next
-// record handed to all waves, 6 = 1 + tile class + 100 * reduction slices.
-constexpr int SK_DIAG_WGS = 16, SK_DIAG_TILES = 64;
+// record handed to all waves, 6 = 1 + tile class + 100 * reduction slices, 7 = the ticket (low half) and the
+// flags it was handed over with.
+// (first 16 workgroups, 64 tiles each; -DSK_DIAG_WGS_N=512 -DSK_DIAG_TILES_N=24 stamps every workgroup of a launch)
+#ifndef SK_DIAG_WGS_N
+#define SK_DIAG_WGS_N 16
+#endif
+#ifndef SK_DIAG_TILES_N
+#define SK_DIAG_TILES_N 64
+#endif
+constexpr int SK_DIAG_WGS = SK_DIAG_WGS_N, SK_DIAG_TILES = SK_DIAG_TILES_N;
 __device__ uint64_t g_diag[SK_DIAG_WGS * SK_DIAG_TILES * 8];
 #define SK_DIAG(slot_)                                                               \
   do {                                                                               \
@@ -2244,6 +2252,8 @@ __global__ void __launch_bounds__(WG_THREADS, 2) sk_superkernel(const TileWork *
 #ifdef SK_DIAG_CLOCKS
     if (blockIdx.x < SK_DIAG_WGS && diag_tile < SK_DIAG_TILES && threadIdx.x == 0)
       g_diag[(blockIdx.x * SK_DIAG_TILES + diag_tile) * 8 + 6] = 1 + T.cls + 100ull * T.S;
+    if (blockIdx.x < SK_DIAG_WGS && diag_tile < SK_DIAG_TILES && threadIdx.x == 0)
+      g_diag[(blockIdx.x * SK_DIAG_TILES + diag_tile) * 8 + 7] = ((uint64_t)flags << 32) | t;  // how it was handed over, and the ticket
 #endif
     const DevProblem &P = W.prob;
     if constexpr (ONLY_DT >= 0) {

@@ -445,9 +445,14 @@ sk_status sk_plan_destroy(sk_plan *plan) {
 
 #ifdef SK_DIAG_CLOCKS
 // Diagnostic build only (not in include/superkernel.h): copies the phase stamps of the current device to `dst`
-// (host memory, at most `bytes`), resp. zeroes them.  Return a hipError_t.
+// (host memory, at most `bytes`), resp. zeroes them (return a hipError_t); the shape of the stamp array.
 int sk_diag_read(void *dst, uint64_t bytes) {
   return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(sk::g_diag), bytes <= sizeof(sk::g_diag) ? bytes : sizeof(sk::g_diag));
+}
+// How many workgroups are stamped, and how many tiles of each.
+void sk_diag_shape(int *workgroups, int *tiles) {
+  *workgroups = sk::SK_DIAG_WGS;
+  *tiles = sk::SK_DIAG_TILES;
 }
 int sk_diag_clear(void) {
   void *p = nullptr;

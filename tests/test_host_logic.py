@@ -81,7 +81,7 @@ def test_tile_phase_table_from_stamps():
     import numpy as np
     from paper_1901_10008_amd import tile_phases as tp
 
-    st = np.zeros((tp.WGS, tp.TILES, 8), dtype=np.int64)
+    st = np.zeros((16, 64, 8), dtype=np.int64)
     # one skinny 16-row tile: taken up at 1000, set-up 100 ticks, first step 300, loop 10000, outputs 50, hand-over 150
     st[0, 0] = [1000, 1100, 1400, 11400, 11450, 11600, 1 + 0 + 100 * 1, 0]
     # two 128x128 slices of a split reduction (3 slices) with different loop times
@@ -95,3 +95,19 @@ def test_tile_phase_table_from_stamps():
     sl = txt[2].split()
     assert txt[2].startswith("LDS tile 128x128, slice") and sl[-7] == "2"
     assert sl[-6:] == ["2.00", "2.00", "30.00", "2.00", "1.00", "37.00"]
+
+
+def test_tile_phase_end_summary_from_stamps():
+    """When the workgroups of a launch finish, from hand-made stamps (100 ticks per microsecond)."""
+    import numpy as np
+    from paper_1901_10008_amd import tile_phases
+    st = np.zeros((3, 4, 8), dtype=np.int64)
+    # workgroup 0: two tiles, ends at tick 21000; workgroup 1: one LDS tile, ends at 30000; workgroup 2: nothing
+    st[0, 0] = [1000, 1100, 1400, 9000, 9100, 9200, 1 + 0 + 100, 0]
+    st[0, 1] = [9200, 9300, 9600, 20000, 20500, 21000, 1 + 6 + 100, 0]
+    st[1, 0] = [2000, 2100, 2400, 29000, 29500, 30000, 1 + 9 + 100, 0]
+    text = tile_phases.end_summary(st)
+    # begin = 1000; ends 200 and 290 us after it; mean 245, idle 45
+    assert "2 workgroups" in text and "290.0 us" in text and "245.0 us" in text and "45.0 us of idle" in text
+    assert "1 LDS tile 280 us, 290" in text and "0 skinny 118 us, 200" in text
+    assert tile_phases.end_summary(np.zeros((2, 2, 8), dtype=np.int64)) == "no tiles stamped"
