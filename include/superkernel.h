@@ -140,10 +140,13 @@ typedef struct {
                           /* rectangles are cut into the fewest 1, 2, 4 or 8 two-dimensional */
                           /* parts of at most this many rectangles, one die per part         */
                           /* (sk_plan_get_xcd_lists); 0 = tiles are taken in table order by  */
-                          /* whichever workgroup is free.  Default 0: the lists halve the    */
-                          /* memory traffic of compute-heavy plans and gain 4 to 10 percent  */
-                          /* there (32, or a value above any operator's tile count where     */
-                          /* there are more operators than dies), and cost mixed plans time  */
+                          /* whichever workgroup is free.  The lists halve the memory        */
+                          /* traffic of compute-heavy plans and gain 0 to 10 percent there,  */
+                          /* and cost plans with skinny tiles time.  Default -1: the planner */
+                          /* decides: lists, with an eighth of the plan's rectangles per     */
+                          /* part, if every operator is in the LDS-tile classes and the sum  */
+                          /* of flops / peak exceeds the sum of operand bytes / bandwidth    */
+                          /* (datasheet ratios, no device query); none otherwise             */
   int32_t reserved;       /* 0                                                               */
 } sk_plan_params;
 
@@ -203,7 +206,7 @@ sk_status sk_release_cached_memory(void);
  * workgroup b starts on tile b and takes further tiles through a single atomic
  * counter; a plan whose tiles are all short (at most 64 KB of operands each)
  * skips the counter and gives workgroup b the tiles b, b + grid, ...  With
- * params.xcd_part > 0 a position of the table that holds an LDS tile only says
+ * per-die lists (params.xcd_part) a position of the table that holds an LDS tile only says
  * that one LDS tile is due: the workgroup runs the next tile of its die's list
  * (sk_plan_get_xcd_lists), so operators still start in table order, and every
  * tile runs exactly once with the same result bits.
@@ -270,7 +273,7 @@ int32_t sk_plan_grid(const sk_plan *plan);
 /* Which die takes which LDS tile (sk_plan_params.xcd_part; Section 1 item (c): the shape of the execution
  * blocks is the runtime's to choose): offsets[9] and, if `tiles` is not null, at most `cap` table indices:
  * tiles[offsets[x] .. offsets[x+1]) are the records die x takes, in order.  offsets[8] is the number of
- * LDS tiles of the plan, 0 with xcd_part = 0.  Host memory, caller-owned. */
+ * LDS tiles of the plan, 0 if the plan has no lists.  Host memory, caller-owned. */
 sk_status sk_plan_get_xcd_lists(const sk_plan *plan, uint32_t *offsets, uint32_t *tiles, int64_t cap);
 
 /*

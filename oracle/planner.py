@@ -181,6 +181,33 @@ def _z_order_8x8():
     return cells
 
 
+def auto_die_part(problems: Sequence, table: bytes, first: Sequence[int]) -> int:
+    """The `part` the planner takes when none is given (xcd_part = -1): 0 (no lists) if the plan has an operator
+    in the skinny classes, or if memory rather than the matrix cores bounds it: sum of flops / peak against sum of
+    operand bytes / bandwidth over the operators, datasheet figures (2500 TFLOP/s for bf16 and fp16, 157.3 for
+    fp32, 8 TB/s), in whole numbers: flops * 2 * (1573 | 25000) against bytes * 983125.  Otherwise an eighth of all
+    output rectangles of the plan, rounded up."""
+    tiles = decode(table)
+    t_flops = t_bytes = rects = 0
+    for i, p in enumerate(problems):
+        t0 = tiles[first[i]]
+        if t0["cls"] not in (CLS_TILE_128x128, CLS_TILE_128x64):
+            return 0
+        mg, ng, kg = canonical(p)
+        bn = 64 if t0["cls"] == CLS_TILE_128x64 else 128
+        rects += -(-mg // 128) * -(-ng // bn)
+        es = ELEM_SIZE[p.dtype]
+        if p.op == "gemm":
+            nbytes = es * (p.M * p.K + p.N * p.K + p.M * p.N)
+        else:
+            nbytes = es * (p.Nb * p.H * p.W * p.Cin + p.Cout * p.R * p.S * p.Cin + mg * p.Cout)
+        t_flops += 2 * mg * ng * kg * 2 * (25000 if p.dtype == "f32" else 1573)
+        t_bytes += nbytes * 983125
+    if rects == 0 or t_flops <= t_bytes:
+        return 0
+    return -(-rects // 8)
+
+
 def die_lists(problems: Sequence, table: bytes, ordr: Sequence[int], first: Sequence[int], part: int):
     """Eight lists of table indices: the LDS tiles of the table, die by die, in the order a die takes them.
 

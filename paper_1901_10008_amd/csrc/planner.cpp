@@ -116,10 +116,35 @@ static int64_t stream_bytes(int64_t Mg, int64_t Ng, int64_t Kg, int64_t es, cons
 // follow a Z-order curve in blocks of 8 x 8, so that the handful of tiles a die runs at any one time share panels as well.
 // The reduction slices of a rectangle stay together.  The lists name tiles of the table; the table itself,
 // and with it the order in which the launch takes LDS tiles up, does not change.
+// xcd_part = -1: the planner decides.  The lists pay where the matrix cores, not memory, bound the launch and no
+// skinny tile is in it (measured: plans of LDS tiles only gain 0 to 10 % when the sum over operators of
+// flops / peak exceeds that of operand bytes / bandwidth, lose 2 to 5 % otherwise, and every plan that mixes in
+// skinny tiles loses).  Peaks as the ratio of the datasheet figures (2500 TFLOP/s for 16-bit types, 157.3 for
+// fp32, 8 TB/s), so that no device property enters: flops * 2 * (1573 | 25000) against bytes * 983125.
+// Then a part is an eighth of all output rectangles of the plan: whole operators per die where there are
+// many, an operator's eighths where there is one.
+static int64_t resolve_xcd_part(const HostPlan &out, const std::vector<Canon> &canon) {
+  if (out.params.xcd_part >= 0) return out.params.xcd_part;
+  unsigned __int128 t_flops = 0, t_bytes = 0;
+  int64_t rects = 0;
+  for (size_t i = 0; i < out.problems.size(); ++i) {
+    if (out.count[i] == 0) continue;
+    const sk_tile &t0 = out.tiles[(size_t)out.first[i]];
+    if (t0.cls != CLS_TILE_128x128 && t0.cls != CLS_TILE_128x64) return 0;  // a skinny operator
+    const int64_t bn = t0.cls == CLS_TILE_128x64 ? 64 : 128;
+    rects += ((canon[i].Mg + 127) / 128) * ((canon[i].Ng + bn - 1) / bn);
+    const unsigned __int128 flops = (unsigned __int128)2 * (uint64_t)canon[i].Mg * (uint64_t)canon[i].Ng * (uint64_t)canon[i].Kg;
+    t_flops += flops * 2u * (out.problems[i].dtype == SK_F32 ? 25000u : 1573u);
+    t_bytes += (unsigned __int128)(uint64_t)operand_bytes(out.problems[i]) * 983125u;
+  }
+  if (rects == 0 || t_flops <= t_bytes) return 0;
+  return (rects + 7) / 8;
+}
+
 static void build_xcd_lists(HostPlan &out, const std::vector<Canon> &canon) {
   out.xorder.clear();
   std::fill(std::begin(out.xoff), std::end(out.xoff), 0u);
-  const int64_t part = out.params.xcd_part;
+  const int64_t part = resolve_xcd_part(out, canon);
   if (part <= 0) return;
   std::vector<uint32_t> lists[8];
   for (const int32_t i : out.order) {
@@ -186,7 +211,7 @@ sk_status plan_host(const sk_problem *problems, int32_t n, const sk_plan_params 
     sk_plan_params_default(&prm);
   if (prm.skinny_max_m < 0 || prm.skinny_max_m > 64 || prm.tile_bytes_min < 1 ||
       prm.tile_bytes_max < prm.tile_bytes_min || prm.balance_div < 1 || prm.max_groups < 1 ||
-      prm.max_groups > 256 || prm.grid_limit < 0 || prm.tail_div < 0 || prm.xcd_part < 0) {
+      prm.max_groups > 256 || prm.grid_limit < 0 || prm.tail_div < 0 || prm.xcd_part < -1) {
     err = "sk_plan_params field out of range";
     return SK_ERR_INVALID_ARG;
   }
@@ -530,6 +555,6 @@ extern "C" void sk_plan_params_default(sk_plan_params *p) {
   p->max_groups = 256;
   p->grid_limit = 0;
   p->tail_div = 384;
-  p->xcd_part = 0;
+  p->xcd_part = -1;
   p->reserved = 0;
 }

@@ -129,14 +129,46 @@ def test_plan_bytes_match_reference_on_random_mixes(seed):
            "tile_bytes_min": tmin, "tile_bytes_max": tmin * int(rng.choice([1, 2, 16, 64])),
            "balance_div": int(rng.choice([1, 7, 64, 2048])), "max_groups": int(rng.choice([1, 3, 4, 64, 256])),
            "tail_div": int(rng.choice([0, 1, 16, 384, 5000]))}
-    part = int(rng.choice([0, 1, 3, 32, 1000]))
+    part = int(rng.choice([-1, 0, 1, 3, 32, 1000]))
     with host_plan(specs, xcd_part=part, **prm) as plan:
         table, order, first, count = P.plan(specs, ref_params(**prm))
         assert sk.sk_plan_get_tiles(plan) == table, prm
         assert sk.sk_plan_get_order(plan) == order
         assert sk.sk_plan_get_ranges(plan) == (first, count)
         P.check_coverage(specs, table)
+        if part < 0:
+            part = P.auto_die_part(specs, table, first)
         assert sk.sk_plan_get_xcd_lists(plan) == P.die_lists(specs, table, order, first, part), (prm, part)
+
+
+def test_die_lists_by_default_only_for_compute_bound_plans_of_lds_tiles():
+    """xcd_part = -1 (the default): lists for the sixteen 2048-cubed GEMMs (512 rectangles per part: two whole
+    operators per die) and the 28x28x128 convolution tenants, none for the memory-bound conv2_2 tenants, for a
+    plan with skinny operators, or for an empty plan; a single large GEMM is cut into eighths."""
+    for idx, want in ((9, [512] * 8), (10, None), (8, [0] * 8), (5, [0] * 8), (3, [0] * 8)):
+        specs = workloads.config(idx, seed=0)
+        with host_plan(specs) as plan:
+            table, order, first, count = P.plan(specs)
+            got = sk.sk_plan_get_xcd_lists(plan)
+            part = P.auto_die_part(specs, table, first)
+            assert got == P.die_lists(specs, table, order, first, part)
+            if want is not None:
+                assert [len(l) for l in got] == want, idx
+            else:
+                assert part > 0 and sum(len(l) for l in got) == len(table) // 32
+    one = [_g(4096, 4096, 4096)]
+    with host_plan(one) as plan:
+        assert [len(l) for l in sk.sk_plan_get_xcd_lists(plan)] == [128] * 8
+    with host_plan([]) as plan:
+        assert sk.sk_plan_get_xcd_lists(plan) == [[]] * 8
+    # 2 * 2048^3 flops * 2 * 1573 against 3 * 2048^2 * 2 bytes * 983125: compute-bound; the same GEMM in fp32
+    # (weight 25000, 4-byte elements) even more so; with 128 rows per operator the bytes win
+    spec = [_g(2048, 2048, 2048)]
+    table, order, first, count = P.plan(spec)
+    assert P.auto_die_part(spec, table, first) == 32
+    thin = [_g(128, 2048, 2048)]
+    table, order, first, count = P.plan(thin)
+    assert 2 * 128 * 2048 * 2048 * 2 * 1573 < (128 * 2048 * 2 + 2048 * 2048) * 2 * 983125 and P.auto_die_part(thin, table, first) == 0
 
 
 @pytest.mark.parametrize("idx,rep,part", [(3, 16, 32), (5, 1, 32), (8, 2, 32), (9, 1, 32), (9, 1, 7), (4, 16, 1), (7, 3, 0)])
